@@ -1,0 +1,82 @@
+"""ctypes front end of cnn_oracle.c (test infrastructure; see that file's header).
+
+calcGradient (Section 2.1): the gradient of the mini-batch loss divided by the
+mini-batch size, for the layer types of Section 4.1.  Everything is float64.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "cnn_oracle.c")
+_LIB = os.path.join(_HERE, "libcnn_oracle.so")
+_lib = None
+
+_TYPES = {"conv": 0, "maxpool": 1, "avgpool": 2, "relu": 3, "fc": 4}
+
+
+def build(force=False):
+    """Compile cnn_oracle.c with gcc (-O2, OpenMP)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(["gcc", "-O2", "-fopenmp", "-shared", "-fPIC", "-o", _LIB, _SRC, "-lm"])
+    return _LIB
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        build()
+        _lib = ctypes.CDLL(_LIB)
+        _lib.cnn_loss_and_gradient.restype = ctypes.c_double
+        _lib.cnn_num_params.restype = ctypes.c_long
+    return _lib
+
+
+def _table(net):
+    rows = []
+    for L in net["layers"]:
+        vals = list(L[1:]) + [0] * (5 - len(L))
+        rows.append([_TYPES[L[0]]] + vals[:4])
+    return np.ascontiguousarray(rows, dtype=np.int32)
+
+
+def _dp(a):
+    return a.ctypes.data_as(ctypes.c_void_p)
+
+
+def num_params(net):
+    t = _table(net)
+    c, h, w = net["input"]
+    return int(lib().cnn_num_params(_dp(t), ctypes.c_int(len(t)), ctypes.c_int(c), ctypes.c_int(h), ctypes.c_int(w)))
+
+
+def loss_and_gradient(net, theta, x, label, want_grad=True):
+    """(loss, grad) of one mini-batch; grad is the mean over the mini-batch (None if not wanted)."""
+    t = _table(net)
+    c, h, w = net["input"]
+    theta = np.ascontiguousarray(theta, dtype=np.float64)
+    x = np.ascontiguousarray(x, dtype=np.float64)
+    label = np.ascontiguousarray(label, dtype=np.int32)
+    n = x.shape[0]
+    assert x.shape == (n, c, h, w) and label.shape == (n,)
+    assert label.min() >= 0 and label.max() < net["classes"]
+    grad = np.empty_like(theta) if want_grad else None
+    loss = lib().cnn_loss_and_gradient(
+        _dp(t), ctypes.c_int(len(t)), ctypes.c_int(c), ctypes.c_int(h), ctypes.c_int(w), ctypes.c_int(n),
+        _dp(theta), ctypes.c_long(theta.size), _dp(x), _dp(label),
+        _dp(grad) if want_grad else ctypes.c_void_p(0))
+    if not np.isfinite(loss) and np.isnan(loss):
+        raise ValueError("parameter vector length does not match the network")
+    return float(loss), grad
+
+
+def make_callback(net):
+    """grad(theta, (x, label)) -> (g, loss) for oracle.protocol.run."""
+    def cb(theta, batch):
+        loss, g = loss_and_gradient(net, theta, batch[0], batch[1])
+        return g, loss
+    return cb

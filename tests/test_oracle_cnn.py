@@ -1,0 +1,201 @@
+"""Pins for oracle.cnn (calcGradient, Section 2.1 / 4.1) that do not rest on the oracle itself:
+finite differences, PyTorch's float64 autograd (library routines), closed forms, brute force,
+and the parameter counts the paper prints (tests/golden/paper_facts.txt)."""
+import os
+
+import numpy as np
+import pytest
+import torch
+import torch.nn.functional as F
+
+import workloads as wl
+from oracle import cnn
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden", "paper_facts.txt")
+
+
+def gold():
+    out = {}
+    for line in open(GOLD):
+        line = line.split("#")[0].strip()
+        if line:
+            k, v = line.split("=")
+            out[k.strip()] = float(v)
+    return out
+
+
+def rand_case(net, mu, seed):
+    rng = np.random.default_rng(seed)
+    P = wl.num_params(net)
+    theta = rng.standard_normal(P) * 0.3
+    x = rng.standard_normal((mu,) + net["input"])
+    y = rng.integers(0, net["classes"], mu).astype(np.int32)
+    return theta, x, y
+
+
+def torch_loss(net, theta, x, y):
+    """Same network from torch's own float64 routines; autograd gives the gradient."""
+    t = torch.tensor(theta, dtype=torch.float64, requires_grad=True)
+    a = torch.tensor(x, dtype=torch.float64)
+    pos = 0
+    for L in net["layers"]:
+        if L[0] == "conv":
+            _, co, k, s, p = L
+            ci = a.shape[1]
+            nw = co * ci * k * k
+            w = t[pos:pos + nw].reshape(co, ci, k, k)
+            b = t[pos + nw:pos + nw + co]
+            pos += nw + co
+            a = F.conv2d(a, w, b, stride=s, padding=p)
+        elif L[0] == "maxpool":
+            a = F.max_pool2d(a, L[1], L[2], ceil_mode=True)
+        elif L[0] == "avgpool":
+            a = F.avg_pool2d(a, L[1], L[2], ceil_mode=True, count_include_pad=False)
+        elif L[0] == "relu":
+            a = F.relu(a)
+        elif L[0] == "fc":
+            a = a.reshape(a.shape[0], -1)
+            nw = L[1] * a.shape[1]
+            w = t[pos:pos + nw].reshape(L[1], a.shape[1])
+            b = t[pos + nw:pos + nw + L[1]]
+            pos += nw + L[1]
+            a = F.linear(a, w, b)
+    assert pos == t.numel()
+    loss = F.cross_entropy(a.reshape(a.shape[0], -1), torch.tensor(y, dtype=torch.long))
+    loss.backward()
+    return loss.item(), t.grad.numpy()
+
+
+NETS = {
+    "max_clipped": wl.tiny_net(3, 9, 7, 5, conv=((4, 3, 1, 1),), pool="maxpool"),
+    "avg_clipped": wl.tiny_net(2, 8, 8, 3, conv=((3, 3, 1, 0),), pool="avgpool"),
+    "stride2_pad": wl.tiny_net(3, 11, 10, 4, conv=((4, 5, 2, 2), (5, 3, 1, 1)), pool="avgpool", fc_hidden=6),
+    "two_conv_max": wl.tiny_net(2, 12, 12, 3, conv=((3, 3, 1, 1), (4, 3, 1, 0)), pool="maxpool", fc_hidden=7),
+    "stride4_nopad": wl.tiny_net(3, 23, 23, 4, conv=((5, 11, 4, 0),), pool="maxpool"),
+}
+
+
+@pytest.mark.parametrize("name", sorted(NETS))
+def test_finite_differences(name):
+    net = NETS[name]
+    theta, x, y = rand_case(net, 2, 1)
+    loss, g = cnn.loss_and_gradient(net, theta, x, y)
+    rng = np.random.default_rng(2)
+    idx = rng.choice(theta.size, size=min(60, theta.size), replace=False)
+    h = 1e-6
+    for k in idx:
+        tp, tm = theta.copy(), theta.copy()
+        tp[k] += h
+        tm[k] -= h
+        lp, _ = cnn.loss_and_gradient(net, tp, x, y, want_grad=False)
+        lm, _ = cnn.loss_and_gradient(net, tm, x, y, want_grad=False)
+        fd = (lp - lm) / (2 * h)
+        assert abs(fd - g[k]) <= 1e-6 * max(1.0, abs(g[k])), (name, k, fd, g[k])
+
+
+@pytest.mark.parametrize("name", sorted(NETS))
+def test_against_torch_autograd_tiny(name):
+    net = NETS[name]
+    theta, x, y = rand_case(net, 3, 5)
+    loss, g = cnn.loss_and_gradient(net, theta, x, y)
+    tl, tg = torch_loss(net, theta, x, y)
+    assert abs(loss - tl) < 1e-12 * max(1, abs(tl))
+    np.testing.assert_allclose(g, tg, rtol=1e-10, atol=1e-13)
+
+
+def test_against_torch_autograd_cifar3():
+    net = wl.CIFAR3
+    rng = np.random.default_rng(7)
+    theta = wl.init_weights(net, 11).astype(np.float64) * 5          # larger weights: non-trivial activations
+    theta += (rng.standard_normal(theta.size) * 0.01)                # non-zero biases too
+    x = wl.images(net, 2, 12)
+    y = wl.labels(net, 2, 13)
+    loss, g = cnn.loss_and_gradient(net, theta, x, y)
+    tl, tg = torch_loss(net, theta, x.astype(np.float64), y)
+    assert abs(loss - tl) < 1e-12
+    np.testing.assert_allclose(g, tg, rtol=1e-9, atol=1e-14)
+
+
+def test_alex8_first_layers_against_torch():
+    # the stride-4 11x11 first layer and the 3x3/2 pools of the large net, on a cropped input
+    net = {"name": "alexhead", "input": (3, 67, 67), "classes": 7,
+           "layers": [("conv", 8, 11, 4, 0), ("relu",), ("maxpool", 3, 2),
+                      ("conv", 6, 5, 1, 2), ("relu",), ("maxpool", 3, 2), ("fc", 7)]}
+    theta, x, y = rand_case(net, 2, 3)
+    theta *= 0.2
+    loss, g = cnn.loss_and_gradient(net, theta, x, y)
+    tl, tg = torch_loss(net, theta, x, y)
+    assert abs(loss - tl) < 1e-12 * max(1, abs(tl))
+    np.testing.assert_allclose(g, tg, rtol=1e-9, atol=1e-13)
+
+
+def test_parameter_counts_match_paper():
+    g = gold()
+    p = cnn.num_params(wl.CIFAR3)
+    assert p == 89578
+    # the paper prints ~90 K parameters and ~350 kB (Section 4.1)
+    assert abs(p - g["cifar_params_approx"]) / g["cifar_params_approx"] < 0.01
+    assert abs(4 * p - g["cifar_bytes_approx"]) / g["cifar_bytes_approx"] < 0.03
+    assert cnn.num_params(wl.ALEX8) == 62378344
+    assert cnn.num_params(wl.CIFAR3) == wl.num_params(wl.CIFAR3)
+    assert cnn.num_params(wl.ALEX8) == wl.num_params(wl.ALEX8)
+
+
+def test_zero_weights_closed_form():
+    # all-zero parameters: logits 0, loss = log(K); only the last bias has a gradient: 1/K - freq(label)
+    net = wl.CIFAR3
+    P = wl.num_params(net)
+    x = wl.images(net, 4, 1)
+    y = np.array([3, 3, 9, 0], np.int32)
+    loss, g = cnn.loss_and_gradient(net, np.zeros(P), x, y)
+    assert abs(loss - np.log(10)) < 1e-14
+    expect = np.full(10, 0.1) - np.bincount(y, minlength=10) / 4
+    np.testing.assert_allclose(g[-10:], expect, atol=1e-15)
+    assert np.all(g[:-10] == 0)
+
+
+def test_single_conv_brute_force():
+    # one conv + fc, conv output checked through the loss of a linear read-out: compare the conv
+    # gradient with scipy's cross-correlation (a library routine)
+    from scipy.signal import correlate2d
+    net = {"name": "c", "input": (1, 6, 5), "classes": 2, "layers": [("conv", 1, 3, 1, 1), ("fc", 2)]}
+    rng = np.random.default_rng(0)
+    theta = rng.standard_normal(wl.num_params(net))
+    x = rng.standard_normal((1, 1, 6, 5))
+    y = np.array([1], np.int32)
+    loss, g = cnn.loss_and_gradient(net, theta, x, y)
+    w = theta[:9].reshape(3, 3)
+    conv = correlate2d(x[0, 0], w, mode="same") + theta[9]
+    fcw = theta[10:10 + 60].reshape(2, 30)
+    z = fcw @ conv.reshape(-1) + theta[70:72]
+    p = np.exp(z - z.max())
+    p /= p.sum()
+    assert abs(loss + np.log(p[1])) < 1e-13
+    dz = p - np.array([0.0, 1.0])
+    dconv = (fcw.T @ dz).reshape(6, 5)
+    dw = correlate2d(np.pad(x[0, 0], 1), dconv, mode="valid")
+    np.testing.assert_allclose(g[:9].reshape(3, 3), dw, rtol=1e-11, atol=1e-14)
+    assert abs(g[9] - dconv.sum()) < 1e-13
+
+
+def test_gradient_is_mean_over_minibatch():
+    # calcGradient divides by the mini-batch size (Section 2.1): batch gradient = mean of per-example ones
+    net = NETS["avg_clipped"]
+    theta, x, y = rand_case(net, 4, 9)
+    _, g = cnn.loss_and_gradient(net, theta, x, y)
+    parts = [cnn.loss_and_gradient(net, theta, x[i:i + 1], y[i:i + 1])[1] for i in range(4)]
+    np.testing.assert_allclose(g, np.mean(parts, axis=0), rtol=1e-12, atol=1e-15)
+
+
+def test_maxpool_first_maximum_wins():
+    # 1x1 conv mixes two channels so that two window positions tie exactly in value while their
+    # inputs differ; the weight gradient then reveals which position received the pooled gradient.
+    net = {"name": "t", "input": (2, 3, 3), "classes": 2,
+           "layers": [("conv", 1, 1, 1, 0), ("maxpool", 3, 2), ("fc", 2)]}
+    x = np.zeros((1, 2, 3, 3))
+    x[0, 0, 0, 0] = 2.0          # position A (first in row-major order): y = 1*2 + 1*0 = 2
+    x[0, 1, 2, 2] = 2.0          # position B (last):                     y = 1*0 + 1*2 = 2
+    theta = np.array([1.0, 1.0, 0.0, 0.7, -0.4, 0.0, 0.0])   # conv w0 w1 b | fc w(2x1) b(2)
+    assert theta.size == wl.num_params(net)
+    _, g = cnn.loss_and_gradient(net, theta, x, np.array([0], np.int32))
+    assert g[0] != 0.0 and g[1] == 0.0
