@@ -1,0 +1,143 @@
+#!/usr/bin/env python3
+"""Benchmark of the staleness-aware n-softsync ASGD hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload server|cifar|alex]
+
+Default workload "server" is BASELINE config 1, the parameter-server microbenchmark: P = 60 M fp32
+parameters, lambda = 54 gradients resident in HBM, momentum 0.9, weight decay 5e-4.  One step consumes every
+learner's gradient once in each of the two protocols the config names:
+    54-softsync: 54 consecutive sumGradients+applyUpdate with c = 1   (20 B per parameter and update)
+     1-softsync:  1 sumGradients+applyUpdate with c = 54              (232 B per parameter)
+The printed value is algorithmic HBM bytes (4 (c + 4) per parameter and update) over wall time of the step.
+Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def cpu_baseline_server(cfg, budget_s=12.0):
+    """The oracle's server update, as it stands, on a slice of the same workload."""
+    import numpy as np
+    from oracle import protocol
+    Ps = 1 << 21
+    lam = cfg["lam"]
+    rng = np.random.default_rng(0)
+    th = rng.standard_normal(Ps) * 0.01
+    v = np.zeros(Ps)
+    G = [rng.standard_normal(Ps) * 1e-3 for _ in range(lam)]
+    taus = cfg["staleness"]()
+    t0 = time.perf_counter()
+    nbytes = 0
+    reps = 0
+    while time.perf_counter() - t0 < budget_s:
+        for l in range(lam):                                   # 54-softsync: c = 1
+            th, v = protocol.server_update(th, v, [G[l]], [int(taus[l])], cfg["alpha0"], cfg["momentum"], cfg["weight_decay"])
+        th, v = protocol.server_update(th, v, G, [int(t) for t in taus], cfg["alpha0"], cfg["momentum"], cfg["weight_decay"])
+        nbytes += Ps * (lam * 20 + 4 * (lam + 4))
+        reps += 1
+    dt = time.perf_counter() - t0
+    return {"value": nbytes / dt / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "sample": "%d steps of the same two protocols on a %d-element slice of the parameter vector "
+                      "(numpy fp64 oracle; bytes counted with the fp32 formula 4(c+4) per parameter)" % (reps, Ps)}
+
+
+def bench_server(args):
+    import numpy as np
+    import torch
+    import workloads as wl
+    from paper_1511_05950_amd import binding
+
+    cfg = wl.config(1)
+    P, lam = cfg["num_params"], cfg["lam"]
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(wl.SEED0 + 1000)
+    theta0 = torch.randn(P, device=dev, generator=gen) * 0.01
+    grads = [torch.randn(P, device=dev, generator=gen) * 1e-3 for _ in range(lam)]
+    taus = cfg["staleness"]()
+    kw = dict(net=None, num_params=P, alpha0=cfg["alpha0"], momentum=cfg["momentum"], weight_decay=cfg["weight_decay"])
+    ctxA = binding.Sasgd(lam, 0, 54, 1, init_weights=theta0, **kw)     # 54-softsync, c = 1
+    ctxB = binding.Sasgd(lam, 0, 1, 1, init_weights=theta0, **kw)      # 1-softsync,  c = 54
+
+    def step():
+        i = ctxA.timestamp()
+        for l in range(lam):
+            ctxA.pushGradientExternal(grads[l], i + l - min(int(taus[l]), i + l))
+            ctxA.sumGradients()
+            ctxA.applyUpdate()
+        j = ctxB.timestamp()
+        for l in range(lam):
+            ctxB.pushGradientExternal(grads[l], j - min(int(taus[l]), j))
+        ctxB.sumGradients()
+        ctxB.applyUpdate()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ctxA.setProfiling(True)
+    ctxB.setProfiling(True)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    msA, nA = ctxA.phaseTime(1)
+    msB, nB = ctxB.phaseTime(1)
+    ctxA.destroy()
+    ctxB.destroy()
+
+    bytes_step = P * (lam * 20 + 4 * (lam + 4))
+    value = bytes_step * args.steps / dt / 1e9
+    kA = msA / nA * 1e-3                      # average duration of one c=1 launch, seconds
+    kB = msB / nB * 1e-3
+    achA = P * 20 / kA / 1e9
+    achB = P * 4 * (lam + 4) / kB / 1e9
+    out = {
+        "metric": "applyUpdate HBM GB/s", "value": round(value, 1), "unit": "GB/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(dt / args.steps * 1e3, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "BASELINE config 1: server update microbench, P=60e6 fp32, lambda=54; one step = "
+                               "54 updates at c=1 (54-softsync) + 1 update at c=54 (1-softsync)",
+                   "num_params": P, "lambda": lam, "momentum": cfg["momentum"], "weight_decay": cfg["weight_decay"]},
+        "roofline": {"bound": "hbm", "kernel": "apply_update_kernel (c=1)", "achieved": round(achA, 1),
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achA / HBM_PEAK_GBS, 4), "traffic": None,
+                     "avg_launch_us": round(kA * 1e6, 2), "bytes_per_launch": P * 20},
+        "roofline_c54": {"bound": "hbm", "kernel": "apply_update_kernel (c=54)", "achieved": round(achB, 1),
+                         "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achB / HBM_PEAK_GBS, 4), "traffic": None,
+                         "avg_launch_us": round(kB * 1e6, 2), "bytes_per_launch": P * 4 * (lam + 4)},
+    }
+    if not args.no_cpu:
+        out["cpu_baseline"] = cpu_baseline_server(cfg)
+    return out
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="server")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg (profiling runs)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only (lambda learners are simulated on it); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+    if args.workload == "server":
+        out = bench_server(args)
+    else:
+        raise SystemExit("unknown workload " + args.workload)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,172 @@
+/*
+ * sasgd.h -- C ABI of the staleness-aware n-softsync ASGD hot path on one MI355X (gfx950).
+ *
+ * The calls carry the names of the protocol steps of the paper's Section 2.1:
+ *   learner:           getMinibatch, pullWeights, calcGradient, pushGradient
+ *   parameter server:  sumGradients, applyUpdate
+ * lambda learners are simulated on one GPU.  The server keeps the weight versions
+ * theta_i, theta_{i-1}, ... in a ring buffer in HBM; a learner that "pulls" binds one of
+ * those versions, so the staleness tau = i - j of Section 2.1 is reproduced exactly.
+ *
+ * Conventions
+ *  - Plain C.  Every call returns 0 (SASGD_OK) or a negative SASGD_E* code; nothing aborts or
+ *    throws.  sasgd_last_error() gives a message for the last failure on a context.
+ *  - "dev" pointers are device (HBM) addresses, "host" pointers are ordinary host memory.
+ *  - All device work is enqueued on the hipStream_t given at creation (passed as void*).
+ *    Calls return without waiting for the device, except the copy* getters, which block.
+ *  - The context owns the weight ring, momentum, per-learner gradient buffers and
+ *    workspaces; all are allocated in sasgd_create and freed in sasgd_destroy; no other
+ *    call allocates device memory.  The caller owns mini-batch buffers and externally
+ *    pushed gradients and keeps them alive until the work that reads them has completed
+ *    on the stream.
+ *  - A context is not thread-safe.
+ *
+ * Flat parameter order (weights, gradients, momentum alike): layers in network order; for
+ * each convolution the weights [Cout][Cin][kh][kw] then the bias [Cout]; for each fully
+ * connected layer the weights [out][in] (in = C,H,W flattened in that order) then the bias.
+ */
+#ifndef SASGD_H
+#define SASGD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct sasgd_ctx sasgd_ctx;
+
+enum {
+  SASGD_OK = 0,
+  SASGD_EINVAL = -1,    /* bad argument or configuration                                   */
+  SASGD_ESTATE = -2,    /* protocol order violated (e.g. calcGradient before pullWeights)   */
+  SASGD_ENOTREADY = -3, /* fewer than c gradients pending                                  */
+  SASGD_ERANGE = -4,    /* weight version not (or no longer) in the ring                   */
+  SASGD_EHIP = -5,      /* a HIP runtime call failed                                       */
+  SASGD_ENOMEM = -6     /* allocation failed                                               */
+};
+
+enum { SASGD_NET_NONE = 0, SASGD_NET_CIFAR3 = 1, SASGD_NET_ALEX8 = 2, SASGD_NET_CUSTOM = 3 };
+enum { SASGD_FP32 = 0, SASGD_BF16 = 1 };
+enum { SASGD_LR_PER_GRADIENT = 0, SASGD_LR_MEAN_STALENESS = 1, SASGD_LR_CONSTANT = 2 };
+enum { SASGD_CONV = 0, SASGD_MAXPOOL = 1, SASGD_AVGPOOL = 2, SASGD_RELU = 3, SASGD_FC = 4 };
+
+/* One layer of a custom network (SASGD_NET_CUSTOM).  The loss, softmax cross-entropy averaged
+ * over the mini-batch, follows the last layer implicitly.
+ *   CONV:    units = output channels, window x window kernel, stride, pad (zero padding)
+ *   MAXPOOL / AVGPOOL: window, stride; output size ceil((H - window)/stride) + 1, windows clipped
+ *            at the border, the average taken over the in-bounds elements
+ *   RELU:    must directly follow a CONV, FC or pooling layer
+ *   FC:      units = outputs                                                              */
+typedef struct {
+  int32_t kind, units, window, stride, pad;
+} sasgd_layer;
+
+typedef struct {
+  int32_t lambda;       /* number of learners (Section 2.1), 1..64                                   */
+  int32_t mu;           /* mini-batch size per learner (Section 2.1); ignored for NET_NONE           */
+  int32_t n;            /* splitting parameter of n-softsync, 1..lambda; c = floor(lambda / n)
+                           gradients enter one update (Section 2.2)                                  */
+  int32_t ring_depth;   /* R >= 1 weight versions kept; a pull of staleness tau needs tau < R        */
+  int32_t net;          /* SASGD_NET_*; NET_NONE = server only (gradients pushed externally)         */
+  int32_t compute;      /* SASGD_FP32, or SASGD_BF16 = bf16 operands, fp32 accumulation; master
+                           weights, momentum and gradients are fp32 either way                       */
+  int32_t lr_mode;      /* PER_GRADIENT: alpha0 / tau_l for each gradient (Section 2.4);
+                           MEAN_STALENESS: alpha0 / mean_l(tau_l); CONSTANT: alpha0.  A staleness
+                           of 0 uses alpha0 unmodulated in every mode.                               */
+  int32_t reserved0;
+  int64_t num_params;   /* NET_NONE: length P of the parameter vector; otherwise 0 or the expected
+                           P, checked against the network                                            */
+  float alpha0;         /* base learning rate                                                        */
+  float momentum;       /* m in  v <- m v + sum_l coef_l g_l + (sum_l coef_l) wd theta               */
+  float weight_decay;   /* wd; theta_{i+1} = theta_i - v                                             */
+  float reserved1;
+  void* stream;         /* hipStream_t; NULL = the default stream                                    */
+  /* NET_CUSTOM only */
+  const sasgd_layer* layers;
+  int32_t num_layers;
+  int32_t in_channels, in_height, in_width;
+  /* optional allocator (e.g. backed by a tensor library); NULL = hipMalloc / hipFree */
+  void* (*alloc)(size_t bytes, void* user);
+  void (*release)(void* ptr, void* user);
+  void* alloc_user;
+} sasgd_config;
+
+/* Create a context.  init_weights: P floats in flat parameter order, host or device memory
+ * (detected); copied into weight version 0.  Momentum starts at 0, the timestamp at 0.
+ * Errors: EINVAL (configuration), ENOMEM, EHIP. */
+int sasgd_create(const sasgd_config* cfg, const float* init_weights, sasgd_ctx** out);
+int sasgd_destroy(sasgd_ctx* ctx);
+
+/* ---- learner side (Section 2.1) ------------------------------------------------------- */
+
+/* getMinibatch: bind the mini-batch learner `learner` will use in its next calcGradient.
+ * images_dev: float32 [mu][C][H][W]; labels_dev: int32 [mu], each in [0, classes).  No copy is
+ * made.  (Random selection from a dataset is the caller's business.) */
+int sasgd_getMinibatch(sasgd_ctx* ctx, int32_t learner, const float* images_dev, const int32_t* labels_dev);
+
+/* pullWeights: bind weight version j = i - min(staleness_request, i), i = current timestamp;
+ * the gradient computed next carries timestamp j (Section 2.1).  staleness_request = 0 is the
+ * paper's "pull the current weights"; a positive request stands in for a learner that pulled
+ * that many updates ago.  Errors: ERANGE if version j has left the ring. */
+int sasgd_pullWeights(sasgd_ctx* ctx, int32_t learner, int32_t staleness_request, int64_t* out_timestamp);
+
+/* calcGradient: forward and backward pass of the network over the bound mini-batches of the
+ * `count` listed learners (each on its own bound weight version), all in one batch of kernel
+ * launches.  Each learner's result is the gradient of the mean loss over its mini-batch, i.e.
+ * already divided by mu (Section 2.1; inner term of the server-view update, Section 3).
+ * out_loss_dev: optional device float[count], the mean loss of each listed learner.
+ * Errors: ESTATE if a listed learner has no mini-batch or weights bound, or still has a
+ * gradient pending at the server; EINVAL for duplicates or NET_NONE. */
+int sasgd_calcGradient(sasgd_ctx* ctx, const int32_t* learners, int32_t count, float* out_loss_dev);
+
+/* pushGradient: hand the learner's gradient and its timestamp j to the server.  The staleness
+ * tau = i - j (i = server timestamp now) is fixed here and returned.  No data moves. */
+int sasgd_pushGradient(sasgd_ctx* ctx, int32_t learner, int32_t* out_staleness);
+
+/* Push a caller-owned device gradient (float32 [P]) with timestamp j <= i (server microbenchmark,
+ * or gradients produced elsewhere). */
+int sasgd_pushGradientExternal(sasgd_ctx* ctx, const float* grad_dev, int64_t timestamp, int32_t* out_staleness);
+
+/* ---- parameter-server side (Section 2.1, 2.2, 2.4) ------------------------------------ */
+
+/* sumGradients: close the accumulation window.  Needs at least c pending gradients, takes the
+ * first c in arrival order and fixes their coefficients coef_l = alpha(tau_l) / c.  The sum itself
+ * is carried out inside applyUpdate's single pass.  out_pending: gradients pending before the call.
+ * Errors: ENOTREADY when fewer than c are pending (nothing changes). */
+int sasgd_sumGradients(sasgd_ctx* ctx, int32_t* out_pending);
+
+/* applyUpdate: theta_{i+1} = theta_i - v with v <- m v + sum_l coef_l g_l + (sum_l coef_l) wd theta_i
+ * (the n-softsync rule of Section 2.2 when m = wd = 0), written to ring slot (i+1) mod R; the
+ * timestamp becomes i+1.  Errors: ESTATE without a closed window; ERANGE if the slot to be
+ * overwritten holds a version some learner has pulled but not yet used. */
+int sasgd_applyUpdate(sasgd_ctx* ctx, int64_t* out_new_timestamp);
+
+/* ---- getters -------------------------------------------------------------------------- */
+int sasgd_timestamp(sasgd_ctx* ctx, int64_t* out);
+int sasgd_numParams(sasgd_ctx* ctx, int64_t* out);
+int sasgd_gradientsPerUpdate(sasgd_ctx* ctx, int32_t* out_c);
+/* Timestamp of the learner's last computed gradient (-1 if none). */
+int sasgd_gradientTimestamp(sasgd_ctx* ctx, int32_t learner, int64_t* out);
+/* Blocking copies to host float[P].  copyWeights: version must be in the ring; with BF16 compute
+ * only the current version is held in fp32, older ones are returned from their bf16 copies. */
+int sasgd_copyWeights(sasgd_ctx* ctx, int64_t version, float* host_out);
+int sasgd_copyGradient(sasgd_ctx* ctx, int32_t learner, float* host_out);
+int sasgd_copyMomentum(sasgd_ctx* ctx, float* host_out);
+/* Device address of a learner's gradient buffer (float32 [P]); valid for the context's lifetime. */
+int sasgd_gradientPtr(sasgd_ctx* ctx, int32_t learner, float** out_dev);
+
+/* Accumulated device time of the two hot phases since the last reset, measured with HIP events
+ * on the context's stream when profiling is on (blocking query).
+ * which: 0 = calcGradient launches, 1 = applyUpdate kernel. */
+int sasgd_setProfiling(sasgd_ctx* ctx, int32_t on);
+int sasgd_phaseTime(sasgd_ctx* ctx, int32_t which, double* out_ms_total, int64_t* out_calls);
+
+const char* sasgd_last_error(sasgd_ctx* ctx);
+const char* sasgd_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SASGD_H */

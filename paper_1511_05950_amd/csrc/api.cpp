@@ -1,0 +1,477 @@
+// C ABI of the staleness-aware n-softsync ASGD hot path: host-side protocol state (timestamps,
+// staleness, the pending-gradient window, the ring of weight versions) and the launches of the
+// device work.  Section references are to the paper (Sections 2.1, 2.2, 2.4, 3).
+#include <stdio.h>
+#include <string.h>
+
+#include <algorithm>
+#include <new>
+
+#include "ctx.hpp"
+
+using namespace sasgd;
+
+namespace {
+
+int fail(sasgd_ctx* ctx, int code, const std::string& msg) {
+  if (ctx) ctx->error = msg;
+  return code;
+}
+
+int fail_hip(sasgd_ctx* ctx, hipError_t e, const char* what) {
+  return fail(ctx, SASGD_EHIP, std::string(what) + ": " + hipGetErrorString(e));
+}
+
+void* ctx_alloc(sasgd_ctx* ctx, size_t bytes) {
+  void* p = nullptr;
+  if (bytes == 0) bytes = 256;
+  if (ctx->cfg.alloc) {
+    p = ctx->cfg.alloc(bytes, ctx->cfg.alloc_user);
+  } else if (hipMalloc(&p, bytes) != hipSuccess) {
+    (void)hipGetLastError();
+    p = nullptr;
+  }
+  if (p) ctx->allocations.push_back(p);
+  return p;
+}
+
+void ctx_free_all(sasgd_ctx* ctx) {
+  for (void* p : ctx->allocations) {
+    if (ctx->cfg.release) ctx->cfg.release(p, ctx->cfg.alloc_user);
+    else if (!ctx->cfg.alloc) (void)hipFree(p);
+  }
+  ctx->allocations.clear();
+}
+
+bool is_device_pointer(const void* p) {
+  hipPointerAttribute_t attr;
+  hipError_t e = hipPointerGetAttributes(&attr, p);
+  if (e != hipSuccess) {
+    (void)hipGetLastError();   // plain host memory is reported as an error: clear it
+    return false;
+  }
+  return attr.type == hipMemoryTypeDevice;
+}
+
+inline int slot_of(const sasgd_ctx* ctx, int64_t version) { return (int)(version % ctx->cfg.ring_depth); }
+
+inline bool version_in_ring(const sasgd_ctx* ctx, int64_t version) {
+  return version >= 0 && version <= ctx->timestamp && ctx->timestamp - version < ctx->cfg.ring_depth;
+}
+
+// Device address of the weights a learner reads for `version`.
+const void* version_ptr(const sasgd_ctx* ctx, int64_t version) {
+  if (ctx->cfg.compute == SASGD_BF16) return ctx->ring_b16 + (size_t)slot_of(ctx, version) * ctx->slot_elems_b16;
+  return ctx->ring_f32 + (size_t)slot_of(ctx, version) * (size_t)ctx->P;
+}
+
+void prof_begin(sasgd_ctx* ctx, int which) {
+  if (!ctx->profiling) return;
+  sasgd_ctx::EvPair ev;
+  ev.which = which;
+  if (hipEventCreate(&ev.a) != hipSuccess || hipEventCreate(&ev.b) != hipSuccess) return;
+  (void)hipEventRecord(ev.a, ctx->stream);
+  ctx->events.push_back(ev);
+}
+void prof_end(sasgd_ctx* ctx) {
+  if (!ctx->profiling || ctx->events.empty()) return;
+  (void)hipEventRecord(ctx->events.back().b, ctx->stream);
+}
+void prof_collect(sasgd_ctx* ctx) {
+  for (auto& ev : ctx->events) {
+    float ms = 0.f;
+    if (hipEventSynchronize(ev.b) == hipSuccess && hipEventElapsedTime(&ms, ev.a, ev.b) == hipSuccess) {
+      ctx->phase_ms[ev.which] += ms;
+      ctx->phase_calls[ev.which] += 1;
+    }
+    (void)hipEventDestroy(ev.a);
+    (void)hipEventDestroy(ev.b);
+  }
+  ctx->events.clear();
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* sasgd_version(void) { return "sasgd-gfx950 0.1"; }
+
+const char* sasgd_last_error(sasgd_ctx* ctx) { return ctx ? ctx->error.c_str() : "null context"; }
+
+int sasgd_create(const sasgd_config* cfg, const float* init_weights, sasgd_ctx** out) {
+  if (!cfg || !out || !init_weights) return SASGD_EINVAL;
+  *out = nullptr;
+  if (cfg->lambda < 1 || cfg->lambda > kMaxLearners) return SASGD_EINVAL;
+  if (cfg->n < 1 || cfg->n > cfg->lambda) return SASGD_EINVAL;
+  if (cfg->ring_depth < 1) return SASGD_EINVAL;
+  if (cfg->compute != SASGD_FP32 && cfg->compute != SASGD_BF16) return SASGD_EINVAL;
+  if (cfg->lr_mode < SASGD_LR_PER_GRADIENT || cfg->lr_mode > SASGD_LR_CONSTANT) return SASGD_EINVAL;
+  if (cfg->net < SASGD_NET_NONE || cfg->net > SASGD_NET_CUSTOM) return SASGD_EINVAL;
+  if (cfg->net != SASGD_NET_NONE && cfg->mu < 1) return SASGD_EINVAL;
+  if (cfg->net == SASGD_NET_NONE && cfg->num_params < 1) return SASGD_EINVAL;
+  if (!(cfg->alpha0 >= 0.f) || !(cfg->momentum >= 0.f) || !(cfg->weight_decay >= 0.f)) return SASGD_EINVAL;
+  if ((cfg->alloc == nullptr) != (cfg->release == nullptr)) return SASGD_EINVAL;
+
+  sasgd_ctx* ctx = new (std::nothrow) sasgd_ctx();
+  if (!ctx) return SASGD_ENOMEM;
+  ctx->cfg = *cfg;
+  ctx->cfg.layers = nullptr;   // the layer table is copied into the net plan; never dereferenced later
+  ctx->c = cfg->lambda / cfg->n;   // c = floor(lambda / n), Section 2.2
+  ctx->stream = (hipStream_t)cfg->stream;
+  ctx->timestamp = 0;
+  if (hipGetDevice(&ctx->device) != hipSuccess) {
+    (void)hipGetLastError();
+    delete ctx;
+    return SASGD_EHIP;
+  }
+
+  int rc = SASGD_OK;
+  size_t pack_elems = 0;
+  do {
+    if (cfg->net == SASGD_NET_NONE) {
+      ctx->P = cfg->num_params;
+    } else {
+      int64_t P = 0;
+      std::string err;
+      rc = net_create(*cfg, &ctx->net, &P, &pack_elems, err);
+      if (rc != SASGD_OK) { ctx->error = err; break; }
+      if (cfg->num_params != 0 && cfg->num_params != P) {
+        rc = fail(ctx, SASGD_EINVAL, "num_params does not match the network"); break;
+      }
+      ctx->P = P;
+    }
+    const size_t P = (size_t)ctx->P;
+    const size_t R = (size_t)cfg->ring_depth;
+    const size_t Ppad = (P + 63) & ~(size_t)63;
+    if (cfg->compute == SASGD_BF16) {
+      ctx->ring_f32 = (float*)ctx_alloc(ctx, P * sizeof(float));
+      ctx->slot_elems_b16 = Ppad + ((pack_elems + 63) & ~(size_t)63);
+      ctx->ring_b16 = (bf16_t*)ctx_alloc(ctx, R * ctx->slot_elems_b16 * sizeof(bf16_t));
+      if (!ctx->ring_b16) { rc = fail(ctx, SASGD_ENOMEM, "weight ring (bf16)"); break; }
+    } else {
+      ctx->ring_f32 = (float*)ctx_alloc(ctx, R * P * sizeof(float));
+    }
+    ctx->v = (float*)ctx_alloc(ctx, P * sizeof(float));
+    if (!ctx->ring_f32 || !ctx->v) { rc = fail(ctx, SASGD_ENOMEM, "weight ring / momentum"); break; }
+
+    hipError_t e = hipMemcpyAsync(ctx->ring_f32, init_weights, P * sizeof(float),
+                                  is_device_pointer(init_weights) ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice,
+                                  ctx->stream);
+    if (e == hipSuccess) e = hipMemsetAsync(ctx->v, 0, P * sizeof(float), ctx->stream);
+    if (e == hipSuccess && cfg->compute == SASGD_BF16) {
+      if (ctx->slot_elems_b16 > P)
+        e = hipMemsetAsync(ctx->ring_b16, 0, R * ctx->slot_elems_b16 * sizeof(bf16_t), ctx->stream);
+      if (e == hipSuccess) e = launch_fp32_to_bf16(ctx->ring_f32, ctx->ring_b16, ctx->P, ctx->stream);
+      if (e == hipSuccess && ctx->net) e = net_prepare_version(ctx->net, ctx->ring_b16, ctx->ring_b16 + Ppad, ctx->stream);
+    }
+    if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);   // init_weights may be freed by the caller
+    if (e != hipSuccess) { rc = fail_hip(ctx, e, "initialising weights"); break; }
+
+    ctx->learners.resize((size_t)cfg->lambda);
+    if (ctx->net) {
+      size_t ws = net_workspace_bytes(ctx->net);
+      for (int l = 0; l < cfg->lambda; l++) {
+        Learner& L = ctx->learners[(size_t)l];
+        L.grad = (float*)ctx_alloc(ctx, P * sizeof(float));
+        L.workspace = ctx_alloc(ctx, ws);
+        if (!L.grad || !L.workspace) { rc = fail(ctx, SASGD_ENOMEM, "learner buffers"); break; }
+        net_set_workspace(ctx->net, l, L.workspace);
+      }
+      if (rc != SASGD_OK) break;
+    }
+  } while (0);
+
+  if (rc != SASGD_OK) {
+    // keep the message reachable: the caller gets no context on failure, so print it
+    fprintf(stderr, "sasgd_create failed: %s\n", ctx->error.c_str());
+    if (ctx->net) net_destroy(ctx->net);
+    ctx_free_all(ctx);
+    delete ctx;
+    return rc;
+  }
+  *out = ctx;
+  return SASGD_OK;
+}
+
+int sasgd_destroy(sasgd_ctx* ctx) {
+  if (!ctx) return SASGD_EINVAL;
+  (void)hipStreamSynchronize(ctx->stream);
+  prof_collect(ctx);
+  if (ctx->net) net_destroy(ctx->net);
+  ctx_free_all(ctx);
+  delete ctx;
+  return SASGD_OK;
+}
+
+int sasgd_getMinibatch(sasgd_ctx* ctx, int32_t learner, const float* images_dev, const int32_t* labels_dev) {
+  if (!ctx) return SASGD_EINVAL;
+  if (!ctx->net) return fail(ctx, SASGD_EINVAL, "getMinibatch: context has no network");
+  if (learner < 0 || learner >= ctx->cfg.lambda || !images_dev || !labels_dev)
+    return fail(ctx, SASGD_EINVAL, "getMinibatch: bad learner or null buffer");
+  if (((uintptr_t)images_dev & 15) || ((uintptr_t)labels_dev & 3))
+    return fail(ctx, SASGD_EINVAL, "getMinibatch: images must be 16-byte aligned");
+  Learner& L = ctx->learners[(size_t)learner];
+  L.images = images_dev;
+  L.labels = labels_dev;
+  return SASGD_OK;
+}
+
+int sasgd_pullWeights(sasgd_ctx* ctx, int32_t learner, int32_t staleness_request, int64_t* out_timestamp) {
+  if (!ctx) return SASGD_EINVAL;
+  if (!ctx->net) return fail(ctx, SASGD_EINVAL, "pullWeights: context has no network");
+  if (learner < 0 || learner >= ctx->cfg.lambda || staleness_request < 0)
+    return fail(ctx, SASGD_EINVAL, "pullWeights: bad learner or negative staleness");
+  // a learner cannot hold weights older than theta_0: clamp, so that j >= 0 (Section 2.1: tau = i - j >= 0)
+  const int64_t tau = std::min<int64_t>(staleness_request, ctx->timestamp);
+  const int64_t j = ctx->timestamp - tau;
+  if (!version_in_ring(ctx, j)) return fail(ctx, SASGD_ERANGE, "pullWeights: version has left the ring");
+  Learner& L = ctx->learners[(size_t)learner];
+  L.has_weights = true;
+  L.pulled_version = j;
+  if (out_timestamp) *out_timestamp = j;
+  return SASGD_OK;
+}
+
+int sasgd_calcGradient(sasgd_ctx* ctx, const int32_t* learners, int32_t count, float* out_loss_dev) {
+  if (!ctx) return SASGD_EINVAL;
+  if (!ctx->net) return fail(ctx, SASGD_EINVAL, "calcGradient: context has no network");
+  if (!learners || count < 1 || count > ctx->cfg.lambda) return fail(ctx, SASGD_EINVAL, "calcGradient: bad learner list");
+  bool seen[kMaxLearners] = {false};
+  LearnerBind binds[kMaxLearners];
+  int ids[kMaxLearners];
+  for (int k = 0; k < count; k++) {
+    const int l = learners[k];
+    if (l < 0 || l >= ctx->cfg.lambda || seen[l]) return fail(ctx, SASGD_EINVAL, "calcGradient: bad or duplicate learner");
+    seen[l] = true;
+    const Learner& L = ctx->learners[(size_t)l];
+    if (!L.images || !L.has_weights) return fail(ctx, SASGD_ESTATE, "calcGradient: learner has no mini-batch or no weights bound");
+    if (L.grad_state == GRAD_PENDING) return fail(ctx, SASGD_ESTATE, "calcGradient: learner's previous gradient is still pending at the server");
+    if (!version_in_ring(ctx, L.pulled_version)) return fail(ctx, SASGD_ERANGE, "calcGradient: pulled version has left the ring");
+    ids[k] = l;
+    binds[k].images = L.images;
+    binds[k].labels = L.labels;
+    binds[k].weights = version_ptr(ctx, L.pulled_version);
+    binds[k].version = L.pulled_version;
+    binds[k].grad = L.grad;
+  }
+  prof_begin(ctx, 0);
+  hipError_t e = net_calc_gradient(ctx->net, ids, binds, count, out_loss_dev, ctx->stream);
+  prof_end(ctx);
+  if (e != hipSuccess) return fail_hip(ctx, e, "calcGradient");
+  for (int k = 0; k < count; k++) {
+    Learner& L = ctx->learners[(size_t)ids[k]];
+    L.grad_timestamp = L.pulled_version;   // gradient timestamp = timestamp of the weights used (Section 2.1)
+    L.grad_state = GRAD_COMPUTED;
+    L.has_weights = false;                 // one mini-batch per push: nothing is accrued at the learner
+    L.images = nullptr;
+    L.labels = nullptr;
+  }
+  return SASGD_OK;
+}
+
+int sasgd_pushGradient(sasgd_ctx* ctx, int32_t learner, int32_t* out_staleness) {
+  if (!ctx) return SASGD_EINVAL;
+  if (learner < 0 || learner >= ctx->cfg.lambda || !ctx->net) return fail(ctx, SASGD_EINVAL, "pushGradient: bad learner");
+  Learner& L = ctx->learners[(size_t)learner];
+  if (L.grad_state != GRAD_COMPUTED) return fail(ctx, SASGD_ESTATE, "pushGradient: no freshly computed gradient");
+  if ((int)ctx->pending.size() >= kMaxLearners) return fail(ctx, SASGD_ESTATE, "pushGradient: pending queue full");
+  Pending p;
+  p.grad = L.grad;
+  p.timestamp = L.grad_timestamp;
+  p.staleness = (int32_t)(ctx->timestamp - L.grad_timestamp);   // tau = i - j
+  p.learner = learner;
+  ctx->pending.push_back(p);
+  L.grad_state = GRAD_PENDING;
+  if (out_staleness) *out_staleness = p.staleness;
+  return SASGD_OK;
+}
+
+int sasgd_pushGradientExternal(sasgd_ctx* ctx, const float* grad_dev, int64_t timestamp, int32_t* out_staleness) {
+  if (!ctx) return SASGD_EINVAL;
+  if (!grad_dev || ((uintptr_t)grad_dev & 15)) return fail(ctx, SASGD_EINVAL, "pushGradientExternal: gradient must be a 16-byte aligned device pointer");
+  if (timestamp < 0 || timestamp > ctx->timestamp) return fail(ctx, SASGD_EINVAL, "pushGradientExternal: timestamp must lie in [0, i]");
+  if ((int)ctx->pending.size() >= kMaxLearners) return fail(ctx, SASGD_ESTATE, "pushGradientExternal: pending queue full");
+  Pending p;
+  p.grad = grad_dev;
+  p.timestamp = timestamp;
+  p.staleness = (int32_t)(ctx->timestamp - timestamp);
+  p.learner = -1;
+  ctx->pending.push_back(p);
+  if (out_staleness) *out_staleness = p.staleness;
+  return SASGD_OK;
+}
+
+int sasgd_sumGradients(sasgd_ctx* ctx, int32_t* out_pending) {
+  if (!ctx) return SASGD_EINVAL;
+  if (out_pending) *out_pending = (int32_t)ctx->pending.size();
+  if (ctx->window_closed) return fail(ctx, SASGD_ESTATE, "sumGradients: window already closed; call applyUpdate");
+  const int c = ctx->c;
+  if ((int)ctx->pending.size() < c) return fail(ctx, SASGD_ENOTREADY, "sumGradients: fewer than c gradients pending");
+  // coef_l = alpha(tau_l) / c with alpha(tau) = alpha0 / tau for tau > 0 (Section 2.4) and alpha0 at tau = 0
+  const float a0 = ctx->cfg.alpha0;
+  if (ctx->cfg.lr_mode == SASGD_LR_MEAN_STALENESS) {
+    int64_t sum = 0;
+    for (int l = 0; l < c; l++) sum += ctx->pending[(size_t)l].staleness;
+    float mean = (float)((double)sum / (double)c);
+    float a = a0 / std::max(mean, 1.0f);
+    for (int l = 0; l < c; l++) ctx->window_coef[l] = a / (float)c;
+  } else {
+    for (int l = 0; l < c; l++) {
+      const int32_t tau = ctx->pending[(size_t)l].staleness;
+      float a = ctx->cfg.lr_mode == SASGD_LR_CONSTANT ? a0 : a0 / (float)std::max(tau, 1);
+      ctx->window_coef[l] = a / (float)c;
+    }
+  }
+  ctx->window_count = c;
+  ctx->window_closed = true;
+  return SASGD_OK;
+}
+
+int sasgd_applyUpdate(sasgd_ctx* ctx, int64_t* out_new_timestamp) {
+  if (!ctx) return SASGD_EINVAL;
+  if (!ctx->window_closed) return fail(ctx, SASGD_ESTATE, "applyUpdate: no closed window; call sumGradients first");
+  const int64_t i = ctx->timestamp;
+  const int R = ctx->cfg.ring_depth;
+  const int64_t evicted = i + 1 - R;   // version whose slot theta_{i+1} takes
+  if (evicted >= 0 && R > 1) {
+    for (const Learner& L : ctx->learners)
+      if (L.has_weights && L.pulled_version == evicted)
+        return fail(ctx, SASGD_ERANGE, "applyUpdate: a learner still holds the version this update would overwrite");
+  }
+  UpdateLaunch u;
+  u.P = ctx->P;
+  u.c = ctx->window_count;
+  float abar = 0.f;
+  for (int l = 0; l < u.c; l++) {
+    u.grads[l] = ctx->pending[(size_t)l].grad;
+    u.coef[l] = ctx->window_coef[l];
+    abar += ctx->window_coef[l];
+  }
+  u.momentum = ctx->cfg.momentum;
+  u.decay = abar * ctx->cfg.weight_decay;
+  u.v = ctx->v;
+  const size_t Ppad = ((size_t)ctx->P + 63) & ~(size_t)63;
+  bf16_t* new_slot_b16 = nullptr;
+  if (ctx->cfg.compute == SASGD_BF16) {
+    u.theta_in = ctx->ring_f32;
+    u.theta_out = ctx->ring_f32;
+    new_slot_b16 = ctx->ring_b16 + (size_t)slot_of(ctx, i + 1) * ctx->slot_elems_b16;
+    u.shadow_out = new_slot_b16;
+  } else {
+    u.theta_in = ctx->ring_f32 + (size_t)slot_of(ctx, i) * (size_t)ctx->P;
+    u.theta_out = ctx->ring_f32 + (size_t)slot_of(ctx, i + 1) * (size_t)ctx->P;
+    u.shadow_out = nullptr;
+  }
+  prof_begin(ctx, 1);
+  hipError_t e = launch_apply_update(u, ctx->stream);
+  prof_end(ctx);
+  if (e == hipSuccess && new_slot_b16 && ctx->net)
+    e = net_prepare_version(ctx->net, new_slot_b16, new_slot_b16 + Ppad, ctx->stream);
+  if (e != hipSuccess) return fail_hip(ctx, e, "applyUpdate");
+  for (int l = 0; l < u.c; l++) {
+    const int lr = ctx->pending[(size_t)l].learner;
+    if (lr >= 0) ctx->learners[(size_t)lr].grad_state = GRAD_NONE;
+  }
+  ctx->pending.erase(ctx->pending.begin(), ctx->pending.begin() + u.c);
+  ctx->window_closed = false;
+  ctx->window_count = 0;
+  ctx->timestamp = i + 1;   // every weight update increments the timestamp by one (Section 2.1)
+  if (out_new_timestamp) *out_new_timestamp = ctx->timestamp;
+  return SASGD_OK;
+}
+
+int sasgd_timestamp(sasgd_ctx* ctx, int64_t* out) {
+  if (!ctx || !out) return SASGD_EINVAL;
+  *out = ctx->timestamp;
+  return SASGD_OK;
+}
+
+int sasgd_numParams(sasgd_ctx* ctx, int64_t* out) {
+  if (!ctx || !out) return SASGD_EINVAL;
+  *out = ctx->P;
+  return SASGD_OK;
+}
+
+int sasgd_gradientsPerUpdate(sasgd_ctx* ctx, int32_t* out_c) {
+  if (!ctx || !out_c) return SASGD_EINVAL;
+  *out_c = ctx->c;
+  return SASGD_OK;
+}
+
+int sasgd_gradientTimestamp(sasgd_ctx* ctx, int32_t learner, int64_t* out) {
+  if (!ctx || !out || learner < 0 || learner >= ctx->cfg.lambda) return SASGD_EINVAL;
+  const Learner& L = ctx->learners[(size_t)learner];
+  *out = L.grad_state == GRAD_NONE ? -1 : L.grad_timestamp;
+  return SASGD_OK;
+}
+
+int sasgd_copyWeights(sasgd_ctx* ctx, int64_t version, float* host_out) {
+  if (!ctx || !host_out) return SASGD_EINVAL;
+  if (!version_in_ring(ctx, version)) return fail(ctx, SASGD_ERANGE, "copyWeights: version not in the ring");
+  const size_t bytes = (size_t)ctx->P * sizeof(float);
+  hipError_t e;
+  if (ctx->cfg.compute == SASGD_BF16 && version != ctx->timestamp) {
+    // only the bf16 copy of an old version exists: fetch it and widen on the host
+    std::vector<bf16_t> tmp((size_t)ctx->P);
+    e = hipMemcpyAsync(tmp.data(), ctx->ring_b16 + (size_t)slot_of(ctx, version) * ctx->slot_elems_b16,
+                       (size_t)ctx->P * sizeof(bf16_t), hipMemcpyDeviceToHost, ctx->stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
+    if (e == hipSuccess)
+      for (size_t k = 0; k < (size_t)ctx->P; k++) {
+        uint32_t u = (uint32_t)tmp[k] << 16;
+        memcpy(&host_out[k], &u, 4);
+      }
+  } else {
+    const float* src = ctx->cfg.compute == SASGD_BF16 ? ctx->ring_f32
+                                                      : ctx->ring_f32 + (size_t)slot_of(ctx, version) * (size_t)ctx->P;
+    e = hipMemcpyAsync(host_out, src, bytes, hipMemcpyDeviceToHost, ctx->stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
+  }
+  if (e != hipSuccess) return fail_hip(ctx, e, "copyWeights");
+  return SASGD_OK;
+}
+
+int sasgd_copyGradient(sasgd_ctx* ctx, int32_t learner, float* host_out) {
+  if (!ctx || !host_out || learner < 0 || learner >= ctx->cfg.lambda) return SASGD_EINVAL;
+  const Learner& L = ctx->learners[(size_t)learner];
+  if (!L.grad) return fail(ctx, SASGD_EINVAL, "copyGradient: context has no network");
+  if (L.grad_timestamp < 0) return fail(ctx, SASGD_ESTATE, "copyGradient: learner has not computed a gradient");
+  hipError_t e = hipMemcpyAsync(host_out, L.grad, (size_t)ctx->P * sizeof(float), hipMemcpyDeviceToHost, ctx->stream);
+  if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
+  if (e != hipSuccess) return fail_hip(ctx, e, "copyGradient");
+  return SASGD_OK;
+}
+
+int sasgd_copyMomentum(sasgd_ctx* ctx, float* host_out) {
+  if (!ctx || !host_out) return SASGD_EINVAL;
+  hipError_t e = hipMemcpyAsync(host_out, ctx->v, (size_t)ctx->P * sizeof(float), hipMemcpyDeviceToHost, ctx->stream);
+  if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
+  if (e != hipSuccess) return fail_hip(ctx, e, "copyMomentum");
+  return SASGD_OK;
+}
+
+int sasgd_gradientPtr(sasgd_ctx* ctx, int32_t learner, float** out_dev) {
+  if (!ctx || !out_dev || learner < 0 || learner >= ctx->cfg.lambda) return SASGD_EINVAL;
+  if (!ctx->learners[(size_t)learner].grad) return fail(ctx, SASGD_EINVAL, "gradientPtr: context has no network");
+  *out_dev = ctx->learners[(size_t)learner].grad;
+  return SASGD_OK;
+}
+
+int sasgd_setProfiling(sasgd_ctx* ctx, int32_t on) {
+  if (!ctx) return SASGD_EINVAL;
+  prof_collect(ctx);
+  ctx->profiling = on != 0;
+  ctx->phase_ms[0] = ctx->phase_ms[1] = 0.0;
+  ctx->phase_calls[0] = ctx->phase_calls[1] = 0;
+  return SASGD_OK;
+}
+
+int sasgd_phaseTime(sasgd_ctx* ctx, int32_t which, double* out_ms_total, int64_t* out_calls) {
+  if (!ctx || which < 0 || which > 1) return SASGD_EINVAL;
+  prof_collect(ctx);
+  if (out_ms_total) *out_ms_total = ctx->phase_ms[which];
+  if (out_calls) *out_calls = ctx->phase_calls[which];
+  return SASGD_OK;
+}
+
+}  // extern "C"

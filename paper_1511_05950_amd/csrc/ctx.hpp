@@ -1,0 +1,102 @@
+// Internal state of a sasgd context (host side).  Not part of the C ABI.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <string>
+#include <vector>
+
+#include "../../include/sasgd.h"
+
+namespace sasgd {
+
+constexpr int kMaxLearners = 64;   // also the largest c one applyUpdate launch reduces
+
+typedef uint16_t bf16_t;           // raw bf16 bits in HBM
+
+// ---------------------------------------------------------------- fused server update (update.hip)
+struct UpdateLaunch {
+  const float* theta_in;   // theta_i  [P]
+  float* theta_out;        // theta_{i+1} [P] (may alias theta_in)
+  float* v;                // momentum [P], updated in place
+  bf16_t* shadow_out;      // optional bf16 copy of theta_{i+1} [P], or nullptr
+  int64_t P;
+  int32_t c;
+  const float* grads[kMaxLearners];
+  float coef[kMaxLearners];
+  float momentum;
+  float decay;             // (sum_l coef_l) * weight_decay
+};
+hipError_t launch_apply_update(const UpdateLaunch& u, hipStream_t stream);
+hipError_t launch_fp32_to_bf16(const float* src, bf16_t* dst, int64_t n, hipStream_t stream);
+hipError_t launch_bf16_to_fp32(const bf16_t* src, float* dst, int64_t n, hipStream_t stream);
+
+// ---------------------------------------------------------------- network (net.cpp)
+struct Net;   // layer plan + per-learner workspaces
+struct LearnerBind {
+  const float* images;     // [mu][C][H][W] fp32, caller-owned
+  const int32_t* labels;   // [mu]
+  const void* weights;     // bound weight version (fp32 or bf16 flat vector, plus packed copies)
+  int64_t version;
+  float* grad;             // [P] fp32 output
+};
+int net_create(const sasgd_config& cfg, Net** out, int64_t* out_P, size_t* out_pack_elems, std::string& err);
+void net_destroy(Net* net);
+// Device memory the net needs per learner, in bytes (activations, gradient activations, argmax).
+size_t net_workspace_bytes(const Net* net);
+void net_set_workspace(Net* net, int learner, void* ws);
+// Per weight version: derive the kernel-friendly copies (bf16 repacked conv filters) from the flat vector.
+hipError_t net_prepare_version(Net* net, const void* flat, void* packed, hipStream_t stream);
+hipError_t net_calc_gradient(Net* net, const int* learners, const LearnerBind* binds, int count,
+                             float* out_loss_dev, hipStream_t stream);
+
+// ---------------------------------------------------------------- context
+enum GradState { GRAD_NONE = 0, GRAD_COMPUTED = 1, GRAD_PENDING = 2 };
+
+struct Learner {
+  const float* images = nullptr;
+  const int32_t* labels = nullptr;
+  bool has_weights = false;
+  int64_t pulled_version = -1;
+  int64_t grad_timestamp = -1;
+  GradState grad_state = GRAD_NONE;
+  float* grad = nullptr;       // [P] fp32 (nullptr for NET_NONE)
+  void* workspace = nullptr;
+};
+
+struct Pending {
+  const float* grad;
+  int64_t timestamp;   // j
+  int32_t staleness;   // tau = i - j at push time
+  int32_t learner;     // -1 for external gradients
+};
+
+}  // namespace sasgd
+
+struct sasgd_ctx {
+  sasgd_config cfg;
+  int32_t c = 1;
+  int64_t P = 0;
+  int64_t timestamp = 0;             // i
+  hipStream_t stream = nullptr;
+  int device = 0;
+  // weight versions
+  float* ring_f32 = nullptr;         // FP32 compute: [R][P]; BF16 compute: [1][P] master
+  sasgd::bf16_t* ring_b16 = nullptr; // BF16 compute: [R][P + pack] shadow copies
+  size_t slot_elems_b16 = 0;         // elements per bf16 slot (P rounded up + packed filters)
+  float* v = nullptr;                // momentum [P]
+  std::vector<sasgd::Learner> learners;
+  std::vector<sasgd::Pending> pending;
+  bool window_closed = false;
+  int32_t window_count = 0;
+  float window_coef[sasgd::kMaxLearners];
+  sasgd::Net* net = nullptr;
+  std::vector<void*> allocations;
+  std::string error;
+  // profiling
+  bool profiling = false;
+  struct EvPair { hipEvent_t a, b; int which; };
+  std::vector<EvPair> events;
+  double phase_ms[2] = {0, 0};
+  int64_t phase_calls[2] = {0, 0};
+};

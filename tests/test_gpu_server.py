@@ -1,0 +1,172 @@
+"""GPU parity of sumGradients + applyUpdate (fused kernel) against oracle.protocol, through the C ABI.
+
+Tolerance: the kernel accumulates in fp32 (an FMA chain of c terms, then three more operations), the
+oracle in fp64.  Per update the relative rounding error of an element is below (c + 4) * 2^-24 of the
+largest intermediate; over K updates it grows at most linearly.  The bound asked for is 1e-3 relative
+on the weights after K updates (fp32); the test holds the much tighter 1e-5 over the vector norm.
+"""
+import numpy as np
+import pytest
+
+import workloads as wl
+from oracle import protocol
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+
+def relerr(a, b):
+    a = np.asarray(a, np.float64)
+    b = np.asarray(b, np.float64)
+    return np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-300)
+
+
+def run_server_case(P, lam, n, K, alpha0, m, wd, lr_mode, seed, compute="fp32", max_tau=None):
+    from paper_1511_05950_amd import binding
+    rng = np.random.default_rng(seed)
+    c = lam // n
+    max_tau = 2 * lam if max_tau is None else max_tau
+    theta0 = (rng.standard_normal(P) * 0.01).astype(np.float32)
+    G = (rng.standard_normal((lam, P)) * 1e-3).astype(np.float32)
+    sched = rng.integers(0, max_tau + 1, size=(K, c))
+    Gd = [torch.from_numpy(G[l]).cuda() for l in range(lam)]     # separate allocations: 16-byte aligned
+    ctx = binding.Sasgd(lam, 0, n, 1, net=None, compute=compute, lr_mode=lr_mode, num_params=P, alpha0=alpha0,
+                        momentum=m, weight_decay=wd, init_weights=theta0)
+    th = theta0.astype(np.float64)
+    v = np.zeros(P)
+    for i in range(K):
+        taus = []
+        for l in range(c):
+            g = (i * c + l) % lam
+            tau = int(min(sched[i][l], i))
+            got = ctx.pushGradientExternal(Gd[g], i - tau)
+            assert got == tau                               # staleness bookkeeping is exact
+            taus.append(tau)
+            if l < c - 1:
+                with pytest.raises(binding.SasgdError) as ei:
+                    ctx.sumGradients()
+                assert ei.value.code == binding.ENOTREADY
+        assert ctx.sumGradients() == c
+        assert ctx.applyUpdate() == i + 1
+        th, v = protocol.server_update(th, v, [G[(i * c + l) % lam] for l in range(c)], taus, alpha0, m, wd, lr_mode)
+    assert ctx.timestamp() == K
+    w = ctx.copyWeights()
+    mom = ctx.copyMomentum()
+    ctx.destroy()
+    return w, mom, th, v
+
+
+@pytest.mark.parametrize("P", [1, 3, 4, 1023, 65536 + 5, 1_000_003])
+def test_update_sizes_and_ragged_tails(P):
+    w, mom, th, v = run_server_case(P, lam=6, n=2, K=7, alpha0=0.01, m=0.9, wd=5e-4, lr_mode="per_gradient", seed=P)
+    assert relerr(w, th) < 1e-5 and relerr(mom, v) < 1e-5
+    np.testing.assert_allclose(w, th, rtol=0, atol=1e-6 * np.abs(th).max())
+
+
+@pytest.mark.parametrize("lam,n", [(54, 54), (54, 1), (30, 15), (18, 18), (18, 1), (7, 2), (64, 1)])
+def test_update_softsync_shapes(lam, n):
+    w, mom, th, v = run_server_case(200_003, lam, n, K=5 if n == 1 else 60, alpha0=0.01, m=0.9, wd=5e-4,
+                                    lr_mode="per_gradient", seed=lam * 100 + n)
+    assert relerr(w, th) < 1e-5 and relerr(mom, v) < 1e-5
+
+
+@pytest.mark.parametrize("mode", ["per_gradient", "mean_staleness", "constant"])
+def test_update_lr_modes(mode):
+    w, mom, th, v = run_server_case(50_001, 8, 2, K=20, alpha0=0.05, m=0.5, wd=1e-3, lr_mode=mode, seed=5, max_tau=6)
+    assert relerr(w, th) < 1e-5 and relerr(mom, v) < 1e-5
+
+
+def test_update_without_momentum_is_the_softsync_rule():
+    w, mom, th, v = run_server_case(10_007, 4, 1, K=6, alpha0=0.1, m=0.0, wd=0.0, lr_mode="per_gradient", seed=9, max_tau=3)
+    assert relerr(w, th) < 1e-6
+
+
+def test_update_bf16_shadow_matches_master():
+    from paper_1511_05950_amd import binding
+    P = 70_001
+    rng = np.random.default_rng(0)
+    theta0 = (rng.standard_normal(P) * 0.01).astype(np.float32)
+    g = torch.from_numpy((rng.standard_normal(P) * 1e-3).astype(np.float32)).cuda()
+    ctx = binding.Sasgd(2, 0, 2, 3, net=None, compute="bf16", num_params=P, alpha0=0.1, momentum=0.9, init_weights=theta0)
+    for i in range(3):
+        ctx.pushGradientExternal(g, i)
+        ctx.sumGradients()
+        ctx.applyUpdate()
+    cur = ctx.copyWeights(3)            # fp32 master
+    old = ctx.copyWeights(2)            # bf16 copy of the previous version
+    prev_exact = cur + ctx.copyMomentum()   # theta_2 = theta_3 + v_3
+    ctx.destroy()
+    # bf16 has 8 significant bits: relative rounding error at most 2^-9 per element
+    np.testing.assert_allclose(old, prev_exact, rtol=2.0 ** -8, atol=1e-12)
+    assert np.all((old.view(np.uint32) & 0xFFFF) == 0)
+
+
+def test_protocol_errors():
+    from paper_1511_05950_amd import binding
+    P = 1000
+    g = torch.zeros(P, device="cuda")
+    ctx = binding.Sasgd(4, 0, 2, 1, net=None, num_params=P, init_weights=np.zeros(P, np.float32))
+    with pytest.raises(binding.SasgdError) as e:
+        ctx.applyUpdate()
+    assert e.value.code == binding.ESTATE
+    with pytest.raises(binding.SasgdError) as e:
+        ctx.pushGradientExternal(g, 1)                 # timestamp in the future
+    assert e.value.code == binding.EINVAL
+    with pytest.raises(binding.SasgdError) as e:
+        ctx.getMinibatch(0, g, g)                      # server-only context
+    assert e.value.code == binding.EINVAL
+    ctx.pushGradientExternal(g, 0)
+    with pytest.raises(binding.SasgdError) as e:
+        ctx.sumGradients()
+    assert e.value.code == binding.ENOTREADY
+    ctx.pushGradientExternal(g, 0)
+    ctx.pushGradientExternal(g, 0)                     # a third gradient waits for the next window
+    assert ctx.sumGradients() == 3
+    with pytest.raises(binding.SasgdError) as e:
+        ctx.sumGradients()
+    assert e.value.code == binding.ESTATE
+    assert ctx.applyUpdate() == 1
+    with pytest.raises(binding.SasgdError) as e:
+        ctx.sumGradients()
+    assert e.value.code == binding.ENOTREADY
+    ctx.destroy()
+
+
+def test_config1_full_size_sampled():
+    """BASELINE config 1 at full size (P = 60 M, lambda = 54), in the launch configuration bench.py times.
+    The update is element-wise, so the oracle is evaluated on a sample of the elements (both ends of the
+    vector plus random positions)."""
+    from paper_1511_05950_amd import binding
+    cfg = wl.config(1)
+    P, lam = cfg["num_params"], cfg["lam"]
+    rng = np.random.default_rng(1)
+    idx = np.unique(np.concatenate([np.arange(4096), np.arange(P - 4096, P), rng.integers(0, P, 200_000)]))
+    theta0 = wl.config1_theta(P)
+    taus = cfg["staleness"]()
+    nG = 6                                              # distinct gradient buffers (1.44 GB); reused round-robin
+    Gs, Gd = [], []
+    for l in range(nG):
+        g = wl.config1_gradient(l, P)
+        Gs.append(g[idx].astype(np.float64))
+        Gd.append(torch.from_numpy(g).cuda())
+        del g
+    for n in (54, 1):
+        c = lam // n
+        K = 54 if n == 54 else 3
+        ctx = binding.Sasgd(lam, 0, n, 1, net=None, num_params=P, alpha0=cfg["alpha0"], momentum=cfg["momentum"],
+                            weight_decay=cfg["weight_decay"], init_weights=theta0)
+        th, v = theta0[idx].astype(np.float64), np.zeros(idx.size)
+        for i in range(K):
+            tl = []
+            for l in range(c):
+                tau = int(min(taus[(i * c + l) % lam], i))
+                assert ctx.pushGradientExternal(Gd[(i * c + l) % nG], i - tau) == tau
+                tl.append(tau)
+            ctx.sumGradients()
+            ctx.applyUpdate()
+            th, v = protocol.server_update(th, v, [Gs[(i * c + l) % nG] for l in range(c)], tl, cfg["alpha0"],
+                                           cfg["momentum"], cfg["weight_decay"])
+        w = ctx.copyWeights()[idx]
+        mom = ctx.copyMomentum()[idx]
+        ctx.destroy()
+        assert relerr(w, th) < 1e-5 and relerr(mom, v) < 1e-5, (n, relerr(w, th), relerr(mom, v))
