@@ -33,6 +33,8 @@ def lib():
         _lib = ctypes.CDLL(_LIB)
         _lib.cnn_loss_and_gradient.restype = ctypes.c_double
         _lib.cnn_num_params.restype = ctypes.c_long
+        _lib.round_to_bf16.restype = ctypes.c_double
+        _lib.round_to_bf16.argtypes = [ctypes.c_double]
     return _lib
 
 
@@ -54,8 +56,16 @@ def num_params(net):
     return int(lib().cnn_num_params(_dp(t), ctypes.c_int(len(t)), ctypes.c_int(c), ctypes.c_int(h), ctypes.c_int(w)))
 
 
-def loss_and_gradient(net, theta, x, label, want_grad=True):
-    """(loss, grad) of one mini-batch; grad is the mean over the mini-batch (None if not wanted)."""
+def round_to_bf16(v):
+    """Nearest bfloat16 (ties to even) of a float."""
+    return float(lib().round_to_bf16(float(v)))
+
+
+def loss_and_gradient(net, theta, x, label, want_grad=True, round_bf16=False):
+    """(loss, grad) of one mini-batch; grad is the mean over the mini-batch (None if not wanted).
+
+    round_bf16: reduced-precision mode, tensors held between layers are rounded to bfloat16
+    (see cnn_oracle.c)."""
     t = _table(net)
     c, h, w = net["input"]
     theta = np.ascontiguousarray(theta, dtype=np.float64)
@@ -68,15 +78,15 @@ def loss_and_gradient(net, theta, x, label, want_grad=True):
     loss = lib().cnn_loss_and_gradient(
         _dp(t), ctypes.c_int(len(t)), ctypes.c_int(c), ctypes.c_int(h), ctypes.c_int(w), ctypes.c_int(n),
         _dp(theta), ctypes.c_long(theta.size), _dp(x), _dp(label),
-        _dp(grad) if want_grad else ctypes.c_void_p(0))
+        _dp(grad) if want_grad else ctypes.c_void_p(0), ctypes.c_int(1 if round_bf16 else 0))
     if not np.isfinite(loss) and np.isnan(loss):
         raise ValueError("parameter vector length does not match the network")
     return float(loss), grad
 
 
-def make_callback(net):
+def make_callback(net, round_bf16=False):
     """grad(theta, (x, label)) -> (g, loss) for oracle.protocol.run."""
     def cb(theta, batch):
-        loss, g = loss_and_gradient(net, theta, batch[0], batch[1])
+        loss, g = loss_and_gradient(net, theta, batch[0], batch[1], round_bf16=round_bf16)
         return g, loss
     return cb

@@ -24,6 +24,15 @@
  *    the average pool divides by the number of in-bounds elements;
  *  - max-pool ties go to the first element in row-major window order; ReLU'(0) = 0;
  *  - loss = mean over the mini-batch of -log softmax(z)[label].
+ *
+ * Reduced-precision mode (round_bf16 != 0).  "bf16 compute" means that every tensor kept in
+ * memory between layers is a bfloat16 number (8 significant bits, round to nearest even) while
+ * sums are carried in higher precision.  In this mode the oracle rounds, and only rounds: the
+ * images, the parameters, the output of every layer except the final class scores, the gradient
+ * of the loss with respect to the class scores, and every activation gradient handed from one
+ * layer to the previous one.  All sums stay in double precision and the parameter gradient is
+ * not rounded.  ReLU signs and max-pool winners are therefore decided on bfloat16 values, the
+ * precision in which a bf16 implementation has to take them.
  */
 #include <math.h>
 #include <stdlib.h>
@@ -39,6 +48,22 @@ static int pool_out(int n, int k, int s) {
   int o = (n - k + s - 1) / s + 1;          /* ceil((n-k)/s) + 1 */
   if ((o - 1) * s >= n) o -= 1;             /* last window must start inside */
   return o < 1 ? 1 : o;
+}
+
+/* round a double to the nearest bfloat16 (ties to even), going through float as hardware does */
+double round_to_bf16(double v) {
+  float f = (float)v;
+  unsigned int u;
+  memcpy(&u, &f, 4);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return v;             /* NaN stays NaN */
+  u += 0x7fffu + ((u >> 16) & 1u);
+  u &= 0xffff0000u;
+  memcpy(&f, &u, 4);
+  return (double)f;
+}
+static void round_array(double* a, size_t n, int on) {
+  if (!on) return;
+  for (size_t i = 0; i < n; i++) a[i] = round_to_bf16(a[i]);
 }
 
 /* ------------------------------------------------------------------ convolution */
@@ -260,8 +285,11 @@ double softmax_ce(const double* z, const int* label, double* dz, int N, int K) {
  * Returns the loss, or NaN when P does not match the network.
  */
 double cnn_loss_and_gradient(const olayer* layers, int nlayers, int C, int H, int W, int N,
-                             const double* theta, long P, const double* x, const int* label,
-                             double* grad) {
+                             const double* theta_in, long P, const double* x, const int* label,
+                             double* grad, int round_bf16) {
+  double* theta = (double*)malloc(sizeof(double) * (size_t)P);
+  memcpy(theta, theta_in, sizeof(double) * (size_t)P);
+  round_array(theta, (size_t)P, round_bf16);
   /* forward: keep every layer's input */
   double** act = (double**)calloc((size_t)nlayers + 1, sizeof(double*));
   int** argm = (int**)calloc((size_t)nlayers, sizeof(int*));
@@ -270,6 +298,7 @@ double cnn_loss_and_gradient(const olayer* layers, int nlayers, int C, int H, in
   size_t n0 = (size_t)N * C * H * W;
   act[0] = (double*)malloc(sizeof(double) * n0);
   memcpy(act[0], x, sizeof(double) * n0);
+  round_array(act[0], n0, round_bf16);
   sc[0] = C; sc[1] = H; sc[2] = W;
   long pos = 0;
   for (int li = 0; li < nlayers; li++) {
@@ -301,6 +330,7 @@ double cnn_loss_and_gradient(const olayer* layers, int nlayers, int C, int H, in
         pos += nw + oc;
       } break;
     }
+    if (li + 1 < nlayers) round_array(act[li + 1], no, round_bf16);   /* the class scores stay unrounded */
     sc[3 * (li + 1)] = oc; sc[3 * (li + 1) + 1] = oh; sc[3 * (li + 1) + 2] = ow;
   }
   double loss = NAN;
@@ -308,6 +338,7 @@ double cnn_loss_and_gradient(const olayer* layers, int nlayers, int C, int H, in
     int K = sc[3 * nlayers] * sc[3 * nlayers + 1] * sc[3 * nlayers + 2];
     double* d = (double*)malloc(sizeof(double) * (size_t)N * K);
     loss = softmax_ce(act[nlayers], label, d, N, K);
+    round_array(d, (size_t)N * K, round_bf16);
     /* backward */
     for (int li = nlayers - 1; li >= 0 && grad; li--) {
       const olayer* L = &layers[li];
@@ -330,12 +361,13 @@ double cnn_loss_and_gradient(const olayer* layers, int nlayers, int C, int H, in
       }
       free(d);
       d = dprev;
+      if (d) round_array(d, ni, round_bf16);
     }
     free(d);
   }
   for (int li = 0; li <= nlayers; li++) free(act[li]);
   for (int li = 0; li < nlayers; li++) free(argm[li]);
-  free(act); free(argm); free(sc); free(off);
+  free(act); free(argm); free(sc); free(off); free(theta);
   return loss;
 }
 

@@ -208,8 +208,8 @@ int sasgd_getMinibatch(sasgd_ctx* ctx, int32_t learner, const float* images_dev,
   if (!ctx->net) return fail(ctx, SASGD_EINVAL, "getMinibatch: context has no network");
   if (learner < 0 || learner >= ctx->cfg.lambda || !images_dev || !labels_dev)
     return fail(ctx, SASGD_EINVAL, "getMinibatch: bad learner or null buffer");
-  if (((uintptr_t)images_dev & 15) || ((uintptr_t)labels_dev & 3))
-    return fail(ctx, SASGD_EINVAL, "getMinibatch: images must be 16-byte aligned");
+  if (((uintptr_t)images_dev & 3) || ((uintptr_t)labels_dev & 3))
+    return fail(ctx, SASGD_EINVAL, "getMinibatch: buffers must be 4-byte aligned");
   Learner& L = ctx->learners[(size_t)learner];
   L.images = images_dev;
   L.labels = labels_dev;

@@ -1,0 +1,247 @@
+// Element-wise and windowed layers of calcGradient (Section 2.1; layer types of Section 4.1): input
+// re-layout, max / average pooling with clipped ceil-mode windows, flattening, softmax cross-entropy.
+// All are bandwidth-bound; lanes walk the channel-innermost (NHWC) index so loads and stores coalesce,
+// reductions over classes use one wavefront per image.  blockIdx.z selects the learner.
+#include "dev_common.hpp"
+#include "kernels.hpp"
+
+namespace sasgd {
+
+static inline dim3 grid_for(int64_t total, int count, int cap = 4096) {
+  int64_t b = (total + 255) / 256;
+  if (b > cap) b = cap;
+  if (b < 1) b = 1;
+  return dim3((unsigned)b, 1, (unsigned)count);
+}
+
+// ------------------------------------------------------------------ input NCHW fp32 -> NHWC T
+template <typename T>
+__global__ __launch_bounds__(256) void pack_input_kernel(CPtrTab images, PtrTab ws, size_t out_off, int N, int C, int H, int W) {
+  const float* in = (const float*)images.p[blockIdx.z];
+  T* out = (T*)ws.p[blockIdx.z] + out_off;
+  const int64_t total = (int64_t)N * C * H * W;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
+    int c = (int)(i % C);
+    int64_t r = i / C;
+    int w = (int)(r % W);
+    r /= W;
+    int h = (int)(r % H);
+    int n = (int)(r / H);
+    stf(out + i, in[(((int64_t)n * C + c) * H + h) * W + w]);
+  }
+}
+
+hipError_t launch_pack_input(bool is_bf16, const CPtrTab& images, const PtrTab& ws, size_t out_off, int count, int N, int C, int H,
+                             int W, hipStream_t s) {
+  dim3 g = grid_for((int64_t)N * C * H * W, count);
+  if (is_bf16) hipLaunchKernelGGL(pack_input_kernel<bf16_t>, g, dim3(256), 0, s, images, ws, out_off, N, C, H, W);
+  else hipLaunchKernelGGL(pack_input_kernel<float>, g, dim3(256), 0, s, images, ws, out_off, N, C, H, W);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ pooling
+// Windows start at (oh*stride, ow*stride) and are clipped at the border.  Max: the first maximum in
+// row-major window order wins and its position inside the window is kept (one byte) for the backward
+// pass.  Average: the divisor is the number of in-bounds elements.
+template <typename T, bool MAX>
+__global__ __launch_bounds__(256) void pool_fwd_kernel(PtrTab ws, size_t x_off, size_t y_off, size_t arg_byte_off, PoolShape sh,
+                                                       int relu) {
+  const T* x = (const T*)ws.p[blockIdx.z] + x_off;
+  T* y = (T*)ws.p[blockIdx.z] + y_off;
+  uint8_t* arg = (uint8_t*)ws.p[blockIdx.z] + arg_byte_off;
+  const int64_t total = (int64_t)sh.N * sh.OH * sh.OW * sh.C;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
+    int c = (int)(i % sh.C);
+    int64_t r = i / sh.C;
+    int ow = (int)(r % sh.OW);
+    r /= sh.OW;
+    int oh = (int)(r % sh.OH);
+    int n = (int)(r / sh.OH);
+    const int h0 = oh * sh.stride, w0 = ow * sh.stride;
+    float acc = 0.f;
+    int best = 0, cnt = 0;
+    for (int kh = 0; kh < sh.ks && h0 + kh < sh.H; kh++)
+      for (int kw = 0; kw < sh.ks && w0 + kw < sh.W; kw++) {
+        float v = ldf(x + (((int64_t)n * sh.H + h0 + kh) * sh.W + w0 + kw) * sh.C + c);
+        if (MAX) {
+          if (cnt == 0 || v > acc) { acc = v; best = kh * sh.ks + kw; }
+        } else {
+          acc += v;
+        }
+        cnt++;
+      }
+    if (!MAX) acc /= (float)cnt;
+    if (relu) acc = fmaxf(acc, 0.f);
+    stf(y + i, acc);
+    if (MAX) arg[i] = (uint8_t)best;
+  }
+}
+
+template <typename T, bool MAX>
+__global__ __launch_bounds__(256) void pool_bwd_kernel(PtrTab ws, size_t dy_off, size_t dx_off, size_t arg_byte_off, PoolShape sh,
+                                                       int use_mask, size_t mask_off) {
+  const T* dy = (const T*)ws.p[blockIdx.z] + dy_off;
+  T* dx = (T*)ws.p[blockIdx.z] + dx_off;
+  const T* mask = (const T*)ws.p[blockIdx.z] + mask_off;
+  const uint8_t* arg = (const uint8_t*)ws.p[blockIdx.z] + arg_byte_off;
+  const int64_t total = (int64_t)sh.N * sh.H * sh.W * sh.C;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
+    int c = (int)(i % sh.C);
+    int64_t r = i / sh.C;
+    int iw = (int)(r % sh.W);
+    r /= sh.W;
+    int ih = (int)(r % sh.H);
+    int n = (int)(r / sh.H);
+    float acc = 0.f;
+    if (!use_mask || ldf(mask + i) > 0.f) {
+      // windows that contain (ih, iw): oh*stride <= ih < oh*stride + ks
+      int oh_lo = ih - sh.ks + 1 > 0 ? (ih - sh.ks + sh.stride) / sh.stride : 0;
+      int oh_hi = min(sh.OH - 1, ih / sh.stride);
+      int ow_lo = iw - sh.ks + 1 > 0 ? (iw - sh.ks + sh.stride) / sh.stride : 0;
+      int ow_hi = min(sh.OW - 1, iw / sh.stride);
+      for (int oh = oh_lo; oh <= oh_hi; oh++)
+        for (int ow = ow_lo; ow <= ow_hi; ow++) {
+          const int64_t o = (((int64_t)n * sh.OH + oh) * sh.OW + ow) * sh.C + c;
+          if (MAX) {
+            if (arg[o] == (uint8_t)((ih - oh * sh.stride) * sh.ks + (iw - ow * sh.stride))) acc += ldf(dy + o);
+          } else {
+            int ch = min(oh * sh.stride + sh.ks, sh.H) - oh * sh.stride;
+            int cw = min(ow * sh.stride + sh.ks, sh.W) - ow * sh.stride;
+            acc += ldf(dy + o) / (float)(ch * cw);
+          }
+        }
+    }
+    stf(dx + i, acc);
+  }
+}
+
+hipError_t launch_pool_fwd(bool is_bf16, bool is_max, const PtrTab& ws, size_t x_off, size_t y_off, size_t arg_byte_off,
+                           const PoolShape& sh, bool relu, int count, hipStream_t s) {
+  dim3 g = grid_for((int64_t)sh.N * sh.OH * sh.OW * sh.C, count);
+  int r = relu ? 1 : 0;
+  if (is_bf16) {
+    if (is_max) hipLaunchKernelGGL((pool_fwd_kernel<bf16_t, true>), g, dim3(256), 0, s, ws, x_off, y_off, arg_byte_off, sh, r);
+    else hipLaunchKernelGGL((pool_fwd_kernel<bf16_t, false>), g, dim3(256), 0, s, ws, x_off, y_off, arg_byte_off, sh, r);
+  } else {
+    if (is_max) hipLaunchKernelGGL((pool_fwd_kernel<float, true>), g, dim3(256), 0, s, ws, x_off, y_off, arg_byte_off, sh, r);
+    else hipLaunchKernelGGL((pool_fwd_kernel<float, false>), g, dim3(256), 0, s, ws, x_off, y_off, arg_byte_off, sh, r);
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_pool_bwd(bool is_bf16, bool is_max, const PtrTab& ws, size_t dy_off, size_t dx_off, size_t arg_byte_off,
+                           const PoolShape& sh, bool use_mask, size_t mask_off, int count, hipStream_t s) {
+  dim3 g = grid_for((int64_t)sh.N * sh.H * sh.W * sh.C, count);
+  int um = use_mask ? 1 : 0;
+  if (is_bf16) {
+    if (is_max) hipLaunchKernelGGL((pool_bwd_kernel<bf16_t, true>), g, dim3(256), 0, s, ws, dy_off, dx_off, arg_byte_off, sh, um, mask_off);
+    else hipLaunchKernelGGL((pool_bwd_kernel<bf16_t, false>), g, dim3(256), 0, s, ws, dy_off, dx_off, arg_byte_off, sh, um, mask_off);
+  } else {
+    if (is_max) hipLaunchKernelGGL((pool_bwd_kernel<float, true>), g, dim3(256), 0, s, ws, dy_off, dx_off, arg_byte_off, sh, um, mask_off);
+    else hipLaunchKernelGGL((pool_bwd_kernel<float, false>), g, dim3(256), 0, s, ws, dy_off, dx_off, arg_byte_off, sh, um, mask_off);
+  }
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ flatten (NHWC -> C,H,W order) and back
+template <typename T>
+__global__ __launch_bounds__(256) void flatten_fwd_kernel(PtrTab ws, size_t x_off, size_t y_off, int N, int C, int H, int W) {
+  const T* x = (const T*)ws.p[blockIdx.z] + x_off;
+  T* y = (T*)ws.p[blockIdx.z] + y_off;
+  const int HW = H * W;
+  const int64_t total = (int64_t)N * C * HW;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
+    int hw = (int)(i % HW);
+    int64_t r = i / HW;
+    int c = (int)(r % C);
+    int n = (int)(r / C);
+    y[i] = x[((int64_t)n * HW + hw) * C + c];
+  }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void flatten_bwd_kernel(PtrTab ws, size_t dy_off, size_t dx_off, int N, int C, int H, int W,
+                                                          int use_mask, size_t mask_off) {
+  const T* dy = (const T*)ws.p[blockIdx.z] + dy_off;
+  T* dx = (T*)ws.p[blockIdx.z] + dx_off;
+  const T* mask = (const T*)ws.p[blockIdx.z] + mask_off;
+  const int HW = H * W;
+  const int64_t total = (int64_t)N * C * HW;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
+    int c = (int)(i % C);
+    int64_t r = i / C;
+    int hw = (int)(r % HW);
+    int n = (int)(r / HW);
+    float v = ldf(dy + ((int64_t)n * C + c) * HW + hw);
+    if (use_mask && !(ldf(mask + i) > 0.f)) v = 0.f;
+    stf(dx + i, v);
+  }
+}
+
+hipError_t launch_flatten_fwd(bool is_bf16, const PtrTab& ws, size_t x_off, size_t y_off, int N, int C, int H, int W, int count,
+                              hipStream_t s) {
+  dim3 g = grid_for((int64_t)N * C * H * W, count);
+  if (is_bf16) hipLaunchKernelGGL(flatten_fwd_kernel<bf16_t>, g, dim3(256), 0, s, ws, x_off, y_off, N, C, H, W);
+  else hipLaunchKernelGGL(flatten_fwd_kernel<float>, g, dim3(256), 0, s, ws, x_off, y_off, N, C, H, W);
+  return hipGetLastError();
+}
+
+hipError_t launch_flatten_bwd(bool is_bf16, const PtrTab& ws, size_t dy_off, size_t dx_off, int N, int C, int H, int W, bool use_mask,
+                              size_t mask_off, int count, hipStream_t s) {
+  dim3 g = grid_for((int64_t)N * C * H * W, count);
+  int um = use_mask ? 1 : 0;
+  if (is_bf16) hipLaunchKernelGGL(flatten_bwd_kernel<bf16_t>, g, dim3(256), 0, s, ws, dy_off, dx_off, N, C, H, W, um, mask_off);
+  else hipLaunchKernelGGL(flatten_bwd_kernel<float>, g, dim3(256), 0, s, ws, dy_off, dx_off, N, C, H, W, um, mask_off);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ softmax cross-entropy
+// One workgroup per learner, one wavefront per image (images strided over the four wavefronts).  The
+// per-image losses are summed in image order by lane 0 of the workgroup so the result does not depend on
+// scheduling.  dz = (softmax(z) - onehot(label)) / N, i.e. the gradient of the MEAN loss: this is where
+// the division by the mini-batch size enters (Section 2.1).
+template <typename T, typename Z>
+__global__ __launch_bounds__(256) void softmax_ce_kernel(PtrTab ws, CPtrTab labels, size_t z_off, size_t dz_off, int N, int K,
+                                                         float* loss_out) {
+  extern __shared__ float img_loss[];   // [N]
+  const int l = blockIdx.x;
+  const Z* z = reinterpret_cast<const Z*>((const T*)ws.p[l] + z_off);
+  T* dz = (T*)ws.p[l] + dz_off;
+  const int32_t* lab = (const int32_t*)labels.p[l];
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const float invN = 1.0f / (float)N;
+  for (int n = wave; n < N; n += 4) {
+    const Z* zn = z + (int64_t)n * K;
+    float m = -INFINITY;
+    for (int j = lane; j < K; j += 64) m = fmaxf(m, ldf(zn + j));
+    m = wave_max(m);
+    float sum = 0.f;
+    for (int j = lane; j < K; j += 64) sum += expf(ldf(zn + j) - m);
+    sum = wave_sum(sum);
+    const int y = lab[n];
+    const bool valid = y >= 0 && y < K;
+    const float inv = 1.0f / sum;
+    for (int j = lane; j < K; j += 64) {
+      float p = expf(ldf(zn + j) - m) * inv;
+      stf(dz + (int64_t)n * K + j, (p - (j == y ? 1.f : 0.f)) * invN);
+    }
+    if (lane == 0) img_loss[n] = valid ? -(ldf(zn + y) - m - logf(sum)) : NAN;   // a label outside [0,K) poisons the loss
+  }
+  __syncthreads();
+  if (threadIdx.x == 0 && loss_out) {
+    float tot = 0.f;
+    for (int n = 0; n < N; n++) tot += img_loss[n];
+    loss_out[l] = tot * invN;
+  }
+}
+
+hipError_t launch_softmax_ce(bool is_bf16, bool z_f32, const PtrTab& ws, const CPtrTab& labels, size_t z_off, size_t dz_off, int N,
+                             int K, float* loss_out, int count, hipStream_t s) {
+  size_t shm = (size_t)N * sizeof(float);
+  if (is_bf16 && z_f32) hipLaunchKernelGGL((softmax_ce_kernel<bf16_t, float>), dim3(count), dim3(256), shm, s, ws, labels, z_off, dz_off, N, K, loss_out);
+  else if (is_bf16) hipLaunchKernelGGL((softmax_ce_kernel<bf16_t, bf16_t>), dim3(count), dim3(256), shm, s, ws, labels, z_off, dz_off, N, K, loss_out);
+  else hipLaunchKernelGGL((softmax_ce_kernel<float, float>), dim3(count), dim3(256), shm, s, ws, labels, z_off, dz_off, N, K, loss_out);
+  return hipGetLastError();
+}
+
+}  // namespace sasgd

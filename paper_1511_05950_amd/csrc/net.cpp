@@ -1,11 +1,261 @@
-// placeholder
-#include "ctx.hpp"
+// Network plan and executor of calcGradient (Section 2.1): the layer list is turned into a list of
+// device operations with fixed offsets into one per-learner workspace; a calcGradient call walks the list
+// forward and backward, every launch covering all listed learners at once.  ReLU layers are fused into the
+// operation that produces their input (its output is stored after the ReLU; the backward mask is applied
+// by whichever kernel produces the gradient of that tensor).
+#include <string.h>
+
+#include <vector>
+
+#include "kernels.hpp"
+
 namespace sasgd {
-struct Net {};
-int net_create(const sasgd_config&, Net**, int64_t*, size_t*, std::string& err) { err = "network path not built"; return SASGD_EINVAL; }
-void net_destroy(Net*) {}
-size_t net_workspace_bytes(const Net*) { return 0; }
-void net_set_workspace(Net*, int, void*) {}
-hipError_t net_prepare_version(Net*, const void*, void*, hipStream_t) { return hipSuccess; }
-hipError_t net_calc_gradient(Net*, const int*, const LearnerBind*, int, float*, hipStream_t) { return hipErrorNotSupported; }
+
+enum OpKind { OP_CONV, OP_POOL_MAX, OP_POOL_AVG, OP_FLATTEN };
+
+struct Op {
+  OpKind kind;
+  bool relu = false;           // output stored after ReLU
+  bool is_fc = false;
+  bool out_f32 = false;        // output kept in fp32 (class scores)
+  ConvShape cs{};              // OP_CONV
+  PoolShape ps{};              // pools; OP_FLATTEN uses N,C,H,W
+  int64_t w_off = 0, b_off = 0;
+  int in_t = 0, out_t = 0;     // tensor indices
+  size_t arg_off = 0;          // byte offset of the max-pool argmax, from the workspace base
+};
+
+struct Tensor {
+  size_t off = 0;              // element offset in the workspace
+  size_t elems = 0;
+  bool relu = false;           // values are post-ReLU (a gradient flowing into it must be masked)
+};
+
+struct Net {
+  int mu = 0;
+  bool bf16 = false;
+  int classes = 0;
+  bool scores_f32 = false;
+  int64_t P = 0;
+  std::vector<Op> ops;
+  std::vector<Tensor> tensors; // tensor 0 = re-laid-out input
+  int inC = 0, inH = 0, inW = 0;
+  size_t grad_a = 0, grad_b = 0, grad_elems = 0;   // two gradient-activation buffers (element offsets)
+  size_t ws_bytes = 0;
+  void* ws[kMaxLearners] = {nullptr};
+};
+
+static int pool_out_size(int n, int k, int s) {
+  int o = (n - k + s - 1) / s + 1;
+  if ((o - 1) * s >= n) o--;
+  return o < 1 ? 1 : o;
 }
+
+static const sasgd_layer kCifar3[] = {
+    {SASGD_CONV, 32, 5, 1, 2}, {SASGD_MAXPOOL, 0, 3, 2, 0}, {SASGD_RELU, 0, 0, 0, 0},
+    {SASGD_CONV, 32, 5, 1, 2}, {SASGD_RELU, 0, 0, 0, 0},    {SASGD_AVGPOOL, 0, 3, 2, 0},
+    {SASGD_CONV, 64, 5, 1, 2}, {SASGD_RELU, 0, 0, 0, 0},    {SASGD_AVGPOOL, 0, 3, 2, 0},
+    {SASGD_FC, 10, 0, 0, 0}};
+
+static const sasgd_layer kAlex8[] = {
+    {SASGD_CONV, 96, 11, 4, 0}, {SASGD_RELU, 0, 0, 0, 0}, {SASGD_MAXPOOL, 0, 3, 2, 0},
+    {SASGD_CONV, 256, 5, 1, 2}, {SASGD_RELU, 0, 0, 0, 0}, {SASGD_MAXPOOL, 0, 3, 2, 0},
+    {SASGD_CONV, 384, 3, 1, 1}, {SASGD_RELU, 0, 0, 0, 0},
+    {SASGD_CONV, 384, 3, 1, 1}, {SASGD_RELU, 0, 0, 0, 0},
+    {SASGD_CONV, 256, 3, 1, 1}, {SASGD_RELU, 0, 0, 0, 0}, {SASGD_MAXPOOL, 0, 3, 2, 0},
+    {SASGD_FC, 4096, 0, 0, 0},  {SASGD_RELU, 0, 0, 0, 0},
+    {SASGD_FC, 4096, 0, 0, 0},  {SASGD_RELU, 0, 0, 0, 0},
+    {SASGD_FC, 1000, 0, 0, 0}};
+
+int net_create(const sasgd_config& cfg, Net** out, int64_t* out_P, size_t* out_pack_elems, std::string& err) {
+  const sasgd_layer* layers = nullptr;
+  int nl = 0, C = 0, H = 0, W = 0;
+  if (cfg.net == SASGD_NET_CIFAR3) {
+    layers = kCifar3; nl = (int)(sizeof(kCifar3) / sizeof(kCifar3[0])); C = 3; H = 32; W = 32;
+  } else if (cfg.net == SASGD_NET_ALEX8) {
+    layers = kAlex8; nl = (int)(sizeof(kAlex8) / sizeof(kAlex8[0])); C = 3; H = 224; W = 224;
+  } else if (cfg.net == SASGD_NET_CUSTOM) {
+    layers = cfg.layers; nl = cfg.num_layers; C = cfg.in_channels; H = cfg.in_height; W = cfg.in_width;
+    if (!layers || nl < 1 || nl > 256 || C < 1 || H < 1 || W < 1) { err = "custom network: bad layer table or input shape"; return SASGD_EINVAL; }
+  } else {
+    err = "unknown network"; return SASGD_EINVAL;
+  }
+  if (cfg.mu < 1 || cfg.mu > 4096) { err = "mu out of range (1..4096)"; return SASGD_EINVAL; }
+
+  Net* net = new Net();
+  net->mu = cfg.mu;
+  net->bf16 = cfg.compute == SASGD_BF16;
+  net->inC = C; net->inH = H; net->inW = W;
+  const int N = cfg.mu;
+  size_t cursor = 0;       // elements of T
+  auto new_tensor = [&](size_t elems) {
+    Tensor t;
+    t.off = cursor;
+    t.elems = elems;
+    cursor += (elems + 63) & ~(size_t)63;
+    net->tensors.push_back(t);
+    return (int)net->tensors.size() - 1;
+  };
+  int cur = new_tensor((size_t)N * C * H * W);
+  bool flat = false;       // current tensor already in (C,H,W)-flattened order (after a flatten or an fc)
+  int64_t P = 0;
+  size_t arg_bytes = 0;
+  for (int li = 0; li < nl; li++) {
+    const sasgd_layer& L = layers[li];
+    if (L.kind == SASGD_RELU) {
+      if (net->ops.empty() || net->tensors[(size_t)cur].relu) { delete net; err = "relu must directly follow a conv, fc or pooling layer"; return SASGD_EINVAL; }
+      net->ops.back().relu = true;
+      net->tensors[(size_t)cur].relu = true;
+      continue;
+    }
+    Op op;
+    if (L.kind == SASGD_CONV) {
+      if (flat || L.units < 1 || L.window < 1 || L.stride < 1 || L.pad < 0 || L.pad >= L.window || H + 2 * L.pad < L.window || W + 2 * L.pad < L.window) {
+        delete net; err = "conv layer: bad shape"; return SASGD_EINVAL;
+      }
+      op.kind = OP_CONV;
+      op.cs = ConvShape{N, C, H, W, L.units, (H + 2 * L.pad - L.window) / L.stride + 1, (W + 2 * L.pad - L.window) / L.stride + 1, L.window, L.stride, L.pad};
+      op.w_off = P;
+      P += (int64_t)L.units * C * L.window * L.window;
+      op.b_off = P;
+      P += L.units;
+      op.in_t = cur;
+      C = L.units; H = op.cs.OH; W = op.cs.OW;
+      cur = op.out_t = new_tensor((size_t)N * C * H * W);
+    } else if (L.kind == SASGD_MAXPOOL || L.kind == SASGD_AVGPOOL) {
+      if (flat || L.window < 1 || L.window > 15 || L.stride < 1 || L.window > H || L.window > W) { delete net; err = "pooling layer: bad shape"; return SASGD_EINVAL; }
+      op.kind = L.kind == SASGD_MAXPOOL ? OP_POOL_MAX : OP_POOL_AVG;
+      op.ps = PoolShape{N, C, H, W, pool_out_size(H, L.window, L.stride), pool_out_size(W, L.window, L.stride), L.window, L.stride};
+      op.in_t = cur;
+      H = op.ps.OH; W = op.ps.OW;
+      cur = op.out_t = new_tensor((size_t)N * C * H * W);
+      if (op.kind == OP_POOL_MAX) { op.arg_off = arg_bytes; arg_bytes += ((size_t)N * C * H * W + 255) & ~(size_t)255; }
+    } else if (L.kind == SASGD_FC) {
+      if (L.units < 1) { delete net; err = "fc layer: bad shape"; return SASGD_EINVAL; }
+      if (!flat && H * W > 1) {           // bring the tensor into the (C,H,W) order of the fc weights
+        Op fl;
+        fl.kind = OP_FLATTEN;
+        fl.ps = PoolShape{N, C, H, W, 0, 0, 0, 0};
+        fl.in_t = cur;
+        cur = fl.out_t = new_tensor((size_t)N * C * H * W);
+        net->ops.push_back(fl);
+      }
+      const int in = C * H * W;
+      op.kind = OP_CONV;
+      op.is_fc = true;
+      op.cs = ConvShape{N, in, 1, 1, L.units, 1, 1, 1, 1, 0};
+      op.w_off = P;
+      P += (int64_t)L.units * in;
+      op.b_off = P;
+      P += L.units;
+      op.in_t = cur;
+      C = L.units; H = 1; W = 1;
+      flat = true;
+      cur = op.out_t = new_tensor((size_t)N * C);
+    } else {
+      delete net; err = "unknown layer kind"; return SASGD_EINVAL;
+    }
+    net->ops.push_back(op);
+  }
+  if (P < 1) { delete net; err = "network has no parameters"; return SASGD_EINVAL; }
+  if (net->tensors[(size_t)cur].relu) { delete net; err = "the class scores must not pass through a relu"; return SASGD_EINVAL; }
+  net->classes = C * H * W;
+  if (net->classes < 2) { delete net; err = "network output must have at least two classes"; return SASGD_EINVAL; }
+  if (!flat && H * W > 1) {               // scores must be one vector per image in class order
+    Op fl;
+    fl.kind = OP_FLATTEN;
+    fl.ps = PoolShape{N, C, H, W, 0, 0, 0, 0};
+    fl.in_t = cur;
+    cur = fl.out_t = new_tensor((size_t)N * C * H * W);
+    net->ops.push_back(fl);
+  }
+  if (net->ops.back().kind == OP_CONV) {   // class scores produced by a conv / fc: keep them in fp32
+    net->ops.back().out_f32 = true;
+    net->scores_f32 = true;
+    if (net->bf16) { new_tensor(net->tensors[(size_t)cur].elems); }   // room for the wider elements (tensor is last in the arena)
+  }
+  net->P = P;
+  size_t maxe = 0;
+  for (const Tensor& t : net->tensors) maxe = t.elems > maxe ? t.elems : maxe;
+  net->grad_elems = (maxe + 63) & ~(size_t)63;
+  net->grad_a = cursor;
+  net->grad_b = cursor + net->grad_elems;
+  cursor += 2 * net->grad_elems;
+  const size_t esz = net->bf16 ? 2 : 4;
+  size_t bytes = (cursor * esz + 255) & ~(size_t)255;
+  for (Op& op : net->ops) op.arg_off += bytes;
+  bytes += arg_bytes;
+  net->ws_bytes = bytes + 256;
+  *out = net;
+  *out_P = P;
+  *out_pack_elems = 0;
+  return SASGD_OK;
+}
+
+void net_destroy(Net* net) { delete net; }
+size_t net_workspace_bytes(const Net* net) { return net->ws_bytes; }
+void net_set_workspace(Net* net, int learner, void* ws) { net->ws[learner] = ws; }
+
+hipError_t net_prepare_version(Net*, const void*, void*, hipStream_t) { return hipSuccess; }
+
+#define TRY(x) do { hipError_t e__ = (x); if (e__ != hipSuccess) return e__; } while (0)
+
+hipError_t net_calc_gradient(Net* net, const int* learners, const LearnerBind* binds, int count, float* out_loss_dev,
+                             hipStream_t stream) {
+  PtrTab ws, grads;
+  CPtrTab wts, imgs, labs;
+  memset(&ws, 0, sizeof(ws)); memset(&grads, 0, sizeof(grads));
+  memset(&wts, 0, sizeof(wts)); memset(&imgs, 0, sizeof(imgs)); memset(&labs, 0, sizeof(labs));
+  for (int k = 0; k < count; k++) {
+    ws.p[k] = net->ws[learners[k]];
+    grads.p[k] = binds[k].grad;
+    wts.p[k] = binds[k].weights;
+    imgs.p[k] = binds[k].images;
+    labs.p[k] = binds[k].labels;
+  }
+  const bool bf = net->bf16;
+  const std::vector<Tensor>& T = net->tensors;
+  // ---- forward
+  TRY(launch_pack_input(bf, imgs, ws, T[0].off, count, net->mu, net->inC, net->inH, net->inW, stream));
+  for (const Op& op : net->ops) {
+    const size_t xi = T[(size_t)op.in_t].off, yo = T[(size_t)op.out_t].off;
+    switch (op.kind) {
+      case OP_CONV:
+        TRY(launch_conv_fwd_simple(bf, ws, wts, xi, yo, op.w_off, op.b_off, op.cs, op.relu, op.out_f32, count, stream));
+        break;
+      case OP_POOL_MAX:
+      case OP_POOL_AVG:
+        TRY(launch_pool_fwd(bf, op.kind == OP_POOL_MAX, ws, xi, yo, op.arg_off, op.ps, op.relu, count, stream));
+        break;
+      case OP_FLATTEN:
+        TRY(launch_flatten_fwd(bf, ws, xi, yo, op.ps.N, op.ps.C, op.ps.H, op.ps.W, count, stream));
+        break;
+    }
+  }
+  // ---- loss and its gradient with respect to the class scores
+  size_t dy = net->grad_a, dx = net->grad_b;
+  TRY(launch_softmax_ce(bf, net->scores_f32, ws, labs, T[(size_t)net->ops.back().out_t].off, dy, net->mu, net->classes, out_loss_dev, count, stream));
+  // ---- backward
+  for (int k = (int)net->ops.size() - 1; k >= 0; k--) {
+    const Op& op = net->ops[(size_t)k];
+    const Tensor& tin = T[(size_t)op.in_t];
+    const bool need_dx = op.in_t != 0;          // the network input needs no gradient
+    switch (op.kind) {
+      case OP_CONV:
+        TRY(launch_conv_wgrad_simple(bf, ws, grads, tin.off, dy, op.w_off, op.b_off, op.cs, count, stream));
+        if (need_dx) TRY(launch_conv_dgrad_simple(bf, ws, wts, dy, dx, op.w_off, op.cs, tin.relu, tin.off, count, stream));
+        break;
+      case OP_POOL_MAX:
+      case OP_POOL_AVG:
+        if (need_dx) TRY(launch_pool_bwd(bf, op.kind == OP_POOL_MAX, ws, dy, dx, op.arg_off, op.ps, tin.relu, tin.off, count, stream));
+        break;
+      case OP_FLATTEN:
+        if (need_dx) TRY(launch_flatten_bwd(bf, ws, dy, dx, op.ps.N, op.ps.C, op.ps.H, op.ps.W, tin.relu, tin.off, count, stream));
+        break;
+    }
+    if (need_dx) { size_t t = dy; dy = dx; dx = t; }
+  }
+  return hipSuccess;
+}
+
+}  // namespace sasgd
