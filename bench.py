@@ -21,6 +21,10 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+# HBM bytes per launch of the update kernel at P = 60e6, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
+# script scaled by a plain 240 MB copy in the same run (summary: profiles/apply_update_config1.txt)
+TRAFFIC_C1 = 1.2000e9
+TRAFFIC_C54 = 13.920e9
 
 
 def cpu_baseline_server(cfg, budget_s=12.0):
@@ -80,6 +84,14 @@ def bench_server(args):
         ctxB.sumGradients()
         ctxB.applyUpdate()
 
+    if args.calibrate_copy:
+        # a plain device-to-device copy of one gradient (240 MB read + 240 MB written): the reference the
+        # rocprofv3 FETCH_SIZE / WRITE_SIZE counters of the update kernels are scaled by
+        scratch = torch.empty_like(grads[0])
+        for l in range(3):
+            scratch.copy_(grads[l])
+        torch.cuda.synchronize()
+        del scratch
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -109,10 +121,10 @@ def bench_server(args):
                                "54 updates at c=1 (54-softsync) + 1 update at c=54 (1-softsync)",
                    "num_params": P, "lambda": lam, "momentum": cfg["momentum"], "weight_decay": cfg["weight_decay"]},
         "roofline": {"bound": "hbm", "kernel": "apply_update_kernel (c=1)", "achieved": round(achA, 1),
-                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achA / HBM_PEAK_GBS, 4), "traffic": None,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achA / HBM_PEAK_GBS, 4), "traffic": TRAFFIC_C1,
                      "avg_launch_us": round(kA * 1e6, 2), "bytes_per_launch": P * 20},
         "roofline_c54": {"bound": "hbm", "kernel": "apply_update_kernel (c=54)", "achieved": round(achB, 1),
-                         "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achB / HBM_PEAK_GBS, 4), "traffic": None,
+                         "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achB / HBM_PEAK_GBS, 4), "traffic": TRAFFIC_C54,
                          "avg_launch_us": round(kB * 1e6, 2), "bytes_per_launch": P * 4 * (lam + 4)},
     }
     if not args.no_cpu:
@@ -127,6 +139,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="server")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg (profiling runs)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run plain 240 MB device copies (reference for rocprofv3 byte counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (lambda learners are simulated on it); use --gpus 1",
