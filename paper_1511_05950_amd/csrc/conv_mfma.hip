@@ -1,0 +1,457 @@
+// bf16 MFMA implicit-GEMM kernels for calcGradient's convolutions and fully connected layers
+// (Section 2.1 learner step; layer shapes of Section 4.1), written for gfx950 (CDNA4):
+// v_mfma_f32_32x32x16_bf16 tiles, fp32 accumulation, LDS-staged im2col tiles, 64-wide wavefronts.
+//
+// GEMM views (activations NHWC bf16, "chunk" = 8 consecutive channels = 16 bytes):
+//   forward  y[m][n]  = sum_k im2col(x)[m][k] * Wp[n][k]      m = (image, oh, ow), k = (kh, kw, c)
+//   dgrad    dx[m][c] = sum_k im2col(dy)[m][k] * Wt[c][k]     the same kernel on dy with flipped, transposed
+//                                                             filters (stride 1), or, for fully connected
+//                                                             layers, with the B operand read transposed
+//   wgrad    dW[n][k] = sum_m dy[m][n] * im2col(x)[m][k]      both operands are contraction-major in memory;
+//                                                             they are staged as they lie and read with the
+//                                                             LDS transpose load (ds_read_b64_tr_b16)
+// The im2col matrix is never materialised: a tile loader gathers 16-byte chunks straight from the NHWC
+// tensor (zero outside the image).  Only stride-1 windows are handled here; a strided first layer is
+// turned into a stride-1 layer by a space-to-depth re-layout of the input (see pack_input).
+#include "dev_common.hpp"
+#include "kernels.hpp"
+
+namespace sasgd {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(4 * sizeof(short)))) short shortx4;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
+
+constexpr int BK = 32;           // contraction elements per step (4 chunks)
+constexpr int LDA = BK + 8;      // row stride (elements) of k-contiguous LDS tiles: 80 B, conflict-free 16 B reads
+
+// Source index, in the flat [K][Creal][ksr][ksr] filter, of packed element (n, tap, cp) of a virtual
+// stride-1 layer, or -1 for padding.  s2d > 1: the layer is a strided one seen through a
+// space-to-depth input: channel cp = (dy*s2d + dx)*Creal + c, tap = (KY, KX), kh = s2d*KY + dy.
+__host__ __device__ inline int64_t filter_src(const VConv& v, int n, int tap, int cp) {
+  int kh, kw, c;
+  if (v.s2d == 1) {
+    if (cp >= v.Creal) return -1;
+    c = cp; kh = tap / v.ks; kw = tap % v.ks;
+  } else {
+    int g = cp / v.Creal;
+    c = cp % v.Creal;
+    if (g >= v.s2d * v.s2d) return -1;
+    kh = v.s2d * (tap / v.ks) + g / v.s2d;
+    kw = v.s2d * (tap % v.ks) + g % v.s2d;
+    if (kh >= v.ksr || kw >= v.ksr) return -1;
+  }
+  return (((int64_t)n * v.Creal + c) * v.ksr + kh) * v.ksr + kw;
+}
+
+// ------------------------------------------------------------------ filter packing (once per weight version)
+// fwd:  Wp[n][tap][cp]            (row length Kp = padded ks*ks*C)
+// bwd:  Wt[c][tap'][n]            tap' = flipped tap, row length Kpt = padded ks*ks*K   (stride-1 layers only)
+__global__ __launch_bounds__(256) void pack_filters_kernel(const bf16_t* __restrict__ flat, bf16_t* __restrict__ packed, VConv v,
+                                                           int64_t w_off, int64_t fwd_off, int64_t bwd_off, int Kp, int Kpt,
+                                                           int want_bwd) {
+  const int64_t nf = (int64_t)v.K * Kp;
+  const int64_t nb = want_bwd ? (int64_t)v.C * Kpt : 0;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < nf + nb; i += (int64_t)gridDim.x * 256) {
+    if (i < nf) {
+      int n = (int)(i / Kp), k = (int)(i % Kp);
+      int tap = k / v.C, cp = k % v.C;
+      int64_t src = tap < v.ks * v.ks ? filter_src(v, n, tap, cp) : -1;
+      packed[fwd_off + i] = src >= 0 ? flat[w_off + src] : (bf16_t)0;
+    } else {
+      int64_t j = i - nf;
+      int c = (int)(j / Kpt), k = (int)(j % Kpt);
+      int tap = k / v.K, n = k % v.K;
+      bf16_t val = 0;
+      if (tap < v.ks * v.ks) {
+        int flipped = v.ks * v.ks - 1 - tap;            // (ks-1-kh, ks-1-kw)
+        int64_t src = filter_src(v, n, flipped, c);
+        if (src >= 0) val = flat[w_off + src];
+      }
+      packed[bwd_off + j] = val;
+    }
+  }
+}
+
+hipError_t launch_pack_filters(const void* flat, void* packed, const VConv& v, int64_t w_off, int64_t fwd_off, int64_t bwd_off,
+                               int Kp, int Kpt, bool want_bwd, hipStream_t s) {
+  int64_t total = (int64_t)v.K * Kp + (want_bwd ? (int64_t)v.C * Kpt : 0);
+  int blocks = (int)((total + 255) / 256 < 2048 ? (total + 255) / 256 : 2048);
+  hipLaunchKernelGGL(pack_filters_kernel, dim3(blocks), dim3(256), 0, s, (const bf16_t*)flat, (bf16_t*)packed, v, w_off, fwd_off,
+                     bwd_off, Kp, Kpt, want_bwd ? 1 : 0);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ im2col chunk gather
+// Row m of the virtual im2col matrix, chunk q (8 channels of one tap): 16 bytes from the NHWC tensor or zeros.
+struct RowPos {
+  const bf16_t* base;   // &t[n][oh - pad][ow - pad][0]  (may point outside; only dereferenced when in range)
+  int oh, ow;           // already offset by -pad
+  bool valid;
+};
+
+__device__ __forceinline__ RowPos row_pos(const bf16_t* t, const IGemm& g, int m) {
+  RowPos r;
+  r.valid = m < g.M;
+  int mm = r.valid ? m : 0;
+  int ow = mm % g.OW;
+  int rest = mm / g.OW;
+  int oh = rest % g.OH;
+  int n = rest / g.OH;
+  r.oh = oh - g.pad;
+  r.ow = ow - g.pad;
+  r.base = t + (((int64_t)n * g.H + r.oh) * g.W + r.ow) * g.C;
+  return r;
+}
+
+__device__ __forceinline__ uint4 gather_chunk(const RowPos& r, const IGemm& g, int q) {
+  uint4 z = make_uint4(0, 0, 0, 0);
+  if (!r.valid || q >= g.Kchunks) return z;
+  int tap = q / g.CPT;
+  int c8 = q - tap * g.CPT;
+  int kh = tap / g.ks, kw = tap - kh * g.ks;
+  int ih = r.oh + kh, iw = r.ow + kw;
+  if (ih < 0 || ih >= g.H || iw < 0 || iw >= g.W) return z;
+  return *reinterpret_cast<const uint4*>(r.base + ((int64_t)kh * g.W + kw) * g.C + c8 * 8);
+}
+
+// ------------------------------------------------------------------ forward / dgrad kernel
+// Block tile BM x BN, four wavefronts each owning a WM x WN sub-tile of 32x32 MFMA blocks.
+// BT = false: B rows are output columns, k-contiguous (packed filters): B[n][k], row length ldb.
+// BT = true : B is stored contraction-major, B[k][n] with row length ldb (flat fully connected weights
+//             used for dgrad); its tile is staged as it lies and read with the transpose load.
+template <int BM, int BN, int WM, int WN, bool BT>
+__global__ __launch_bounds__(256) void igemm_kernel(PtrTab ws, CPtrTab wts, IGemm g, Epilogue ep) {
+  constexpr int WAVES_N = BN / WN;
+  constexpr int TM = WM / 32, TN = WN / 32;
+  constexpr int LDBT = BN + (BN == 128 ? 32 : (BN == 64 ? 32 : 0));   // transposed tile: row stride = 16 (mod 64) words
+  constexpr int A_ELEMS = BM * LDA;
+  constexpr int B_ELEMS = BT ? BK * LDBT : BN * LDA;
+  __shared__ __attribute__((aligned(16))) bf16_t lds[2 * (A_ELEMS + B_ELEMS)];
+
+  const int z = blockIdx.z;
+  const bf16_t* act = (const bf16_t*)ws.p[z] + g.a_off;
+  const bf16_t* Bm = (const bf16_t*)wts.p[z] + g.b_off;
+  const int m0 = blockIdx.x * BM, n0 = blockIdx.y * BN;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm0 = (wave / WAVES_N) * WM, wn0 = (wave % WAVES_N) * WN;
+
+  // loader assignment: chunk column cc (0..3) is fixed per thread, rows stride 64
+  constexpr int A_LOADS = (BM * 4 + 255) / 256;
+  constexpr int B_LOADS = BT ? (BK * (BN / 8) + 255) / 256 : (BN * 4 + 255) / 256;
+  const int cc = tid & 3, lrow = tid >> 2;
+  RowPos rp[A_LOADS];
+#pragma unroll
+  for (int i = 0; i < A_LOADS; i++) rp[i] = row_pos(act, g, m0 + lrow + 64 * i);
+
+  uint4 ra[A_LOADS], rb[B_LOADS];
+  auto load_regs = [&](int ks) {
+#pragma unroll
+    for (int i = 0; i < A_LOADS; i++)
+      if (lrow + 64 * i < BM) ra[i] = gather_chunk(rp[i], g, ks * 4 + cc);
+    if (!BT) {
+#pragma unroll
+      for (int i = 0; i < B_LOADS; i++) {
+        int r = lrow + 64 * i;
+        int n = n0 + r;
+        int q = ks * 4 + cc;
+        rb[i] = make_uint4(0, 0, 0, 0);
+        if (r < BN && n < g.Ncols && q * 8 < g.ldb) rb[i] = *reinterpret_cast<const uint4*>(Bm + (int64_t)n * g.ldb + q * 8);
+      }
+    } else {
+      constexpr int CPR = BN / 8;   // chunks per tile row
+#pragma unroll
+      for (int i = 0; i < B_LOADS; i++) {
+        int idx = tid + 256 * i;
+        int r = idx / CPR, ch = idx % CPR;
+        int k = ks * BK + r, n = n0 + ch * 8;
+        rb[i] = make_uint4(0, 0, 0, 0);
+        if (r < BK && k < g.Kchunks * 8 && n < g.Ncols) rb[i] = *reinterpret_cast<const uint4*>(Bm + (int64_t)k * g.ldb + n);
+      }
+    }
+  };
+  auto store_lds = [&](int buf) {
+    bf16_t* A = lds + buf * (A_ELEMS + B_ELEMS);
+    bf16_t* B = A + A_ELEMS;
+#pragma unroll
+    for (int i = 0; i < A_LOADS; i++)
+      if (lrow + 64 * i < BM) *reinterpret_cast<uint4*>(A + (lrow + 64 * i) * LDA + cc * 8) = ra[i];
+    if (!BT) {
+#pragma unroll
+      for (int i = 0; i < B_LOADS; i++)
+        if (lrow + 64 * i < BN) *reinterpret_cast<uint4*>(B + (lrow + 64 * i) * LDA + cc * 8) = rb[i];
+    } else {
+      constexpr int CPR = BN / 8;
+#pragma unroll
+      for (int i = 0; i < B_LOADS; i++) {
+        int idx = tid + 256 * i;
+        int r = idx / CPR, ch = idx % CPR;
+        if (r < BK) *reinterpret_cast<uint4*>(B + r * LDBT + ch * 8) = rb[i];
+      }
+    }
+  };
+
+  floatx16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; i++)
+#pragma unroll
+    for (int j = 0; j < TN; j++)
+#pragma unroll
+      for (int r = 0; r < 16; r++) acc[i][j][r] = 0.f;
+
+  const int ksteps = (g.Kchunks + 3) / 4;
+  load_regs(0);
+  store_lds(0);
+  __syncthreads();
+  for (int ks = 0; ks < ksteps; ks++) {
+    const int buf = ks & 1;
+    if (ks + 1 < ksteps) load_regs(ks + 1);
+    const bf16_t* A = lds + buf * (A_ELEMS + B_ELEMS);
+    const bf16_t* B = A + A_ELEMS;
+#pragma unroll
+    for (int kk = 0; kk < 2; kk++) {
+      bf16x8 a[TM], b[TN];
+#pragma unroll
+      for (int i = 0; i < TM; i++)
+        a[i] = *reinterpret_cast<const bf16x8*>(A + (wm0 + 32 * i + (lane & 31)) * LDA + 16 * kk + 8 * (lane >> 5));
+      if (!BT) {
+#pragma unroll
+        for (int j = 0; j < TN; j++)
+          b[j] = *reinterpret_cast<const bf16x8*>(B + (wn0 + 32 * j + (lane & 31)) * LDA + 16 * kk + 8 * (lane >> 5));
+      } else {
+        // transpose load: lane j16 of a 16-lane group supplies the row k0 + j16/4, columns 4*(j16%4)..+3 and
+        // receives the four k values of column (lane%16) of the group's 16 columns
+        const int j16 = lane & 15, half = (lane >> 4) & 1, kb = 16 * kk + 8 * (lane >> 5);
+#pragma unroll
+        for (int j = 0; j < TN; j++) {
+          const bf16_t* p = B + (kb + (j16 >> 2)) * LDBT + wn0 + 32 * j + 16 * half + 4 * (j16 & 3);
+          union { bf16x8 v; shortx4 h[2]; } u;
+          u.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((shortx4 __attribute__((address_space(3)))*)(p));
+          u.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((shortx4 __attribute__((address_space(3)))*)(p + 4 * LDBT));
+          b[j] = u.v;
+        }
+      }
+#pragma unroll
+      for (int i = 0; i < TM; i++)
+#pragma unroll
+        for (int j = 0; j < TN; j++) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+    }
+    if (ks + 1 < ksteps) store_lds(buf ^ 1);
+    __syncthreads();
+  }
+
+  // epilogue: lane holds column n = l%32 and rows 8*(r/4) + 4*(l/32) + r%4 of every 32x32 block
+  bf16_t* out = (bf16_t*)ws.p[z] + ep.out_off;
+  const bf16_t* mask = (const bf16_t*)ws.p[z] + ep.mask_off;
+  const bf16_t* bias = (const bf16_t*)wts.p[z] + ep.bias_off;
+#pragma unroll
+  for (int j = 0; j < TN; j++) {
+    const int n = n0 + wn0 + 32 * j + (lane & 31);
+    if (n >= g.Ncols) continue;
+    const float bv = ep.has_bias ? bf2f(bias[n]) : 0.f;
+#pragma unroll
+    for (int i = 0; i < TM; i++)
+#pragma unroll
+      for (int r = 0; r < 16; r++) {
+        const int m = m0 + wm0 + 32 * i + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+        if (m >= g.M) continue;
+        float v = acc[i][j][r] + bv;
+        if (ep.relu) v = fmaxf(v, 0.f);
+        const int64_t o = (int64_t)m * g.Ncols + n;
+        if (ep.use_mask && !(bf2f(mask[o]) > 0.f)) v = 0.f;
+        if (ep.out_f32) reinterpret_cast<float*>(out)[o] = v;
+        else out[o] = f2bf(v);
+      }
+  }
+}
+
+template <int BM, int BN, int WM, int WN, bool BT>
+static void launch_igemm_t(const PtrTab& ws, const CPtrTab& wts, const IGemm& g, const Epilogue& ep, int count, hipStream_t s) {
+  dim3 grid((unsigned)((g.M + BM - 1) / BM), (unsigned)((g.Ncols + BN - 1) / BN), (unsigned)count);
+  hipLaunchKernelGGL((igemm_kernel<BM, BN, WM, WN, BT>), grid, dim3(256), 0, s, ws, wts, g, ep);
+}
+
+hipError_t launch_igemm(const PtrTab& ws, const CPtrTab& wts, const IGemm& g, const Epilogue& ep, bool b_transposed, int count,
+                        hipStream_t s) {
+  if (g.C % 8 || g.ldb % 8 || (b_transposed && g.Ncols % 8)) return hipErrorInvalidValue;
+  if (g.M <= 32) {
+    if (b_transposed) launch_igemm_t<32, 128, 32, 32, true>(ws, wts, g, ep, count, s);
+    else launch_igemm_t<32, 128, 32, 32, false>(ws, wts, g, ep, count, s);
+  } else if (g.Ncols <= 32) {
+    if (b_transposed) launch_igemm_t<128, 32, 32, 32, true>(ws, wts, g, ep, count, s);
+    else launch_igemm_t<128, 32, 32, 32, false>(ws, wts, g, ep, count, s);
+  } else if (g.Ncols <= 64) {
+    if (b_transposed) launch_igemm_t<128, 64, 64, 32, true>(ws, wts, g, ep, count, s);
+    else launch_igemm_t<128, 64, 64, 32, false>(ws, wts, g, ep, count, s);
+  } else {
+    if (b_transposed) launch_igemm_t<128, 128, 64, 64, true>(ws, wts, g, ep, count, s);
+    else launch_igemm_t<128, 128, 64, 64, false>(ws, wts, g, ep, count, s);
+  }
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ weight gradient
+// dW tile [BMG output channels][BNG im2col columns], contraction over output positions m in steps of 32.
+// dy tile  [32 m][BMG n]  and  im2col tile [32 m][BNG k]  are staged as they lie in memory (rows = m) and
+// read with the transpose load.  The result is scattered into the flat fp32 gradient through filter_src().
+template <int BMG, int BNG>
+__global__ __launch_bounds__(256) void igemm_wgrad_kernel(PtrTab ws, PtrTab grads, IGemm g, VConv v, size_t dy_off, int64_t w_off) {
+  constexpr int WMG = BMG / 2, WNG = BNG / 2;          // 2 x 2 wavefronts
+  constexpr int TM = WMG / 32, TN = WNG / 32;
+  constexpr int LDT_A = BMG + 32 - (BMG == 32 ? 32 : 0);
+  constexpr int LDT_B = BNG + 32 - (BNG == 32 ? 32 : 0);
+  constexpr int A_ELEMS = BK * LDT_A, B_ELEMS = BK * LDT_B;
+  __shared__ __attribute__((aligned(16))) bf16_t lds[2 * (A_ELEMS + B_ELEMS)];
+
+  const int z = blockIdx.z;
+  const bf16_t* x = (const bf16_t*)ws.p[z] + g.a_off;
+  const bf16_t* dy = (const bf16_t*)ws.p[z] + dy_off;
+  const int n0 = blockIdx.x * BMG, k0 = blockIdx.y * BNG;   // output-channel and im2col-column origins
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm0 = (wave >> 1) * WMG, wn0 = (wave & 1) * WNG;
+
+  constexpr int CPR_A = BMG / 8, CPR_B = BNG / 8;
+  constexpr int A_LOADS = (BK * CPR_A + 255) / 256, B_LOADS = (BK * CPR_B + 255) / 256;
+  uint4 ra[A_LOADS], rb[B_LOADS];
+  auto load_regs = [&](int ms) {
+#pragma unroll
+    for (int i = 0; i < A_LOADS; i++) {
+      int idx = tid + 256 * i;
+      int r = idx / CPR_A, ch = idx % CPR_A;
+      int m = ms * BK + r, n = n0 + ch * 8;
+      ra[i] = make_uint4(0, 0, 0, 0);
+      if (r < BK && m < g.M && n < g.Ncols) ra[i] = *reinterpret_cast<const uint4*>(dy + (int64_t)m * g.Ncols + n);
+    }
+#pragma unroll
+    for (int i = 0; i < B_LOADS; i++) {
+      int idx = tid + 256 * i;
+      int r = idx / CPR_B, ch = idx % CPR_B;
+      rb[i] = make_uint4(0, 0, 0, 0);
+      if (r < BK) {
+        RowPos rp = row_pos(x, g, ms * BK + r);
+        rb[i] = gather_chunk(rp, g, k0 / 8 + ch);
+      }
+    }
+  };
+  auto store_lds = [&](int buf) {
+    bf16_t* A = lds + buf * (A_ELEMS + B_ELEMS);
+    bf16_t* B = A + A_ELEMS;
+#pragma unroll
+    for (int i = 0; i < A_LOADS; i++) {
+      int idx = tid + 256 * i;
+      int r = idx / CPR_A, ch = idx % CPR_A;
+      if (r < BK) *reinterpret_cast<uint4*>(A + r * LDT_A + ch * 8) = ra[i];
+    }
+#pragma unroll
+    for (int i = 0; i < B_LOADS; i++) {
+      int idx = tid + 256 * i;
+      int r = idx / CPR_B, ch = idx % CPR_B;
+      if (r < BK) *reinterpret_cast<uint4*>(B + r * LDT_B + ch * 8) = rb[i];
+    }
+  };
+
+  floatx16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; i++)
+#pragma unroll
+    for (int j = 0; j < TN; j++)
+#pragma unroll
+      for (int r = 0; r < 16; r++) acc[i][j][r] = 0.f;
+
+  const int msteps = (g.M + BK - 1) / BK;
+  load_regs(0);
+  store_lds(0);
+  __syncthreads();
+  const int j16 = lane & 15, half = (lane >> 4) & 1;
+  for (int ms = 0; ms < msteps; ms++) {
+    const int buf = ms & 1;
+    if (ms + 1 < msteps) load_regs(ms + 1);
+    const bf16_t* A = lds + buf * (A_ELEMS + B_ELEMS);
+    const bf16_t* B = A + A_ELEMS;
+#pragma unroll
+    for (int kk = 0; kk < 2; kk++) {
+      const int kb = 16 * kk + 8 * (lane >> 5);
+      bf16x8 a[TM], b[TN];
+#pragma unroll
+      for (int i = 0; i < TM; i++) {
+        const bf16_t* p = A + (kb + (j16 >> 2)) * LDT_A + wm0 + 32 * i + 16 * half + 4 * (j16 & 3);
+        union { bf16x8 v; shortx4 h[2]; } u;
+        u.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((shortx4 __attribute__((address_space(3)))*)(p));
+        u.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((shortx4 __attribute__((address_space(3)))*)(p + 4 * LDT_A));
+        a[i] = u.v;
+      }
+#pragma unroll
+      for (int j = 0; j < TN; j++) {
+        const bf16_t* p = B + (kb + (j16 >> 2)) * LDT_B + wn0 + 32 * j + 16 * half + 4 * (j16 & 3);
+        union { bf16x8 v; shortx4 h[2]; } u;
+        u.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((shortx4 __attribute__((address_space(3)))*)(p));
+        u.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((shortx4 __attribute__((address_space(3)))*)(p + 4 * LDT_B));
+        b[j] = u.v;
+      }
+#pragma unroll
+      for (int i = 0; i < TM; i++)
+#pragma unroll
+        for (int j = 0; j < TN; j++) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+    }
+    if (ms + 1 < msteps) store_lds(buf ^ 1);
+    __syncthreads();
+  }
+
+  float* dw = (float*)grads.p[z] + w_off;
+#pragma unroll
+  for (int j = 0; j < TN; j++) {
+    const int k = k0 + wn0 + 32 * j + (lane & 31);       // im2col column = tap * C + cp
+    if (k >= g.Kchunks * 8) continue;
+    const int tap = k / g.C, cp = k - tap * g.C;
+#pragma unroll
+    for (int i = 0; i < TM; i++)
+#pragma unroll
+      for (int r = 0; r < 16; r++) {
+        const int n = n0 + wm0 + 32 * i + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+        if (n >= g.Ncols) continue;
+        const int64_t dst = filter_src(v, n, tap, cp);
+        if (dst >= 0) dw[dst] = acc[i][j][r];
+      }
+  }
+}
+
+hipError_t launch_igemm_wgrad(const PtrTab& ws, const PtrTab& grads, const IGemm& g, const VConv& v, size_t dy_off, int64_t w_off,
+                              int count, hipStream_t s) {
+  if (g.C % 8 || g.Ncols % 8) return hipErrorInvalidValue;
+  const int kcols = g.Kchunks * 8;
+  if (g.Ncols <= 32 && false) return hipErrorInvalidValue;
+  if (g.Ncols <= 64) {
+    dim3 grid((unsigned)((g.Ncols + 63) / 64), (unsigned)((kcols + 127) / 128), (unsigned)count);
+    hipLaunchKernelGGL((igemm_wgrad_kernel<64, 128>), grid, dim3(256), 0, s, ws, grads, g, v, dy_off, w_off);
+  } else {
+    dim3 grid((unsigned)((g.Ncols + 127) / 128), (unsigned)((kcols + 127) / 128), (unsigned)count);
+    hipLaunchKernelGGL((igemm_wgrad_kernel<128, 128>), grid, dim3(256), 0, s, ws, grads, g, v, dy_off, w_off);
+  }
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ bias gradient: db[n] = sum_m dy[m][n]
+// One workgroup per 64 output channels: lane = channel (coalesced 128-byte rows), the four wavefronts take
+// interleaved rows and are combined through LDS in a fixed order.
+__global__ __launch_bounds__(256) void bias_grad_kernel(PtrTab ws, PtrTab grads, size_t dy_off, int64_t b_off, int M, int Ncols) {
+  __shared__ float part[4][64];
+  const bf16_t* dy = (const bf16_t*)ws.p[blockIdx.z] + dy_off;
+  float* db = (float*)grads.p[blockIdx.z] + b_off;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int n = blockIdx.x * 64 + lane;
+  float acc = 0.f;
+  if (n < Ncols)
+    for (int m = wave; m < M; m += 4) acc += bf2f(dy[(int64_t)m * Ncols + n]);
+  part[wave][lane] = acc;
+  __syncthreads();
+  if (wave == 0 && n < Ncols) db[n] = (part[0][lane] + part[1][lane]) + (part[2][lane] + part[3][lane]);
+}
+
+hipError_t launch_bias_grad(const PtrTab& ws, const PtrTab& grads, size_t dy_off, int64_t b_off, int M, int Ncols, int count,
+                            hipStream_t s) {
+  dim3 grid((unsigned)((Ncols + 63) / 64), 1, (unsigned)count);
+  hipLaunchKernelGGL(bias_grad_kernel, grid, dim3(256), 0, s, ws, grads, dy_off, b_off, M, Ncols);
+  return hipGetLastError();
+}
+
+}  // namespace sasgd

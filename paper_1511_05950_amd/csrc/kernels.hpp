@@ -26,9 +26,51 @@ struct PoolShape {
   int N, C, H, W, OH, OW, ks, stride;
 };
 
+// Re-layout of the caller's images.  s2d == 1: NCHW fp32 -> NHWC with channels zero-padded to Cp.
+// s2d == s > 1 (space to depth): out[n][Y][X][(dy*s+dx)*C + c] = in[n][c][s*Y+dy][s*X+dx], zero outside the
+// image and in the padding channels; a stride-s convolution on the image is a stride-1 one on this tensor.
+struct InPack {
+  int C, H, W;      // source
+  int Cp, Hp, Wp;   // destination
+  int s2d;
+};
+
+// A convolution as the MFMA kernels see it (stride 1): C = effective (padded or space-to-depth) input
+// channels, ks = effective window, K = output channels; Creal / ksr describe the flat filter [K][Creal][ksr][ksr].
+struct VConv {
+  int C, ks, K, s2d, Creal, ksr;
+};
+
+// One implicit GEMM: D[m][n] = sum_k im2col(t)[m][k] * B(n, k).  t = NHWC tensor [*][H][W][C] at a_off (elements
+// of bf16 from the workspace base), output positions OH x OW, window ks, zero padding pad, stride 1.
+struct IGemm {
+  size_t a_off;
+  int64_t b_off;            // elements of bf16 from the learner's weight-version base
+  int M, Ncols;             // M = images * OH * OW
+  int H, W, C, OH, OW, ks, pad;
+  int Kchunks, CPT;         // ks*ks*C/8 and C/8
+  int ldb;                  // row length of B in elements
+};
+
+struct Epilogue {
+  size_t out_off, mask_off; // elements of bf16 from the workspace base
+  int64_t bias_off;         // elements of bf16 from the weight-version base
+  int has_bias, relu, use_mask, out_f32;
+};
+
 // is_bf16 selects T.  All offsets are in elements of T from the learner's workspace base, except where noted.
-hipError_t launch_pack_input(bool is_bf16, const CPtrTab& images, const PtrTab& ws, size_t out_off, int count, int N, int C,
-                             int H, int W, hipStream_t s);
+hipError_t launch_pack_input(bool is_bf16, const CPtrTab& images, const PtrTab& ws, size_t out_off, int count, int N,
+                             const InPack& ip, hipStream_t s);
+
+// ---- bf16 MFMA path (conv_mfma.hip)
+hipError_t launch_pack_filters(const void* flat, void* packed, const VConv& v, int64_t w_off, int64_t fwd_off, int64_t bwd_off,
+                               int Kp, int Kpt, bool want_bwd, hipStream_t s);
+hipError_t launch_igemm(const PtrTab& ws, const CPtrTab& wts, const IGemm& g, const Epilogue& ep, bool b_transposed, int count,
+                        hipStream_t s);
+hipError_t launch_igemm_wgrad(const PtrTab& ws, const PtrTab& grads, const IGemm& g, const VConv& v, size_t dy_off, int64_t w_off,
+                              int count, hipStream_t s);
+hipError_t launch_bias_grad(const PtrTab& ws, const PtrTab& grads, size_t dy_off, int64_t b_off, int M, int Ncols, int count,
+                            hipStream_t s);
 
 // y = conv(x, w) + b, optional ReLU.  w_off / b_off: element offsets into the learner's flat weight vector.
 // out_f32: y is stored as fp32 whatever T is (class scores).

@@ -16,26 +16,34 @@ static inline dim3 grid_for(int64_t total, int count, int cap = 4096) {
 
 // ------------------------------------------------------------------ input NCHW fp32 -> NHWC T
 template <typename T>
-__global__ __launch_bounds__(256) void pack_input_kernel(CPtrTab images, PtrTab ws, size_t out_off, int N, int C, int H, int W) {
+__global__ __launch_bounds__(256) void pack_input_kernel(CPtrTab images, PtrTab ws, size_t out_off, int N, InPack ip) {
   const float* in = (const float*)images.p[blockIdx.z];
   T* out = (T*)ws.p[blockIdx.z] + out_off;
-  const int64_t total = (int64_t)N * C * H * W;
+  const int64_t total = (int64_t)N * ip.Hp * ip.Wp * ip.Cp;
   for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
-    int c = (int)(i % C);
-    int64_t r = i / C;
-    int w = (int)(r % W);
-    r /= W;
-    int h = (int)(r % H);
-    int n = (int)(r / H);
-    stf(out + i, in[(((int64_t)n * C + c) * H + h) * W + w]);
+    int cp = (int)(i % ip.Cp);
+    int64_t r = i / ip.Cp;
+    int X = (int)(r % ip.Wp);
+    r /= ip.Wp;
+    int Y = (int)(r % ip.Hp);
+    int n = (int)(r / ip.Hp);
+    float v = 0.f;
+    if (ip.s2d == 1) {
+      if (cp < ip.C) v = in[(((int64_t)n * ip.C + cp) * ip.H + Y) * ip.W + X];
+    } else {
+      int g = cp / ip.C, c = cp % ip.C;
+      int h = ip.s2d * Y + g / ip.s2d, w = ip.s2d * X + g % ip.s2d;
+      if (g < ip.s2d * ip.s2d && h < ip.H && w < ip.W) v = in[(((int64_t)n * ip.C + c) * ip.H + h) * ip.W + w];
+    }
+    stf(out + i, v);
   }
 }
 
-hipError_t launch_pack_input(bool is_bf16, const CPtrTab& images, const PtrTab& ws, size_t out_off, int count, int N, int C, int H,
-                             int W, hipStream_t s) {
-  dim3 g = grid_for((int64_t)N * C * H * W, count);
-  if (is_bf16) hipLaunchKernelGGL(pack_input_kernel<bf16_t>, g, dim3(256), 0, s, images, ws, out_off, N, C, H, W);
-  else hipLaunchKernelGGL(pack_input_kernel<float>, g, dim3(256), 0, s, images, ws, out_off, N, C, H, W);
+hipError_t launch_pack_input(bool is_bf16, const CPtrTab& images, const PtrTab& ws, size_t out_off, int count, int N,
+                             const InPack& ip, hipStream_t s) {
+  dim3 g = grid_for((int64_t)N * ip.Cp * ip.Hp * ip.Wp, count);
+  if (is_bf16) hipLaunchKernelGGL(pack_input_kernel<bf16_t>, g, dim3(256), 0, s, images, ws, out_off, N, ip);
+  else hipLaunchKernelGGL(pack_input_kernel<float>, g, dim3(256), 0, s, images, ws, out_off, N, ip);
   return hipGetLastError();
 }
 

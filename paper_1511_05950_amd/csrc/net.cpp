@@ -3,6 +3,7 @@
 // forward and backward, every launch covering all listed learners at once.  ReLU layers are fused into the
 // operation that produces their input (its output is stored after the ReLU; the backward mask is applied
 // by whichever kernel produces the gradient of that tensor).
+#include <stdlib.h>
 #include <string.h>
 
 #include <vector>
@@ -23,6 +24,14 @@ struct Op {
   int64_t w_off = 0, b_off = 0;
   int in_t = 0, out_t = 0;     // tensor indices
   size_t arg_off = 0;          // byte offset of the max-pool argmax, from the workspace base
+  // bf16 MFMA path (conv / fc ops that qualify)
+  bool mfma = false;
+  VConv vc{};
+  IGemm gf{};                  // forward implicit GEMM
+  IGemm gd{};                  // input-gradient implicit GEMM
+  bool dgrad_bt = false;       // fc: B operand is the flat weight matrix read transposed
+  int64_t pack_fwd = -1, pack_bwd = -1;   // element offsets in the packed-filter region of a version slot
+  int Kp = 0, Kpt = 0;
 };
 
 struct Tensor {
@@ -40,6 +49,9 @@ struct Net {
   std::vector<Op> ops;
   std::vector<Tensor> tensors; // tensor 0 = re-laid-out input
   int inC = 0, inH = 0, inW = 0;
+  InPack inpack{};
+  size_t Ppad = 0;             // start of the packed-filter region inside a version slot (elements)
+  size_t pack_elems = 0;
   size_t grad_a = 0, grad_b = 0, grad_elems = 0;   // two gradient-activation buffers (element offsets)
   size_t ws_bytes = 0;
   void* ws[kMaxLearners] = {nullptr};
@@ -96,8 +108,27 @@ int net_create(const sasgd_config& cfg, Net** out, int64_t* out_P, size_t* out_p
     net->tensors.push_back(t);
     return (int)net->tensors.size() - 1;
   };
-  int cur = new_tensor((size_t)N * C * H * W);
+  // Input re-layout.  For bf16 compute the first convolution runs on the MFMA path when it can: its input is
+  // channel-padded to a multiple of 8 (stride 1) or space-to-depth transformed (stride s, no padding).
+  net->inpack = InPack{C, H, W, C, H, W, 1};
+  bool first_mfma = false;
+  if (net->bf16 && layers[0].kind == SASGD_CONV && layers[0].units % 8 == 0 && layers[0].window >= 1 && layers[0].stride >= 1 &&
+      getenv("SASGD_NO_MFMA") == nullptr) {
+    const sasgd_layer& L0 = layers[0];
+    if (L0.stride == 1) {
+      net->inpack.Cp = (C + 7) & ~7;
+      first_mfma = true;
+    } else if (L0.pad == 0 && L0.window <= H && L0.window <= W) {
+      const int sd = L0.stride;
+      net->inpack = InPack{C, H, W, (sd * sd * C + 7) & ~7, (H + sd - 1) / sd, (W + sd - 1) / sd, sd};
+      first_mfma = true;
+    }
+  }
+  int cur = new_tensor((size_t)N * net->inpack.Cp * net->inpack.Hp * net->inpack.Wp);
   bool flat = false;       // current tensor already in (C,H,W)-flattened order (after a flatten or an fc)
+  size_t pack_cursor = 0;
+  const bool allow_mfma = net->bf16 && getenv("SASGD_NO_MFMA") == nullptr;
+  auto round32 = [](int x) { return (x + 31) & ~31; };
   int64_t P = 0;
   size_t arg_bytes = 0;
   for (int li = 0; li < nl; li++) {
@@ -120,6 +151,30 @@ int net_create(const sasgd_config& cfg, Net** out, int64_t* out_P, size_t* out_p
       op.b_off = P;
       P += L.units;
       op.in_t = cur;
+      if (cur == 0 && first_mfma) {
+        const InPack& ip = net->inpack;
+        const int kse = (L.window + ip.s2d - 1) / ip.s2d;
+        op.mfma = true;
+        op.vc = VConv{ip.Cp, kse, L.units, ip.s2d, C, L.window};
+        op.gf = IGemm{0, 0, N * op.cs.OH * op.cs.OW, L.units, ip.Hp, ip.Wp, ip.Cp, op.cs.OH, op.cs.OW, kse, ip.s2d == 1 ? L.pad : 0,
+                      kse * kse * ip.Cp / 8, ip.Cp / 8, 0};
+        op.Kp = round32(kse * kse * ip.Cp);
+        op.pack_fwd = (int64_t)pack_cursor;
+        pack_cursor += (size_t)L.units * op.Kp;
+      } else if (cur != 0 && allow_mfma && L.stride == 1 && C % 8 == 0 && L.units % 8 == 0) {
+        op.mfma = true;
+        op.vc = VConv{C, L.window, L.units, 1, C, L.window};
+        op.gf = IGemm{0, 0, N * op.cs.OH * op.cs.OW, L.units, H, W, C, op.cs.OH, op.cs.OW, L.window, L.pad, L.window * L.window * C / 8,
+                      C / 8, 0};
+        op.gd = IGemm{0, 0, N * H * W, C, op.cs.OH, op.cs.OW, L.units, H, W, L.window, L.window - 1 - L.pad,
+                      L.window * L.window * L.units / 8, L.units / 8, 0};
+        op.Kp = round32(L.window * L.window * C);
+        op.Kpt = round32(L.window * L.window * L.units);
+        op.pack_fwd = (int64_t)pack_cursor;
+        pack_cursor += (size_t)L.units * op.Kp;
+        op.pack_bwd = (int64_t)pack_cursor;
+        pack_cursor += (size_t)C * op.Kpt;
+      }
       C = L.units; H = op.cs.OH; W = op.cs.OW;
       cur = op.out_t = new_tensor((size_t)N * C * H * W);
     } else if (L.kind == SASGD_MAXPOOL || L.kind == SASGD_AVGPOOL) {
@@ -149,6 +204,15 @@ int net_create(const sasgd_config& cfg, Net** out, int64_t* out_P, size_t* out_p
       op.b_off = P;
       P += L.units;
       op.in_t = cur;
+      if (cur != 0 && allow_mfma && in % 8 == 0 && L.units % 8 == 0 && op.w_off % 8 == 0) {
+        // fully connected: the flat weight matrix [out][in] is the B operand as it lies (forward), and is read
+        // transposed for the input gradient; no packed copy
+        op.mfma = true;
+        op.dgrad_bt = true;
+        op.vc = VConv{in, 1, L.units, 1, in, 1};
+        op.gf = IGemm{0, op.w_off, N, L.units, 1, 1, in, 1, 1, 1, 0, in / 8, in / 8, in};
+        op.gd = IGemm{0, op.w_off, N, in, 1, 1, L.units, 1, 1, 1, 0, L.units / 8, L.units / 8, in};
+      }
       C = L.units; H = 1; W = 1;
       flat = true;
       cur = op.out_t = new_tensor((size_t)N * C);
@@ -175,6 +239,18 @@ int net_create(const sasgd_config& cfg, Net** out, int64_t* out_P, size_t* out_p
     if (net->bf16) { new_tensor(net->tensors[(size_t)cur].elems); }   // room for the wider elements (tensor is last in the arena)
   }
   net->P = P;
+  net->Ppad = ((size_t)P + 63) & ~(size_t)63;
+  net->pack_elems = pack_cursor;
+  for (Op& op : net->ops) {
+    if (!op.mfma) continue;
+    const Tensor& ti = net->tensors[(size_t)op.in_t];
+    op.gf.a_off = ti.off;
+    if (!op.dgrad_bt) {
+      op.gf.b_off = (int64_t)(net->Ppad + (size_t)op.pack_fwd);
+      op.gf.ldb = op.Kp;
+      if (op.pack_bwd >= 0) { op.gd.b_off = (int64_t)(net->Ppad + (size_t)op.pack_bwd); op.gd.ldb = op.Kpt; }
+    }
+  }
   size_t maxe = 0;
   for (const Tensor& t : net->tensors) maxe = t.elems > maxe ? t.elems : maxe;
   net->grad_elems = (maxe + 63) & ~(size_t)63;
@@ -188,7 +264,7 @@ int net_create(const sasgd_config& cfg, Net** out, int64_t* out_P, size_t* out_p
   net->ws_bytes = bytes + 256;
   *out = net;
   *out_P = P;
-  *out_pack_elems = 0;
+  *out_pack_elems = net->pack_elems;
   return SASGD_OK;
 }
 
@@ -196,9 +272,17 @@ void net_destroy(Net* net) { delete net; }
 size_t net_workspace_bytes(const Net* net) { return net->ws_bytes; }
 void net_set_workspace(Net* net, int learner, void* ws) { net->ws[learner] = ws; }
 
-hipError_t net_prepare_version(Net*, const void*, void*, hipStream_t) { return hipSuccess; }
-
 #define TRY(x) do { hipError_t e__ = (x); if (e__ != hipSuccess) return e__; } while (0)
+
+// Derive the packed bf16 filters of every MFMA convolution from the flat bf16 copy of one weight version.
+hipError_t net_prepare_version(Net* net, const void* flat, void* packed, hipStream_t stream) {
+  for (const Op& op : net->ops) {
+    if (!op.mfma || op.pack_fwd < 0) continue;
+    TRY(launch_pack_filters(flat, packed, op.vc, op.w_off, op.pack_fwd, op.pack_bwd < 0 ? 0 : op.pack_bwd, op.Kp, op.Kpt,
+                            op.pack_bwd >= 0, stream));
+  }
+  return hipSuccess;
+}
 
 hipError_t net_calc_gradient(Net* net, const int* learners, const LearnerBind* binds, int count, float* out_loss_dev,
                              hipStream_t stream) {
@@ -216,12 +300,17 @@ hipError_t net_calc_gradient(Net* net, const int* learners, const LearnerBind* b
   const bool bf = net->bf16;
   const std::vector<Tensor>& T = net->tensors;
   // ---- forward
-  TRY(launch_pack_input(bf, imgs, ws, T[0].off, count, net->mu, net->inC, net->inH, net->inW, stream));
+  TRY(launch_pack_input(bf, imgs, ws, T[0].off, count, net->mu, net->inpack, stream));
   for (const Op& op : net->ops) {
     const size_t xi = T[(size_t)op.in_t].off, yo = T[(size_t)op.out_t].off;
     switch (op.kind) {
       case OP_CONV:
-        TRY(launch_conv_fwd_simple(bf, ws, wts, xi, yo, op.w_off, op.b_off, op.cs, op.relu, op.out_f32, count, stream));
+        if (op.mfma) {
+          Epilogue ep{yo, 0, op.b_off, 1, op.relu ? 1 : 0, 0, op.out_f32 ? 1 : 0};
+          TRY(launch_igemm(ws, wts, op.gf, ep, false, count, stream));
+        } else {
+          TRY(launch_conv_fwd_simple(bf, ws, wts, xi, yo, op.w_off, op.b_off, op.cs, op.relu, op.out_f32, count, stream));
+        }
         break;
       case OP_POOL_MAX:
       case OP_POOL_AVG:
@@ -242,8 +331,19 @@ hipError_t net_calc_gradient(Net* net, const int* learners, const LearnerBind* b
     const bool need_dx = op.in_t != 0;          // the network input needs no gradient
     switch (op.kind) {
       case OP_CONV:
-        TRY(launch_conv_wgrad_simple(bf, ws, grads, tin.off, dy, op.w_off, op.b_off, op.cs, count, stream));
-        if (need_dx) TRY(launch_conv_dgrad_simple(bf, ws, wts, dy, dx, op.w_off, op.cs, tin.relu, tin.off, count, stream));
+        if (op.mfma) {
+          TRY(launch_igemm_wgrad(ws, grads, op.gf, op.vc, dy, op.w_off, count, stream));
+          TRY(launch_bias_grad(ws, grads, dy, op.b_off, op.gf.M, op.gf.Ncols, count, stream));
+          if (need_dx) {
+            IGemm gd = op.gd;
+            gd.a_off = dy;
+            Epilogue ep{dx, tin.off, 0, 0, 0, tin.relu ? 1 : 0, 0};
+            TRY(launch_igemm(ws, wts, gd, ep, op.dgrad_bt, count, stream));
+          }
+        } else {
+          TRY(launch_conv_wgrad_simple(bf, ws, grads, tin.off, dy, op.w_off, op.b_off, op.cs, count, stream));
+          if (need_dx) TRY(launch_conv_dgrad_simple(bf, ws, wts, dy, dx, op.w_off, op.cs, tin.relu, tin.off, count, stream));
+        }
         break;
       case OP_POOL_MAX:
       case OP_POOL_AVG:

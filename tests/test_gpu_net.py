@@ -76,6 +76,10 @@ TINY = {
     "two_conv_max": wl.tiny_net(2, 12, 12, 3, conv=((3, 3, 1, 1), (4, 3, 1, 0)), pool="maxpool", fc_hidden=7),
     "stride4_nopad": wl.tiny_net(3, 23, 23, 4, conv=((5, 11, 4, 0),), pool="maxpool"),
     "wide": wl.tiny_net(5, 17, 13, 11, conv=((37, 3, 1, 1), (70, 3, 1, 1)), pool="maxpool", fc_hidden=33),
+    # shapes the bf16 MFMA kernels take (channel counts multiples of 8), with ragged tile edges
+    "mfma_pad3": wl.tiny_net(3, 13, 11, 8, conv=((16, 3, 1, 1), (24, 5, 1, 2)), pool="maxpool", fc_hidden=40),
+    "mfma_s2d": wl.tiny_net(3, 29, 27, 16, conv=((8, 7, 2, 0), (72, 3, 1, 0)), pool="avgpool", fc_hidden=136),
+    "mfma_s4": wl.tiny_net(3, 39, 39, 8, conv=((24, 11, 4, 0), (40, 3, 1, 1), (136, 3, 1, 1)), pool="maxpool", fc_hidden=264),
 }
 
 
