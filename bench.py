@@ -132,6 +132,64 @@ def bench_server(args):
     return out
 
 
+def bench_net(args, cfg_id):
+    """Whole hot path on BASELINE config 3 (CIFAR-shaped, bf16, 1-softsync) or 4 (AlexNet-shaped, bf16, 18-softsync):
+    one step = one server update = c calcGradients (batched launches) + sumGradients + applyUpdate."""
+    import numpy as np
+    import torch
+    import workloads as wl
+    from paper_1511_05950_amd import binding, driver
+
+    cfg = wl.config(cfg_id)
+    net, lam, mu, n, c = cfg["net"], cfg["lam"], cfg["mu"], cfg["n"], cfg["c"]
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    K = args.warmup + args.steps
+    rng = np.random.default_rng(wl.SEED0 + 1000 * cfg_id + 3)
+    hi = {3: 2, 4: 36}[cfg_id]
+    sched = rng.integers(0, hi + 1, size=(K, c)).astype(np.int32)
+    R = hi + 1
+    pool = min(cfg["n_images"], 4096)
+    pool -= pool % mu
+    X = torch.randn((pool,) + net["input"], device=dev, generator=torch.Generator(device=dev).manual_seed(cfg_id))
+    Y = torch.randint(0, net["classes"], (pool,), device=dev, dtype=torch.int32)
+    ctx = binding.Sasgd(lam, mu, n, R, net=net["name"], compute=cfg["compute"], alpha0=cfg["alpha0"], momentum=cfg["momentum"],
+                        weight_decay=cfg["weight_decay"], init_weights=cfg["weights"]())
+
+    def batch_of(i, l):
+        s0 = ((i * c + l) * mu) % pool
+        return X[s0:s0 + mu], Y[s0:s0 + mu]
+
+    driver.run_softsync(ctx, sched[:args.warmup], batch_of, lam)
+    torch.cuda.synchronize()
+    ctx.setProfiling(True)
+    t0 = time.perf_counter()
+    driver.run_softsync(ctx, sched[args.warmup:], batch_of, lam, first_update=args.warmup)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_g, n_g = ctx.phaseTime(0)
+    ms_u, n_u = ctx.phaseTime(1)
+    P = ctx.P
+    ctx.destroy()
+    images = args.steps * c * mu
+    flop_img = {3: 68.87424e6, 4: 6.585512448e9}[cfg_id]     # forward + backward MACs x 2 per image
+    t_grad = ms_g / n_g * 1e-3                                # one batched calcGradient (c learners), seconds
+    ach = c * mu * flop_img / t_grad / 1e12
+    out = {
+        "metric": "training images/sec per GPU", "value": round(images / dt, 1), "unit": "images/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(dt / args.steps * 1e3, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "BASELINE config %d: %s net, lambda=%d, mu=%d, %d-softsync (c=%d), bf16 compute, fp32 master"
+                               % (cfg_id, net["name"], lam, mu, n, c), "num_params": P},
+        "roofline": {"bound": "mfma", "kernel": "calcGradient (all launches of one batched call)", "achieved": round(ach, 2),
+                     "peak": 2500.0, "unit": "TFLOP/s", "frac": round(ach / 2500.0, 5), "traffic": None,
+                     "avg_call_us": round(t_grad * 1e6, 1)},
+        "applyUpdate": {"avg_launch_us": round(ms_u / n_u * 1e3, 2), "bytes_per_launch": P * (4 * c + 18),
+                        "achieved_GBs": round(P * (4 * c + 18) / (ms_u / n_u * 1e-3) / 1e9, 1)},
+    }
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -148,6 +206,8 @@ def main():
         sys.exit(2)
     if args.workload == "server":
         out = bench_server(args)
+    elif args.workload in ("cifar", "alex"):
+        out = bench_net(args, 3 if args.workload == "cifar" else 4)
     else:
         raise SystemExit("unknown workload " + args.workload)
     print(json.dumps(out))

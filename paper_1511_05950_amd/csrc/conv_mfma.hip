@@ -129,7 +129,7 @@ __global__ __launch_bounds__(256) void igemm_kernel(PtrTab ws, CPtrTab wts, IGem
   constexpr int B_ELEMS = BT ? BK * LDBT : BN * LDA;
   __shared__ __attribute__((aligned(16))) bf16_t lds[2 * (A_ELEMS + B_ELEMS)];
 
-  const int z = blockIdx.z;
+  const int z = blockIdx.z / g.splits, sp = blockIdx.z % g.splits;
   const bf16_t* act = (const bf16_t*)ws.p[z] + g.a_off;
   const bf16_t* Bm = (const bf16_t*)wts.p[z] + g.b_off;
   const int m0 = blockIdx.x * BM, n0 = blockIdx.y * BN;
@@ -199,11 +199,16 @@ __global__ __launch_bounds__(256) void igemm_kernel(PtrTab ws, CPtrTab wts, IGem
 #pragma unroll
       for (int r = 0; r < 16; r++) acc[i][j][r] = 0.f;
 
-  const int ksteps = (g.Kchunks + 3) / 4;
-  load_regs(0);
-  store_lds(0);
+  const int all_steps = (g.Kchunks + 3) / 4;
+  const int per = (all_steps + g.splits - 1) / g.splits;
+  const int ks_begin = sp * per;
+  const int ksteps = min(all_steps, ks_begin + per);
+  if (ks_begin < ksteps) {
+    load_regs(ks_begin);
+    store_lds(ks_begin & 1);
+  }
   __syncthreads();
-  for (int ks = 0; ks < ksteps; ks++) {
+  for (int ks = ks_begin; ks < ksteps; ks++) {
     const int buf = ks & 1;
     if (ks + 1 < ksteps) load_regs(ks + 1);
     const bf16_t* A = lds + buf * (A_ELEMS + B_ELEMS);
@@ -241,6 +246,22 @@ __global__ __launch_bounds__(256) void igemm_kernel(PtrTab ws, CPtrTab wts, IGem
   }
 
   // epilogue: lane holds column n = l%32 and rows 8*(r/4) + 4*(l/32) + r%4 of every 32x32 block
+  if (g.splits > 1) {   // raw fp32 partial tile; igemm_finish_kernel adds the splits and applies the epilogue
+    float* part = reinterpret_cast<float*>((char*)ws.p[z] + g.scratch_off) + (int64_t)sp * g.M * g.Ncols;
+#pragma unroll
+    for (int j = 0; j < TN; j++) {
+      const int n = n0 + wn0 + 32 * j + (lane & 31);
+      if (n >= g.Ncols) continue;
+#pragma unroll
+      for (int i = 0; i < TM; i++)
+#pragma unroll
+        for (int r = 0; r < 16; r++) {
+          const int m = m0 + wm0 + 32 * i + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+          if (m < g.M) part[(int64_t)m * g.Ncols + n] = acc[i][j][r];
+        }
+    }
+    return;
+  }
   bf16_t* out = (bf16_t*)ws.p[z] + ep.out_off;
   const bf16_t* mask = (const bf16_t*)ws.p[z] + ep.mask_off;
   const bf16_t* bias = (const bf16_t*)wts.p[z] + ep.bias_off;
@@ -265,15 +286,48 @@ __global__ __launch_bounds__(256) void igemm_kernel(PtrTab ws, CPtrTab wts, IGem
   }
 }
 
+// Sum of the split partials in split order, then bias / ReLU / mask / conversion.
+__global__ __launch_bounds__(256) void igemm_finish_kernel(PtrTab ws, CPtrTab wts, IGemm g, Epilogue ep) {
+  const int z = blockIdx.z;
+  const float* part = reinterpret_cast<const float*>((const char*)ws.p[z] + g.scratch_off);
+  bf16_t* out = (bf16_t*)ws.p[z] + ep.out_off;
+  const bf16_t* mask = (const bf16_t*)ws.p[z] + ep.mask_off;
+  const bf16_t* bias = (const bf16_t*)wts.p[z] + ep.bias_off;
+  const int64_t total = (int64_t)g.M * g.Ncols;
+  for (int64_t o = (int64_t)blockIdx.x * 256 + threadIdx.x; o < total; o += (int64_t)gridDim.x * 256) {
+    float v = 0.f;
+    for (int sp = 0; sp < g.splits; sp++) v += part[(int64_t)sp * total + o];
+    if (ep.has_bias) v += bf2f(bias[o % g.Ncols]);
+    if (ep.relu) v = fmaxf(v, 0.f);
+    if (ep.use_mask && !(bf2f(mask[o]) > 0.f)) v = 0.f;
+    if (ep.out_f32) reinterpret_cast<float*>(out)[o] = v;
+    else out[o] = f2bf(v);
+  }
+}
+
+int choose_splits(int64_t tiles, int count, int steps, size_t bytes_per_split, size_t scratch_bytes) {
+  const int64_t target = 1024;                       // about four workgroups per compute unit
+  int64_t sp = (target + tiles * count - 1) / (tiles * count);
+  if (sp > steps / 4) sp = steps / 4;                // keep at least four contraction steps per workgroup
+  if (bytes_per_split > 0 && (int64_t)(scratch_bytes / bytes_per_split) < sp) sp = (int64_t)(scratch_bytes / bytes_per_split);
+  if (sp > 64) sp = 64;
+  return sp < 2 ? 1 : (int)sp;
+}
+
 template <int BM, int BN, int WM, int WN, bool BT>
 static void launch_igemm_t(const PtrTab& ws, const CPtrTab& wts, const IGemm& g, const Epilogue& ep, int count, hipStream_t s) {
-  dim3 grid((unsigned)((g.M + BM - 1) / BM), (unsigned)((g.Ncols + BN - 1) / BN), (unsigned)count);
+  dim3 grid((unsigned)((g.M + BM - 1) / BM), (unsigned)((g.Ncols + BN - 1) / BN), (unsigned)(count * g.splits));
   hipLaunchKernelGGL((igemm_kernel<BM, BN, WM, WN, BT>), grid, dim3(256), 0, s, ws, wts, g, ep);
+  if (g.splits > 1) {
+    int64_t total = (int64_t)g.M * g.Ncols;
+    unsigned blocks = (unsigned)((total + 255) / 256 < 1024 ? (total + 255) / 256 : 1024);
+    hipLaunchKernelGGL(igemm_finish_kernel, dim3(blocks, 1, (unsigned)count), dim3(256), 0, s, ws, wts, g, ep);
+  }
 }
 
 hipError_t launch_igemm(const PtrTab& ws, const CPtrTab& wts, const IGemm& g, const Epilogue& ep, bool b_transposed, int count,
                         hipStream_t s) {
-  if (g.C % 8 || g.ldb % 8 || (b_transposed && g.Ncols % 8)) return hipErrorInvalidValue;
+  if (g.C % 8 || g.ldb % 8 || (b_transposed && g.Ncols % 8) || g.splits < 1) return hipErrorInvalidValue;
   if (g.M <= 32) {
     if (b_transposed) launch_igemm_t<32, 128, 32, 32, true>(ws, wts, g, ep, count, s);
     else launch_igemm_t<32, 128, 32, 32, false>(ws, wts, g, ep, count, s);
@@ -295,7 +349,8 @@ hipError_t launch_igemm(const PtrTab& ws, const CPtrTab& wts, const IGemm& g, co
 // dy tile  [32 m][BMG n]  and  im2col tile [32 m][BNG k]  are staged as they lie in memory (rows = m) and
 // read with the transpose load.  The result is scattered into the flat fp32 gradient through filter_src().
 template <int BMG, int BNG>
-__global__ __launch_bounds__(256) void igemm_wgrad_kernel(PtrTab ws, PtrTab grads, IGemm g, VConv v, size_t dy_off, int64_t w_off) {
+__global__ __launch_bounds__(256) void igemm_wgrad_kernel(PtrTab ws, PtrTab grads, IGemm g, VConv v, size_t dy_off, int64_t w_off,
+                                                          int64_t b_off) {
   constexpr int WMG = BMG / 2, WNG = BNG / 2;          // 2 x 2 wavefronts
   constexpr int TM = WMG / 32, TN = WNG / 32;
   constexpr int LDT_A = BMG + 32 - (BMG == 32 ? 32 : 0);
@@ -303,7 +358,7 @@ __global__ __launch_bounds__(256) void igemm_wgrad_kernel(PtrTab ws, PtrTab grad
   constexpr int A_ELEMS = BK * LDT_A, B_ELEMS = BK * LDT_B;
   __shared__ __attribute__((aligned(16))) bf16_t lds[2 * (A_ELEMS + B_ELEMS)];
 
-  const int z = blockIdx.z;
+  const int z = blockIdx.z / g.splits, sp = blockIdx.z % g.splits;
   const bf16_t* x = (const bf16_t*)ws.p[z] + g.a_off;
   const bf16_t* dy = (const bf16_t*)ws.p[z] + dy_off;
   const int n0 = blockIdx.x * BMG, k0 = blockIdx.y * BNG;   // output-channel and im2col-column origins
@@ -328,8 +383,13 @@ __global__ __launch_bounds__(256) void igemm_wgrad_kernel(PtrTab ws, PtrTab grad
       int r = idx / CPR_B, ch = idx % CPR_B;
       rb[i] = make_uint4(0, 0, 0, 0);
       if (r < BK) {
-        RowPos rp = row_pos(x, g, ms * BK + r);
-        rb[i] = gather_chunk(rp, g, k0 / 8 + ch);
+        const int q = k0 / 8 + ch;
+        if (q == g.Kchunks) {            // the bias column: im2col value 1 for every real output position
+          if (ms * BK + r < g.M) rb[i].x = 0x3F80u;
+        } else {
+          RowPos rp = row_pos(x, g, ms * BK + r);
+          rb[i] = gather_chunk(rp, g, q);
+        }
       }
     }
   };
@@ -358,12 +418,17 @@ __global__ __launch_bounds__(256) void igemm_wgrad_kernel(PtrTab ws, PtrTab grad
 #pragma unroll
       for (int r = 0; r < 16; r++) acc[i][j][r] = 0.f;
 
-  const int msteps = (g.M + BK - 1) / BK;
-  load_regs(0);
-  store_lds(0);
+  const int all_steps = (g.M + BK - 1) / BK;
+  const int per = (all_steps + g.splits - 1) / g.splits;
+  const int ms_begin = sp * per;
+  const int msteps = min(all_steps, ms_begin + per);
+  if (ms_begin < msteps) {
+    load_regs(ms_begin);
+    store_lds(ms_begin & 1);
+  }
   __syncthreads();
   const int j16 = lane & 15, half = (lane >> 4) & 1;
-  for (int ms = 0; ms < msteps; ms++) {
+  for (int ms = ms_begin; ms < msteps; ms++) {
     const int buf = ms & 1;
     if (ms + 1 < msteps) load_regs(ms + 1);
     const bf16_t* A = lds + buf * (A_ELEMS + B_ELEMS);
@@ -397,11 +462,30 @@ __global__ __launch_bounds__(256) void igemm_wgrad_kernel(PtrTab ws, PtrTab grad
     __syncthreads();
   }
 
+  const int kcols = g.Kchunks * 8;
+  if (g.splits > 1) {   // fp32 partial [split][n][kcols + 8]; wgrad_finish_kernel adds and scatters
+    const int ldk = kcols + 8;
+    float* part = reinterpret_cast<float*>((char*)ws.p[z] + g.scratch_off) + (int64_t)sp * g.Ncols * ldk;
+#pragma unroll
+    for (int j = 0; j < TN; j++) {
+      const int k = k0 + wn0 + 32 * j + (lane & 31);
+      if (k > kcols) continue;
+#pragma unroll
+      for (int i = 0; i < TM; i++)
+#pragma unroll
+        for (int r = 0; r < 16; r++) {
+          const int n = n0 + wm0 + 32 * i + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+          if (n < g.Ncols) part[(int64_t)n * ldk + k] = acc[i][j][r];
+        }
+    }
+    return;
+  }
   float* dw = (float*)grads.p[z] + w_off;
+  float* db = (float*)grads.p[z] + b_off;
 #pragma unroll
   for (int j = 0; j < TN; j++) {
-    const int k = k0 + wn0 + 32 * j + (lane & 31);       // im2col column = tap * C + cp
-    if (k >= g.Kchunks * 8) continue;
+    const int k = k0 + wn0 + 32 * j + (lane & 31);       // im2col column = tap * C + cp; column kcols = bias
+    if (k > kcols) continue;
     const int tap = k / g.C, cp = k - tap * g.C;
 #pragma unroll
     for (int i = 0; i < TM; i++)
@@ -409,48 +493,47 @@ __global__ __launch_bounds__(256) void igemm_wgrad_kernel(PtrTab ws, PtrTab grad
       for (int r = 0; r < 16; r++) {
         const int n = n0 + wm0 + 32 * i + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
         if (n >= g.Ncols) continue;
+        if (k == kcols) { db[n] = acc[i][j][r]; continue; }
         const int64_t dst = filter_src(v, n, tap, cp);
         if (dst >= 0) dw[dst] = acc[i][j][r];
       }
   }
 }
 
-hipError_t launch_igemm_wgrad(const PtrTab& ws, const PtrTab& grads, const IGemm& g, const VConv& v, size_t dy_off, int64_t w_off,
-                              int count, hipStream_t s) {
-  if (g.C % 8 || g.Ncols % 8) return hipErrorInvalidValue;
-  const int kcols = g.Kchunks * 8;
-  if (g.Ncols <= 32 && false) return hipErrorInvalidValue;
-  if (g.Ncols <= 64) {
-    dim3 grid((unsigned)((g.Ncols + 63) / 64), (unsigned)((kcols + 127) / 128), (unsigned)count);
-    hipLaunchKernelGGL((igemm_wgrad_kernel<64, 128>), grid, dim3(256), 0, s, ws, grads, g, v, dy_off, w_off);
-  } else {
-    dim3 grid((unsigned)((g.Ncols + 127) / 128), (unsigned)((kcols + 127) / 128), (unsigned)count);
-    hipLaunchKernelGGL((igemm_wgrad_kernel<128, 128>), grid, dim3(256), 0, s, ws, grads, g, v, dy_off, w_off);
+__global__ __launch_bounds__(256) void wgrad_finish_kernel(PtrTab ws, PtrTab grads, IGemm g, VConv v, int64_t w_off, int64_t b_off) {
+  const int z = blockIdx.z;
+  const int kcols = g.Kchunks * 8, ldk = kcols + 8;
+  const float* part = reinterpret_cast<const float*>((const char*)ws.p[z] + g.scratch_off);
+  float* dw = (float*)grads.p[z] + w_off;
+  float* db = (float*)grads.p[z] + b_off;
+  const int64_t total = (int64_t)g.Ncols * (kcols + 1);
+  for (int64_t o = (int64_t)blockIdx.x * 256 + threadIdx.x; o < total; o += (int64_t)gridDim.x * 256) {
+    const int n = (int)(o / (kcols + 1)), k = (int)(o % (kcols + 1));
+    float acc = 0.f;
+    for (int sp = 0; sp < g.splits; sp++) acc += part[((int64_t)sp * g.Ncols + n) * ldk + k];
+    if (k == kcols) { db[n] = acc; continue; }
+    const int tap = k / g.C, cp = k - tap * g.C;
+    const int64_t dst = filter_src(v, n, tap, cp);
+    if (dst >= 0) dw[dst] = acc;
   }
-  return hipGetLastError();
 }
 
-// ------------------------------------------------------------------ bias gradient: db[n] = sum_m dy[m][n]
-// One workgroup per 64 output channels: lane = channel (coalesced 128-byte rows), the four wavefronts take
-// interleaved rows and are combined through LDS in a fixed order.
-__global__ __launch_bounds__(256) void bias_grad_kernel(PtrTab ws, PtrTab grads, size_t dy_off, int64_t b_off, int M, int Ncols) {
-  __shared__ float part[4][64];
-  const bf16_t* dy = (const bf16_t*)ws.p[blockIdx.z] + dy_off;
-  float* db = (float*)grads.p[blockIdx.z] + b_off;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int n = blockIdx.x * 64 + lane;
-  float acc = 0.f;
-  if (n < Ncols)
-    for (int m = wave; m < M; m += 4) acc += bf2f(dy[(int64_t)m * Ncols + n]);
-  part[wave][lane] = acc;
-  __syncthreads();
-  if (wave == 0 && n < Ncols) db[n] = (part[0][lane] + part[1][lane]) + (part[2][lane] + part[3][lane]);
-}
-
-hipError_t launch_bias_grad(const PtrTab& ws, const PtrTab& grads, size_t dy_off, int64_t b_off, int M, int Ncols, int count,
-                            hipStream_t s) {
-  dim3 grid((unsigned)((Ncols + 63) / 64), 1, (unsigned)count);
-  hipLaunchKernelGGL(bias_grad_kernel, grid, dim3(256), 0, s, ws, grads, dy_off, b_off, M, Ncols);
+hipError_t launch_igemm_wgrad(const PtrTab& ws, const PtrTab& grads, const IGemm& g, const VConv& v, size_t dy_off, int64_t w_off,
+                              int64_t b_off, int count, hipStream_t s) {
+  if (g.C % 8 || g.Ncols % 8 || g.splits < 1) return hipErrorInvalidValue;
+  const int cols = g.Kchunks * 8 + 1;          // im2col columns plus the bias column
+  if (g.Ncols <= 64) {
+    dim3 grid((unsigned)((g.Ncols + 63) / 64), (unsigned)((cols + 127) / 128), (unsigned)(count * g.splits));
+    hipLaunchKernelGGL((igemm_wgrad_kernel<64, 128>), grid, dim3(256), 0, s, ws, grads, g, v, dy_off, w_off, b_off);
+  } else {
+    dim3 grid((unsigned)((g.Ncols + 127) / 128), (unsigned)((cols + 127) / 128), (unsigned)(count * g.splits));
+    hipLaunchKernelGGL((igemm_wgrad_kernel<128, 128>), grid, dim3(256), 0, s, ws, grads, g, v, dy_off, w_off, b_off);
+  }
+  if (g.splits > 1) {
+    int64_t total = (int64_t)g.Ncols * cols;
+    unsigned blocks = (unsigned)((total + 255) / 256 < 2048 ? (total + 255) / 256 : 2048);
+    hipLaunchKernelGGL(wgrad_finish_kernel, dim3(blocks, 1, (unsigned)count), dim3(256), 0, s, ws, grads, g, v, w_off, b_off);
+  }
   return hipGetLastError();
 }
 

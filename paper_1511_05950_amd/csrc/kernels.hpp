@@ -50,6 +50,11 @@ struct IGemm {
   int H, W, C, OH, OW, ks, pad;
   int Kchunks, CPT;         // ks*ks*C/8 and C/8
   int ldb;                  // row length of B in elements
+  // Split of the contraction over `splits` workgroups per tile (fills the chip when there are few tiles):
+  // each writes an fp32 partial tile to scratch (byte offset from the workspace base), a second kernel adds
+  // them in split order and applies the epilogue, so the result does not depend on scheduling.
+  int splits;
+  size_t scratch_off;
 };
 
 struct Epilogue {
@@ -67,10 +72,11 @@ hipError_t launch_pack_filters(const void* flat, void* packed, const VConv& v, i
                                int Kp, int Kpt, bool want_bwd, hipStream_t s);
 hipError_t launch_igemm(const PtrTab& ws, const CPtrTab& wts, const IGemm& g, const Epilogue& ep, bool b_transposed, int count,
                         hipStream_t s);
+// dW and db of one layer (the bias gradient rides along as one extra im2col column of ones).
 hipError_t launch_igemm_wgrad(const PtrTab& ws, const PtrTab& grads, const IGemm& g, const VConv& v, size_t dy_off, int64_t w_off,
-                              int count, hipStream_t s);
-hipError_t launch_bias_grad(const PtrTab& ws, const PtrTab& grads, size_t dy_off, int64_t b_off, int M, int Ncols, int count,
-                            hipStream_t s);
+                              int64_t b_off, int count, hipStream_t s);
+// Split choice: enough workgroups for the chip, bounded by the contraction length and the scratch size.
+int choose_splits(int64_t tiles, int count, int steps, size_t bytes_per_split, size_t scratch_bytes);
 
 // y = conv(x, w) + b, optional ReLU.  w_off / b_off: element offsets into the learner's flat weight vector.
 // out_f32: y is stored as fp32 whatever T is (class scores).

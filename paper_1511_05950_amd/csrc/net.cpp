@@ -54,6 +54,7 @@ struct Net {
   size_t pack_elems = 0;
   size_t grad_a = 0, grad_b = 0, grad_elems = 0;   // two gradient-activation buffers (element offsets)
   size_t ws_bytes = 0;
+  size_t scratch_off = 0, scratch_bytes = 0;   // split-contraction partials (bytes from the workspace base)
   void* ws[kMaxLearners] = {nullptr};
 };
 
@@ -261,6 +262,23 @@ int net_create(const sasgd_config& cfg, Net** out, int64_t* out_P, size_t* out_p
   size_t bytes = (cursor * esz + 255) & ~(size_t)255;
   for (Op& op : net->ops) op.arg_off += bytes;
   bytes += arg_bytes;
+  // scratch for split contractions: room for 8 partial copies of the largest output, within 16..128 MiB
+  size_t need = 0;
+  for (const Op& op : net->ops) {
+    if (!op.mfma) continue;
+    size_t fwd = (size_t)op.gf.M * op.gf.Ncols * 4, wg = (size_t)op.gf.Ncols * (op.gf.Kchunks * 8 + 8) * 4;
+    size_t dg = (size_t)op.gd.M * op.gd.Ncols * 4;
+    need = fwd > need ? fwd : need;
+    need = wg > need ? wg : need;
+    need = dg > need ? dg : need;
+  }
+  if (need > 0) {
+    size_t sb = need * 8;
+    if (sb > ((size_t)128 << 20)) sb = need > ((size_t)128 << 20) ? need : ((size_t)128 << 20);
+    net->scratch_off = (bytes + 255) & ~(size_t)255;
+    net->scratch_bytes = sb;
+    bytes = net->scratch_off + sb;
+  }
   net->ws_bytes = bytes + 256;
   *out = net;
   *out_P = P;
@@ -282,6 +300,13 @@ hipError_t net_prepare_version(Net* net, const void* flat, void* packed, hipStre
                             op.pack_bwd >= 0, stream));
   }
   return hipSuccess;
+}
+
+static void set_splits(const Net* net, IGemm& g, int steps, int count) {
+  const int bm = g.M <= 32 ? 32 : 128, bn = g.M <= 32 ? 128 : (g.Ncols <= 32 ? 32 : (g.Ncols <= 64 ? 64 : 128));
+  const int64_t tiles = (int64_t)((g.M + bm - 1) / bm) * ((g.Ncols + bn - 1) / bn);
+  g.scratch_off = net->scratch_off;
+  g.splits = choose_splits(tiles, count, steps, (size_t)g.M * g.Ncols * 4, net->scratch_bytes);
 }
 
 hipError_t net_calc_gradient(Net* net, const int* learners, const LearnerBind* binds, int count, float* out_loss_dev,
@@ -307,7 +332,9 @@ hipError_t net_calc_gradient(Net* net, const int* learners, const LearnerBind* b
       case OP_CONV:
         if (op.mfma) {
           Epilogue ep{yo, 0, op.b_off, 1, op.relu ? 1 : 0, 0, op.out_f32 ? 1 : 0};
-          TRY(launch_igemm(ws, wts, op.gf, ep, false, count, stream));
+          IGemm gf = op.gf;
+          set_splits(net, gf, (gf.Kchunks + 3) / 4, count);
+          TRY(launch_igemm(ws, wts, gf, ep, false, count, stream));
         } else {
           TRY(launch_conv_fwd_simple(bf, ws, wts, xi, yo, op.w_off, op.b_off, op.cs, op.relu, op.out_f32, count, stream));
         }
@@ -332,11 +359,17 @@ hipError_t net_calc_gradient(Net* net, const int* learners, const LearnerBind* b
     switch (op.kind) {
       case OP_CONV:
         if (op.mfma) {
-          TRY(launch_igemm_wgrad(ws, grads, op.gf, op.vc, dy, op.w_off, count, stream));
-          TRY(launch_bias_grad(ws, grads, dy, op.b_off, op.gf.M, op.gf.Ncols, count, stream));
+          IGemm gw = op.gf;
+          {
+            const int64_t tiles = (int64_t)((gw.Ncols + 127) / 128) * ((gw.Kchunks * 8 + 1 + 127) / 128);
+            gw.scratch_off = net->scratch_off;
+            gw.splits = choose_splits(tiles, count, (gw.M + 31) / 32, (size_t)gw.Ncols * (gw.Kchunks * 8 + 8) * 4, net->scratch_bytes);
+          }
+          TRY(launch_igemm_wgrad(ws, grads, gw, op.vc, dy, op.w_off, op.b_off, count, stream));
           if (need_dx) {
             IGemm gd = op.gd;
             gd.a_off = dy;
+            set_splits(net, gd, (gd.Kchunks + 3) / 4, count);
             Epilogue ep{dx, tin.off, 0, 0, 0, tin.relu ? 1 : 0, 0};
             TRY(launch_igemm(ws, wts, gd, ep, op.dgrad_bt, count, stream));
           }

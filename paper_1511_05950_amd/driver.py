@@ -39,3 +39,48 @@ def run_softsync(ctx, schedule, batch_of, lam, loss_out=None, on_gradient=None, 
         ctx.sumGradients()
         ctx.applyUpdate()
     return log
+
+
+def run_softsync_batched(ctx, schedule, batch_of, lam, loss_out=None, first_update=0):
+    """Same run as run_softsync with calcGradient calls merged across updates.
+
+    The lambda learners of the paper work concurrently; a learner whose weights (version j) already exist can
+    compute before the update that will consume its gradient.  Whenever an update's gradients are not all
+    available, every gradient of the next lambda (one per learner) whose pulled version already exists is
+    computed in the same batched call.  Versions, timestamps and staleness are those of run_softsync; only the
+    grouping of kernel launches changes.  The ring must hold max(schedule) + 1 versions.
+    """
+    c = ctx.c
+    K = len(schedule)
+    done = {}                                   # gradient id -> (learner, timestamp j)
+    log = []
+    calls = 0
+    for k in range(K):
+        i = first_update + k
+        assert ctx.timestamp() == i
+        if any((k * c + l) not in done for l in range(c)):
+            learners = []
+            for g in range(k * c, min(K * c, k * c + lam)):
+                if g in done:
+                    continue
+                k2, l2 = divmod(g, c)
+                i2 = first_update + k2
+                j = i2 - min(int(schedule[k2][l2]), i2)
+                if j > i:
+                    continue                    # its weights do not exist yet
+                learner = (i2 * c + l2) % lam
+                x, y = batch_of(i2, l2)
+                ctx.getMinibatch(learner, x, y)
+                got = ctx.pullWeights(learner, i - j)
+                assert got == j
+                done[g] = (learner, j)
+                learners.append(learner)
+            ctx.calcGradient(learners, loss_out if len(learners) == c else None)
+            calls += 1
+        for l in range(c):
+            learner, j = done.pop(k * c + l)
+            tau = ctx.pushGradient(learner)
+            log.append((i, l, learner, j, tau))
+        ctx.sumGradients()
+        ctx.applyUpdate()
+    return log, calls

@@ -157,6 +157,89 @@ def test_config2_200_updates():
     assert rel(v, ref["v"]) < 1e-3
 
 
+def test_batched_driver_matches_plain_driver():
+    # merging calcGradient calls across updates must not change versions, staleness or (up to summation order) weights
+    from paper_1511_05950_amd import binding, driver
+    cfgd = wl.config(2)
+    net, lam, mu, n = cfgd["net"], cfgd["lam"], cfgd["mu"], cfgd["n"]
+    sched = cfgd["schedule"]()[:60]
+    X, Y, w0 = cfgd["images"](), cfgd["labels"](), cfgd["weights"]()
+    Xd, Yd = torch.from_numpy(X).cuda(), torch.from_numpy(Y).cuda()
+    bo = lambda i, l: (Xd[wl.batch_slice(cfgd, i, l)], Yd[wl.batch_slice(cfgd, i, l)])
+    out = []
+    for batched in (False, True):
+        ctx = binding.Sasgd(lam, mu, n, int(sched.max()) + 1, net=net, alpha0=cfgd["alpha0"], momentum=cfgd["momentum"], init_weights=w0)
+        if batched:
+            log, calls = driver.run_softsync_batched(ctx, sched, bo, lam)
+            assert calls < len(sched)
+        else:
+            log = driver.run_softsync(ctx, sched, bo, lam)
+        out.append((log, ctx.copyWeights()))
+        ctx.destroy()
+    assert out[0][0] == out[1][0]
+    assert rel(out[1][1] - w0, out[0][1] - w0) < 1e-5
+
+
+def cosine(a, b):
+    a = np.asarray(a, np.float64)
+    b = np.asarray(b, np.float64)
+    return float(a @ b / (np.linalg.norm(a) * np.linalg.norm(b)))
+
+
+def alex_gradient(net, netarg, w0, X, Y):
+    from paper_1511_05950_amd import binding
+    mu = X.shape[0]
+    ctx = binding.Sasgd(2, mu, 2, 1, net=netarg, compute="bf16", init_weights=w0)
+    loss = torch.zeros(1, device="cuda")
+    ctx.getMinibatch(1, torch.from_numpy(X).cuda(), torch.from_numpy(Y).cuda())
+    ctx.pullWeights(1, 0)
+    ctx.calcGradient([1], loss)
+    g = ctx.copyGradient(1)
+    ctx.destroy()
+    return g, float(loss.item())
+
+
+def test_alex8_shapes_smooth_variant_full_size():
+    """Every kernel of config 4 at its real shape (mu = 16, 3x224x224, 62.4 M parameters) on the decision-free
+    variant of the network (no ReLU, average pooling): bf16 compute must match the oracle to 2e-2 per tensor."""
+    net = wl.ALEX8_SMOOTH
+    w0 = wl.init_weights(net, wl.SEED0 + 4002, std=0.02)
+    X, Y = wl.images(net, 16, 77), wl.labels(net, 16, 78)
+    g, loss = alex_gradient(net, net, w0, X, Y)
+    rl, rg = cnn.loss_and_gradient(net, w0, X, Y, round_bf16=True)
+    worst, errs = layer_errors(net, g, rg)
+    print("alex8_smooth bf16 vs reduced-precision oracle:", ["%.1e" % e for e in errs])
+    assert worst < 2e-2, errs
+    el, eg = cnn.loss_and_gradient(net, w0, X, Y)
+    worst, errs = layer_errors(net, g, eg)
+    print("alex8_smooth bf16 vs exact oracle:", ["%.1e" % e for e in errs])
+    assert worst < 2e-2, errs
+    assert abs(loss - el) < 1e-3 * abs(el)
+
+
+def test_alex8_gradient_full_size():
+    """One learner step of BASELINE config 4 at full size.  With ReLU and max pooling in an eight-layer net the
+    bf16 gradient is reproducible only to a few per cent by ANY two evaluations that sum in a different order:
+    activations carry ~0.2 % quantisation noise, so ~0.2 % of the ReLU signs differ, and each flipped sign moves a
+    whole term of the weight-gradient sums (relative error ~ sqrt(fraction flipped)).  The oracle shows the same
+    spread between its own exact and reduced-precision modes (tests/test_oracle_cnn.py).  Checked here: the loss,
+    the last layer (no decision between it and the loss) at 2e-2, the rest at the flip-limited level."""
+    net = wl.ALEX8
+    cfgd = wl.config(4)
+    w0 = cfgd["weights"]()
+    X, Y = wl.images(net, cfgd["mu"], 77), wl.labels(net, cfgd["mu"], 78)
+    g, loss = alex_gradient(net, "alex8", w0, X, Y)
+    rl, rg = cnn.loss_and_gradient(net, w0, X, Y, round_bf16=True)
+    worst, errs = layer_errors(net, g, rg)
+    print("alex8 bf16 vs reduced-precision oracle:", ["%.1e" % e for e in errs])
+    assert abs(loss - rl) < 1e-5 * abs(rl)
+    assert errs[-2] < 2e-2 and errs[-1] < 2e-2           # fc8 weights and bias
+    assert worst < 1.5e-1 and cosine(g, rg) > 0.99, (errs, cosine(g, rg))
+    el, eg = cnn.loss_and_gradient(net, w0, X, Y)
+    print("alex8 bf16 vs exact oracle: whole gradient %.2e, cosine %.5f" % (rel(g, eg), cosine(g, eg)))
+    assert rel(g, eg) < 1.5e-1 and cosine(g, eg) > 0.99
+
+
 def test_learner_protocol_errors():
     from paper_1511_05950_amd import binding
     net = TINY["avg_clipped"]

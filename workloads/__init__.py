@@ -53,6 +53,16 @@ ALEX8 = {
 }
 
 
+# Same layer shapes as ALEX8 with every decision removed (no ReLU, average instead of max pooling): the loss is a
+# smooth function of the parameters, so reduced-precision runs can be compared at a tight tolerance at full size.
+ALEX8_SMOOTH = {
+    "name": "alex8_smooth",
+    "input": (3, 224, 224),
+    "classes": 1000,
+    "layers": [("avgpool", L[1], L[2]) if L[0] == "maxpool" else L for L in ALEX8["layers"] if L[0] != "relu"],
+}
+
+
 def tiny_net(c=3, h=9, w=7, classes=5, conv=((4, 3, 1, 1),), pool="maxpool", fc_hidden=None):
     """A small net for gradient checks: conv(s) -> pool -> relu -> [fc relu] -> fc."""
     layers = []
