@@ -45,37 +45,46 @@ __host__ __device__ inline int64_t filter_src(const VConv& v, int n, int tap, in
 }
 
 // ------------------------------------------------------------------ filter packing (once per weight version)
-// fwd:  Wp[n][tap][cp]            (row length Kp = padded ks*ks*C)
-// bwd:  Wt[c][tap'][n]            tap' = flipped tap, row length Kpt = padded ks*ks*K   (stride-1 layers only)
+// Filters are stored in MFMA operand ("fragment") order so that a wavefront fetches the B operand of one
+// 32x32x16 MFMA as one contiguous 1 KiB read, straight into registers:
+//   frag[(nb * KB16 + kb) * 512 + lane * 8 + t] = B[row 32 nb + lane%32][k = 16 kb + 8 (lane/32) + t]
+// fwd: B = Wp[n][tap][cp] (k = tap * C + cp, Kp = padded ks*ks*C);   rows beyond K and k beyond the filter are zero
+// bwd: B = Wt[c][tap'][n] (k = tap' * K + n, tap' = flipped tap, Kpt = padded ks*ks*K), stride-1 layers only
 __global__ __launch_bounds__(256) void pack_filters_kernel(const bf16_t* __restrict__ flat, bf16_t* __restrict__ packed, VConv v,
                                                            int64_t w_off, int64_t fwd_off, int64_t bwd_off, int Kp, int Kpt,
                                                            int want_bwd) {
-  const int64_t nf = (int64_t)v.K * Kp;
-  const int64_t nb = want_bwd ? (int64_t)v.C * Kpt : 0;
+  const int64_t nf = (int64_t)((v.K + 31) & ~31) * Kp;
+  const int64_t nb = want_bwd ? (int64_t)((v.C + 31) & ~31) * Kpt : 0;
   for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < nf + nb; i += (int64_t)gridDim.x * 256) {
-    if (i < nf) {
-      int n = (int)(i / Kp), k = (int)(i % Kp);
+    const bool fwd = i < nf;
+    const int64_t e = fwd ? i : i - nf;
+    const int KB16 = (fwd ? Kp : Kpt) / 16;
+    const int t = (int)(e & 7), lane = (int)((e >> 3) & 63);
+    const int64_t blk = e >> 9;
+    const int kb = (int)(blk % KB16), rb = (int)(blk / KB16);
+    const int row = 32 * rb + (lane & 31), k = 16 * kb + 8 * (lane >> 5) + t;
+    bf16_t val = 0;
+    if (fwd) {
       int tap = k / v.C, cp = k % v.C;
-      int64_t src = tap < v.ks * v.ks ? filter_src(v, n, tap, cp) : -1;
-      packed[fwd_off + i] = src >= 0 ? flat[w_off + src] : (bf16_t)0;
-    } else {
-      int64_t j = i - nf;
-      int c = (int)(j / Kpt), k = (int)(j % Kpt);
-      int tap = k / v.K, n = k % v.K;
-      bf16_t val = 0;
-      if (tap < v.ks * v.ks) {
-        int flipped = v.ks * v.ks - 1 - tap;            // (ks-1-kh, ks-1-kw)
-        int64_t src = filter_src(v, n, flipped, c);
+      if (row < v.K && tap < v.ks * v.ks) {
+        int64_t src = filter_src(v, row, tap, cp);
         if (src >= 0) val = flat[w_off + src];
       }
-      packed[bwd_off + j] = val;
+      packed[fwd_off + e] = val;
+    } else {
+      int tap = k / v.K, n = k % v.K;
+      if (row < v.C && tap < v.ks * v.ks) {
+        int64_t src = filter_src(v, n, v.ks * v.ks - 1 - tap, row);   // flipped tap (ks-1-kh, ks-1-kw)
+        if (src >= 0) val = flat[w_off + src];
+      }
+      packed[bwd_off + e] = val;
     }
   }
 }
 
 hipError_t launch_pack_filters(const void* flat, void* packed, const VConv& v, int64_t w_off, int64_t fwd_off, int64_t bwd_off,
                                int Kp, int Kpt, bool want_bwd, hipStream_t s) {
-  int64_t total = (int64_t)v.K * Kp + (want_bwd ? (int64_t)v.C * Kpt : 0);
+  int64_t total = (int64_t)((v.K + 31) & ~31) * Kp + (want_bwd ? (int64_t)((v.C + 31) & ~31) * Kpt : 0);
   int blocks = (int)((total + 255) / 256 < 2048 ? (total + 255) / 256 : 2048);
   hipLaunchKernelGGL(pack_filters_kernel, dim3(blocks), dim3(256), 0, s, (const bf16_t*)flat, (bf16_t*)packed, v, w_off, fwd_off,
                      bwd_off, Kp, Kpt, want_bwd ? 1 : 0);
@@ -286,6 +295,164 @@ __global__ __launch_bounds__(256) void igemm_kernel(PtrTab ws, CPtrTab wts, IGem
   }
 }
 
+// ------------------------------------------------------------------ convolution forward / dgrad, B from fragments
+// Same tiling as igemm_kernel, but only the gathered im2col tile goes through LDS; the filter operand comes
+// from the fragment-packed copy, one coalesced 1 KiB read per MFMA operand, prefetched one step ahead.  This
+// halves the LDS traffic per MFMA, which is what bounds the LDS-only variant.
+template <int BM, int BN, int WM, int WN>
+__global__ __launch_bounds__(256) void igemm_frag_kernel(PtrTab ws, CPtrTab wts, IGemm g, Epilogue ep) {
+  constexpr int WAVES_N = BN / WN;
+  constexpr int TM = WM / 32, TN = WN / 32;
+  constexpr int A_ELEMS = BM * LDA;
+  __shared__ __attribute__((aligned(16))) bf16_t lds[2 * A_ELEMS];
+
+  const int z = blockIdx.z / g.splits, sp = blockIdx.z % g.splits;
+  const bf16_t* act = (const bf16_t*)ws.p[z] + g.a_off;
+  const bf16_t* Bf = (const bf16_t*)wts.p[z] + g.b_off;
+  const int m0 = blockIdx.x * BM, n0 = blockIdx.y * BN;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm0 = (wave / WAVES_N) * WM, wn0 = (wave % WAVES_N) * WN;
+  const int KB16 = g.ldb / 16;
+  const int NB = (g.Ncols + 31) / 32;
+
+  constexpr int A_LOADS = (BM * 4 + 255) / 256;
+  const int cc = tid & 3, lrow = tid >> 2;
+  RowPos rp[A_LOADS];
+#pragma unroll
+  for (int i = 0; i < A_LOADS; i++) rp[i] = row_pos(act, g, m0 + lrow + 64 * i);
+
+  const int all_steps = (g.Kchunks + 3) / 4;
+  const int per = (all_steps + g.splits - 1) / g.splits;
+  const int ks_begin = sp * per;
+  const int ksteps = min(all_steps, ks_begin + per);
+
+  // running position of this thread's chunk q = 4 ks + cc inside the filter window
+  int q = ks_begin * 4 + cc;
+  int tap = q / g.CPT, c8 = q - tap * g.CPT;
+  int kh = tap / g.ks, kw = tap - kh * g.ks;
+  auto advance = [&]() {
+    q += 4;
+    c8 += 4;
+    while (c8 >= g.CPT) {
+      c8 -= g.CPT;
+      if (++kw == g.ks) { kw = 0; ++kh; }
+    }
+  };
+
+  uint4 ra[A_LOADS];
+  auto load_a = [&]() {
+    const int koff = (kh * g.W + kw) * g.C + c8 * 8;
+#pragma unroll
+    for (int i = 0; i < A_LOADS; i++) {
+      ra[i] = make_uint4(0, 0, 0, 0);
+      if (lrow + 64 * i < BM && rp[i].valid && q < g.Kchunks) {
+        const int ih = rp[i].oh + kh, iw = rp[i].ow + kw;
+        if (ih >= 0 && ih < g.H && iw >= 0 && iw < g.W) ra[i] = *reinterpret_cast<const uint4*>(rp[i].base + koff);
+      }
+    }
+  };
+  auto store_a = [&](int buf) {
+    bf16_t* A = lds + buf * A_ELEMS;
+#pragma unroll
+    for (int i = 0; i < A_LOADS; i++)
+      if (lrow + 64 * i < BM) *reinterpret_cast<uint4*>(A + (lrow + 64 * i) * LDA + cc * 8) = ra[i];
+  };
+  bf16x8 bn[2][TN];
+  auto load_b = [&](int ks) {
+#pragma unroll
+    for (int kk = 0; kk < 2; kk++)
+#pragma unroll
+      for (int j = 0; j < TN; j++) {
+        const int nb = (n0 + wn0) / 32 + j;
+        if (nb < NB) bn[kk][j] = *reinterpret_cast<const bf16x8*>(Bf + ((int64_t)nb * KB16 + ks * 2 + kk) * 512 + lane * 8);
+        else
+#pragma unroll
+          for (int t = 0; t < 8; t++) bn[kk][j][t] = 0;
+      }
+  };
+
+  floatx16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; i++)
+#pragma unroll
+    for (int j = 0; j < TN; j++)
+#pragma unroll
+      for (int r = 0; r < 16; r++) acc[i][j][r] = 0.f;
+
+  if (ks_begin < ksteps) {
+    load_a();
+    load_b(ks_begin);
+    store_a(ks_begin & 1);
+  }
+  __syncthreads();
+  for (int ks = ks_begin; ks < ksteps; ks++) {
+    const int buf = ks & 1;
+    bf16x8 bc[2][TN];
+#pragma unroll
+    for (int kk = 0; kk < 2; kk++)
+#pragma unroll
+      for (int j = 0; j < TN; j++) bc[kk][j] = bn[kk][j];
+    if (ks + 1 < ksteps) {
+      advance();
+      load_a();
+      load_b(ks + 1);
+    }
+    const bf16_t* A = lds + buf * A_ELEMS;
+#pragma unroll
+    for (int kk = 0; kk < 2; kk++) {
+      bf16x8 a[TM];
+#pragma unroll
+      for (int i = 0; i < TM; i++)
+        a[i] = *reinterpret_cast<const bf16x8*>(A + (wm0 + 32 * i + (lane & 31)) * LDA + 16 * kk + 8 * (lane >> 5));
+#pragma unroll
+      for (int i = 0; i < TM; i++)
+#pragma unroll
+        for (int j = 0; j < TN; j++) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], bc[kk][j], acc[i][j], 0, 0, 0);
+    }
+    if (ks + 1 < ksteps) store_a(buf ^ 1);
+    __syncthreads();
+  }
+
+  if (g.splits > 1) {
+    float* part = reinterpret_cast<float*>((char*)ws.p[z] + g.scratch_off) + (int64_t)sp * g.M * g.Ncols;
+#pragma unroll
+    for (int j = 0; j < TN; j++) {
+      const int n = n0 + wn0 + 32 * j + (lane & 31);
+      if (n >= g.Ncols) continue;
+#pragma unroll
+      for (int i = 0; i < TM; i++)
+#pragma unroll
+        for (int r = 0; r < 16; r++) {
+          const int m = m0 + wm0 + 32 * i + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+          if (m < g.M) part[(int64_t)m * g.Ncols + n] = acc[i][j][r];
+        }
+    }
+    return;
+  }
+  bf16_t* out = (bf16_t*)ws.p[z] + ep.out_off;
+  const bf16_t* mask = (const bf16_t*)ws.p[z] + ep.mask_off;
+  const bf16_t* bias = (const bf16_t*)wts.p[z] + ep.bias_off;
+#pragma unroll
+  for (int j = 0; j < TN; j++) {
+    const int n = n0 + wn0 + 32 * j + (lane & 31);
+    if (n >= g.Ncols) continue;
+    const float bv = ep.has_bias ? bf2f(bias[n]) : 0.f;
+#pragma unroll
+    for (int i = 0; i < TM; i++)
+#pragma unroll
+      for (int r = 0; r < 16; r++) {
+        const int m = m0 + wm0 + 32 * i + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+        if (m >= g.M) continue;
+        float v = acc[i][j][r] + bv;
+        if (ep.relu) v = fmaxf(v, 0.f);
+        const int64_t o = (int64_t)m * g.Ncols + n;
+        if (ep.use_mask && !(bf2f(mask[o]) > 0.f)) v = 0.f;
+        if (ep.out_f32) reinterpret_cast<float*>(out)[o] = v;
+        else out[o] = f2bf(v);
+      }
+  }
+}
+
 // Sum of the split partials in split order, then bias / ReLU / mask / conversion.
 __global__ __launch_bounds__(256) void igemm_finish_kernel(PtrTab ws, CPtrTab wts, IGemm g, Epilogue ep) {
   const int z = blockIdx.z;
@@ -323,6 +490,26 @@ static void launch_igemm_t(const PtrTab& ws, const CPtrTab& wts, const IGemm& g,
     unsigned blocks = (unsigned)((total + 255) / 256 < 1024 ? (total + 255) / 256 : 1024);
     hipLaunchKernelGGL(igemm_finish_kernel, dim3(blocks, 1, (unsigned)count), dim3(256), 0, s, ws, wts, g, ep);
   }
+}
+
+template <int BM, int BN, int WM, int WN>
+static void launch_frag_t(const PtrTab& ws, const CPtrTab& wts, const IGemm& g, const Epilogue& ep, int count, hipStream_t s) {
+  dim3 grid((unsigned)((g.M + BM - 1) / BM), (unsigned)((g.Ncols + BN - 1) / BN), (unsigned)(count * g.splits));
+  hipLaunchKernelGGL((igemm_frag_kernel<BM, BN, WM, WN>), grid, dim3(256), 0, s, ws, wts, g, ep);
+  if (g.splits > 1) {
+    int64_t total = (int64_t)g.M * g.Ncols;
+    unsigned blocks = (unsigned)((total + 255) / 256 < 1024 ? (total + 255) / 256 : 1024);
+    hipLaunchKernelGGL(igemm_finish_kernel, dim3(blocks, 1, (unsigned)count), dim3(256), 0, s, ws, wts, g, ep);
+  }
+}
+
+// Convolution forward / input gradient with fragment-packed filters (g.b_off points at the fragment copy).
+hipError_t launch_igemm_frag(const PtrTab& ws, const CPtrTab& wts, const IGemm& g, const Epilogue& ep, int count, hipStream_t s) {
+  if (g.C % 8 || g.ldb % 32 || g.splits < 1) return hipErrorInvalidValue;
+  if (g.Ncols <= 32) launch_frag_t<128, 32, 32, 32>(ws, wts, g, ep, count, s);
+  else if (g.Ncols <= 64) launch_frag_t<128, 64, 64, 32>(ws, wts, g, ep, count, s);
+  else launch_frag_t<128, 128, 64, 64>(ws, wts, g, ep, count, s);
+  return hipGetLastError();
 }
 
 hipError_t launch_igemm(const PtrTab& ws, const CPtrTab& wts, const IGemm& g, const Epilogue& ep, bool b_transposed, int count,

@@ -70,6 +70,7 @@ hipError_t launch_pack_input(bool is_bf16, const CPtrTab& images, const PtrTab& 
 // ---- bf16 MFMA path (conv_mfma.hip)
 hipError_t launch_pack_filters(const void* flat, void* packed, const VConv& v, int64_t w_off, int64_t fwd_off, int64_t bwd_off,
                                int Kp, int Kpt, bool want_bwd, hipStream_t s);
+hipError_t launch_igemm_frag(const PtrTab& ws, const CPtrTab& wts, const IGemm& g, const Epilogue& ep, int count, hipStream_t s);
 hipError_t launch_igemm(const PtrTab& ws, const CPtrTab& wts, const IGemm& g, const Epilogue& ep, bool b_transposed, int count,
                         hipStream_t s);
 // dW and db of one layer (the bias gradient rides along as one extra im2col column of ones).

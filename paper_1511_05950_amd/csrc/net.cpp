@@ -161,7 +161,7 @@ int net_create(const sasgd_config& cfg, Net** out, int64_t* out_P, size_t* out_p
                       kse * kse * ip.Cp / 8, ip.Cp / 8, 0};
         op.Kp = round32(kse * kse * ip.Cp);
         op.pack_fwd = (int64_t)pack_cursor;
-        pack_cursor += (size_t)L.units * op.Kp;
+        pack_cursor += (size_t)round32(L.units) * op.Kp;
       } else if (cur != 0 && allow_mfma && L.stride == 1 && C % 8 == 0 && L.units % 8 == 0) {
         op.mfma = true;
         op.vc = VConv{C, L.window, L.units, 1, C, L.window};
@@ -172,9 +172,9 @@ int net_create(const sasgd_config& cfg, Net** out, int64_t* out_P, size_t* out_p
         op.Kp = round32(L.window * L.window * C);
         op.Kpt = round32(L.window * L.window * L.units);
         op.pack_fwd = (int64_t)pack_cursor;
-        pack_cursor += (size_t)L.units * op.Kp;
+        pack_cursor += (size_t)round32(L.units) * op.Kp;
         op.pack_bwd = (int64_t)pack_cursor;
-        pack_cursor += (size_t)C * op.Kpt;
+        pack_cursor += (size_t)round32(C) * op.Kpt;
       }
       C = L.units; H = op.cs.OH; W = op.cs.OW;
       cur = op.out_t = new_tensor((size_t)N * C * H * W);
@@ -334,7 +334,8 @@ hipError_t net_calc_gradient(Net* net, const int* learners, const LearnerBind* b
           Epilogue ep{yo, 0, op.b_off, 1, op.relu ? 1 : 0, 0, op.out_f32 ? 1 : 0};
           IGemm gf = op.gf;
           set_splits(net, gf, (gf.Kchunks + 3) / 4, count);
-          TRY(launch_igemm(ws, wts, gf, ep, false, count, stream));
+          if (op.pack_fwd >= 0) TRY(launch_igemm_frag(ws, wts, gf, ep, count, stream));
+          else TRY(launch_igemm(ws, wts, gf, ep, false, count, stream));
         } else {
           TRY(launch_conv_fwd_simple(bf, ws, wts, xi, yo, op.w_off, op.b_off, op.cs, op.relu, op.out_f32, count, stream));
         }
@@ -371,7 +372,8 @@ hipError_t net_calc_gradient(Net* net, const int* learners, const LearnerBind* b
             gd.a_off = dy;
             set_splits(net, gd, (gd.Kchunks + 3) / 4, count);
             Epilogue ep{dx, tin.off, 0, 0, 0, tin.relu ? 1 : 0, 0};
-            TRY(launch_igemm(ws, wts, gd, ep, op.dgrad_bt, count, stream));
+            if (op.pack_bwd >= 0) TRY(launch_igemm_frag(ws, wts, gd, ep, count, stream));
+            else TRY(launch_igemm(ws, wts, gd, ep, op.dgrad_bt, count, stream));
           }
         } else {
           TRY(launch_conv_wgrad_simple(bf, ws, grads, tin.off, dy, op.w_off, op.b_off, op.cs, count, stream));
