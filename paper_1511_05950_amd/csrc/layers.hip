@@ -14,6 +14,22 @@ static inline dim3 grid_for(int64_t total, int count, int cap = 4096) {
   return dim3((unsigned)b, 1, (unsigned)count);
 }
 
+struct bf8 {
+  uint4 v;
+  __device__ __forceinline__ float get(int i) const {
+    uint32_t w = i < 2 ? v.x : (i < 4 ? v.y : (i < 6 ? v.z : v.w));
+    return __uint_as_float((i & 1) ? (w & 0xffff0000u) : (w << 16));
+  }
+};
+__device__ __forceinline__ uint4 pack8(const float* f) {
+  uint4 o;
+  o.x = (uint32_t)f2bf(f[0]) | ((uint32_t)f2bf(f[1]) << 16);
+  o.y = (uint32_t)f2bf(f[2]) | ((uint32_t)f2bf(f[3]) << 16);
+  o.z = (uint32_t)f2bf(f[4]) | ((uint32_t)f2bf(f[5]) << 16);
+  o.w = (uint32_t)f2bf(f[6]) | ((uint32_t)f2bf(f[7]) << 16);
+  return o;
+}
+
 // ------------------------------------------------------------------ input NCHW fp32 -> NHWC T
 template <typename T>
 __global__ __launch_bounds__(256) void pack_input_kernel(CPtrTab images, PtrTab ws, size_t out_off, int N, InPack ip) {
@@ -39,8 +55,46 @@ __global__ __launch_bounds__(256) void pack_input_kernel(CPtrTab images, PtrTab 
   }
 }
 
+// One lane per destination pixel (bf16, Cp % 8 == 0): the Cp channels are assembled in registers and written as
+// 16-byte chunks; neighbouring lanes read neighbouring source columns.
+__global__ __launch_bounds__(256) void pack_input_pixel_kernel(CPtrTab images, PtrTab ws, size_t out_off, int N, InPack ip) {
+  const float* in = (const float*)images.p[blockIdx.z];
+  bf16_t* out = (bf16_t*)ws.p[blockIdx.z] + out_off;
+  const int64_t total = (int64_t)N * ip.Hp * ip.Wp;
+  const int64_t plane = (int64_t)ip.H * ip.W;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
+    int X = (int)(i % ip.Wp);
+    int64_t r = i / ip.Wp;
+    int Y = (int)(r % ip.Hp);
+    int n = (int)(r / ip.Hp);
+    const float* src = in + (int64_t)n * ip.C * plane;
+    for (int c0 = 0; c0 < ip.Cp; c0 += 8) {
+      float f[8];
+#pragma unroll
+      for (int e = 0; e < 8; e++) {
+        const int cp = c0 + e;
+        float v = 0.f;
+        if (ip.s2d == 1) {
+          if (cp < ip.C) v = src[cp * plane + (int64_t)Y * ip.W + X];
+        } else {
+          int g = cp / ip.C, c = cp - g * ip.C;
+          int h = ip.s2d * Y + g / ip.s2d, w = ip.s2d * X + g % ip.s2d;
+          if (g < ip.s2d * ip.s2d && h < ip.H && w < ip.W) v = src[c * plane + (int64_t)h * ip.W + w];
+        }
+        f[e] = v;
+      }
+      *reinterpret_cast<uint4*>(out + i * ip.Cp + c0) = pack8(f);
+    }
+  }
+}
+
 hipError_t launch_pack_input(bool is_bf16, const CPtrTab& images, const PtrTab& ws, size_t out_off, int count, int N,
                              const InPack& ip, hipStream_t s) {
+  if (is_bf16 && ip.Cp % 8 == 0 && out_off % 8 == 0) {
+    dim3 gv = grid_for((int64_t)N * ip.Hp * ip.Wp, count, 16384);
+    hipLaunchKernelGGL(pack_input_pixel_kernel, gv, dim3(256), 0, s, images, ws, out_off, N, ip);
+    return hipGetLastError();
+  }
   dim3 g = grid_for((int64_t)N * ip.Cp * ip.Hp * ip.Wp, count);
   if (is_bf16) hipLaunchKernelGGL(pack_input_kernel<bf16_t>, g, dim3(256), 0, s, images, ws, out_off, N, ip);
   else hipLaunchKernelGGL(pack_input_kernel<float>, g, dim3(256), 0, s, images, ws, out_off, N, ip);
@@ -123,10 +177,125 @@ __global__ __launch_bounds__(256) void pool_bwd_kernel(PtrTab ws, size_t dy_off,
   }
 }
 
+// ------------------------------------------------------------------ pooling, 8 channels per lane (bf16, C % 8 == 0)
+// Same arithmetic as the scalar kernels; each lane moves 16-byte channel chunks, so a wavefront reads and
+// writes 1 KiB contiguous runs.
+template <bool MAX>
+__global__ __launch_bounds__(256) void pool_fwd_vec8_kernel(PtrTab ws, size_t x_off, size_t y_off, size_t arg_byte_off, PoolShape sh,
+                                                            int relu) {
+  const bf16_t* x = (const bf16_t*)ws.p[blockIdx.z] + x_off;
+  bf16_t* y = (bf16_t*)ws.p[blockIdx.z] + y_off;
+  uint8_t* arg = (uint8_t*)ws.p[blockIdx.z] + arg_byte_off;
+  const int C8 = sh.C / 8;
+  const int64_t total = (int64_t)sh.N * sh.OH * sh.OW * C8;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
+    int c8 = (int)(i % C8);
+    int64_t r = i / C8;
+    int ow = (int)(r % sh.OW);
+    r /= sh.OW;
+    int oh = (int)(r % sh.OH);
+    int n = (int)(r / sh.OH);
+    const int h0 = oh * sh.stride, w0 = ow * sh.stride;
+    float acc[8];
+    int best[8];
+#pragma unroll
+    for (int e = 0; e < 8; e++) { acc[e] = 0.f; best[e] = 0; }
+    int cnt = 0;
+    for (int kh = 0; kh < sh.ks && h0 + kh < sh.H; kh++)
+      for (int kw = 0; kw < sh.ks && w0 + kw < sh.W; kw++) {
+        bf8 v;
+        v.v = *reinterpret_cast<const uint4*>(x + (((int64_t)n * sh.H + h0 + kh) * sh.W + w0 + kw) * sh.C + c8 * 8);
+#pragma unroll
+        for (int e = 0; e < 8; e++) {
+          float f = v.get(e);
+          if (MAX) {
+            if (cnt == 0 || f > acc[e]) { acc[e] = f; best[e] = kh * sh.ks + kw; }
+          } else {
+            acc[e] += f;
+          }
+        }
+        cnt++;
+      }
+#pragma unroll
+    for (int e = 0; e < 8; e++) {
+      if (!MAX) acc[e] /= (float)cnt;
+      if (relu) acc[e] = fmaxf(acc[e], 0.f);
+    }
+    *reinterpret_cast<uint4*>(y + i * 8) = pack8(acc);
+    if (MAX) {
+      uint2 a;
+      a.x = (uint32_t)best[0] | ((uint32_t)best[1] << 8) | ((uint32_t)best[2] << 16) | ((uint32_t)best[3] << 24);
+      a.y = (uint32_t)best[4] | ((uint32_t)best[5] << 8) | ((uint32_t)best[6] << 16) | ((uint32_t)best[7] << 24);
+      *reinterpret_cast<uint2*>(arg + i * 8) = a;
+    }
+  }
+}
+
+template <bool MAX>
+__global__ __launch_bounds__(256) void pool_bwd_vec8_kernel(PtrTab ws, size_t dy_off, size_t dx_off, size_t arg_byte_off, PoolShape sh,
+                                                            int use_mask, size_t mask_off) {
+  const bf16_t* dy = (const bf16_t*)ws.p[blockIdx.z] + dy_off;
+  bf16_t* dx = (bf16_t*)ws.p[blockIdx.z] + dx_off;
+  const bf16_t* mask = (const bf16_t*)ws.p[blockIdx.z] + mask_off;
+  const uint8_t* arg = (const uint8_t*)ws.p[blockIdx.z] + arg_byte_off;
+  const int C8 = sh.C / 8;
+  const int64_t total = (int64_t)sh.N * sh.H * sh.W * C8;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
+    int c8 = (int)(i % C8);
+    int64_t r = i / C8;
+    int iw = (int)(r % sh.W);
+    r /= sh.W;
+    int ih = (int)(r % sh.H);
+    int n = (int)(r / sh.H);
+    float acc[8];
+#pragma unroll
+    for (int e = 0; e < 8; e++) acc[e] = 0.f;
+    int oh_lo = ih - sh.ks + 1 > 0 ? (ih - sh.ks + sh.stride) / sh.stride : 0;
+    int oh_hi = min(sh.OH - 1, ih / sh.stride);
+    int ow_lo = iw - sh.ks + 1 > 0 ? (iw - sh.ks + sh.stride) / sh.stride : 0;
+    int ow_hi = min(sh.OW - 1, iw / sh.stride);
+    for (int oh = oh_lo; oh <= oh_hi; oh++)
+      for (int ow = ow_lo; ow <= ow_hi; ow++) {
+        const int64_t o = ((((int64_t)n * sh.OH + oh) * sh.OW + ow) * C8 + c8) * 8;
+        bf8 d;
+        d.v = *reinterpret_cast<const uint4*>(dy + o);
+        if (MAX) {
+          const uint2 a = *reinterpret_cast<const uint2*>(arg + o);
+          const uint32_t pos = (uint32_t)((ih - oh * sh.stride) * sh.ks + (iw - ow * sh.stride));
+#pragma unroll
+          for (int e = 0; e < 8; e++) {
+            uint32_t ae = ((e < 4 ? a.x : a.y) >> (8 * (e & 3))) & 0xffu;
+            if (ae == pos) acc[e] += d.get(e);
+          }
+        } else {
+          int ch = min(oh * sh.stride + sh.ks, sh.H) - oh * sh.stride;
+          int cw = min(ow * sh.stride + sh.ks, sh.W) - ow * sh.stride;
+          const float inv = (float)(ch * cw);
+#pragma unroll
+          for (int e = 0; e < 8; e++) acc[e] += d.get(e) / inv;
+        }
+      }
+    if (use_mask) {
+      bf8 mk;
+      mk.v = *reinterpret_cast<const uint4*>(mask + i * 8);
+#pragma unroll
+      for (int e = 0; e < 8; e++)
+        if (!(mk.get(e) > 0.f)) acc[e] = 0.f;
+    }
+    *reinterpret_cast<uint4*>(dx + i * 8) = pack8(acc);
+  }
+}
+
 hipError_t launch_pool_fwd(bool is_bf16, bool is_max, const PtrTab& ws, size_t x_off, size_t y_off, size_t arg_byte_off,
                            const PoolShape& sh, bool relu, int count, hipStream_t s) {
   dim3 g = grid_for((int64_t)sh.N * sh.OH * sh.OW * sh.C, count);
   int r = relu ? 1 : 0;
+  if (is_bf16 && sh.C % 8 == 0 && x_off % 8 == 0 && y_off % 8 == 0 && arg_byte_off % 8 == 0) {
+    dim3 gv = grid_for((int64_t)sh.N * sh.OH * sh.OW * (sh.C / 8), count, 16384);
+    if (is_max) hipLaunchKernelGGL((pool_fwd_vec8_kernel<true>), gv, dim3(256), 0, s, ws, x_off, y_off, arg_byte_off, sh, r);
+    else hipLaunchKernelGGL((pool_fwd_vec8_kernel<false>), gv, dim3(256), 0, s, ws, x_off, y_off, arg_byte_off, sh, r);
+    return hipGetLastError();
+  }
   if (is_bf16) {
     if (is_max) hipLaunchKernelGGL((pool_fwd_kernel<bf16_t, true>), g, dim3(256), 0, s, ws, x_off, y_off, arg_byte_off, sh, r);
     else hipLaunchKernelGGL((pool_fwd_kernel<bf16_t, false>), g, dim3(256), 0, s, ws, x_off, y_off, arg_byte_off, sh, r);
@@ -141,6 +310,12 @@ hipError_t launch_pool_bwd(bool is_bf16, bool is_max, const PtrTab& ws, size_t d
                            const PoolShape& sh, bool use_mask, size_t mask_off, int count, hipStream_t s) {
   dim3 g = grid_for((int64_t)sh.N * sh.H * sh.W * sh.C, count);
   int um = use_mask ? 1 : 0;
+  if (is_bf16 && sh.C % 8 == 0 && dy_off % 8 == 0 && dx_off % 8 == 0 && arg_byte_off % 8 == 0 && mask_off % 8 == 0) {
+    dim3 gv = grid_for((int64_t)sh.N * sh.H * sh.W * (sh.C / 8), count, 16384);
+    if (is_max) hipLaunchKernelGGL((pool_bwd_vec8_kernel<true>), gv, dim3(256), 0, s, ws, dy_off, dx_off, arg_byte_off, sh, um, mask_off);
+    else hipLaunchKernelGGL((pool_bwd_vec8_kernel<false>), gv, dim3(256), 0, s, ws, dy_off, dx_off, arg_byte_off, sh, um, mask_off);
+    return hipGetLastError();
+  }
   if (is_bf16) {
     if (is_max) hipLaunchKernelGGL((pool_bwd_kernel<bf16_t, true>), g, dim3(256), 0, s, ws, dy_off, dx_off, arg_byte_off, sh, um, mask_off);
     else hipLaunchKernelGGL((pool_bwd_kernel<bf16_t, false>), g, dim3(256), 0, s, ws, dy_off, dx_off, arg_byte_off, sh, um, mask_off);
