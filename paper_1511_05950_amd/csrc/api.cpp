@@ -175,9 +175,13 @@ int sasgd_create(const sasgd_config* cfg, const float* init_weights, sasgd_ctx**
         L.grad = (float*)ctx_alloc(ctx, P * sizeof(float));
         L.workspace = ctx_alloc(ctx, ws);
         if (!L.grad || !L.workspace) { rc = fail(ctx, SASGD_ENOMEM, "learner buffers"); break; }
-        net_set_workspace(ctx->net, l, L.workspace);
+        // the workspace starts as zeros: the kernels rely on one never-written block of zeros inside it
+        hipError_t ez = net_set_workspace(ctx->net, l, L.workspace, ctx->stream);
+        if (ez != hipSuccess) { rc = fail_hip(ctx, ez, "clearing workspace"); break; }
       }
       if (rc != SASGD_OK) break;
+      hipError_t ez = hipStreamSynchronize(ctx->stream);
+      if (ez != hipSuccess) { rc = fail_hip(ctx, ez, "clearing workspace"); break; }
     }
   } while (0);
 

@@ -93,6 +93,16 @@ hipError_t launch_pack_filters(const void* flat, void* packed, const VConv& v, i
 
 // ------------------------------------------------------------------ im2col chunk gather
 // Row m of the virtual im2col matrix, chunk q (8 channels of one tap): 16 bytes from the NHWC tensor or zeros.
+// All loads are unconditional (an out-of-range chunk is read from a block of zeros kept in the workspace) and all
+// index arithmetic is branch-free, so the loops below are straight-line code: nothing touches a loaded value
+// before the MFMAs of the current step have been issued, and the compiler can wait on exactly the loads it needs
+// instead of draining the whole queue.
+__device__ __forceinline__ uint32_t fastdiv(uint32_t n, int d, uint32_t magic) { return d == 1 ? n : __umulhi(n, magic); }
+
+__device__ __forceinline__ uint4 ld16_or_zero(const bf16_t* p, bool ok, const bf16_t* zeros) {
+  return *reinterpret_cast<const uint4*>(ok ? p : zeros);
+}
+
 struct RowPos {
   const bf16_t* base;   // &t[n][oh - pad][ow - pad][0]  (may point outside; only dereferenced when in range)
   int oh, ow;           // already offset by -pad
@@ -102,26 +112,24 @@ struct RowPos {
 __device__ __forceinline__ RowPos row_pos(const bf16_t* t, const IGemm& g, int m) {
   RowPos r;
   r.valid = m < g.M;
-  int mm = r.valid ? m : 0;
-  int ow = mm % g.OW;
-  int rest = mm / g.OW;
-  int oh = rest % g.OH;
-  int n = rest / g.OH;
+  const uint32_t mm = r.valid ? (uint32_t)m : 0u;
+  const uint32_t rest = fastdiv(mm, g.OW, g.mg_ow);
+  const int ow = (int)(mm - rest * (uint32_t)g.OW);
+  const uint32_t n = fastdiv(rest, g.OH, g.mg_oh);
+  const int oh = (int)(rest - n * (uint32_t)g.OH);
   r.oh = oh - g.pad;
   r.ow = ow - g.pad;
   r.base = t + (((int64_t)n * g.H + r.oh) * g.W + r.ow) * g.C;
   return r;
 }
 
-__device__ __forceinline__ uint4 gather_chunk(const RowPos& r, const IGemm& g, int q) {
-  uint4 z = make_uint4(0, 0, 0, 0);
-  if (!r.valid || q >= g.Kchunks) return z;
-  int tap = q / g.CPT;
-  int c8 = q - tap * g.CPT;
-  int kh = tap / g.ks, kw = tap - kh * g.ks;
-  int ih = r.oh + kh, iw = r.ow + kw;
-  if (ih < 0 || ih >= g.H || iw < 0 || iw >= g.W) return z;
-  return *reinterpret_cast<const uint4*>(r.base + ((int64_t)kh * g.W + kw) * g.C + c8 * 8);
+__device__ __forceinline__ uint4 gather_chunk(const RowPos& r, const IGemm& g, int q, const bf16_t* zeros) {
+  const uint32_t tap = fastdiv((uint32_t)q, g.CPT, g.mg_cpt);
+  const int c8 = q - (int)tap * g.CPT;
+  const int kh = (int)fastdiv(tap, g.ks, g.mg_ks), kw = (int)tap - kh * g.ks;
+  const int ih = r.oh + kh, iw = r.ow + kw;
+  const bool ok = r.valid && q < g.Kchunks && (unsigned)ih < (unsigned)g.H && (unsigned)iw < (unsigned)g.W;
+  return ld16_or_zero(r.base + ((int64_t)kh * g.W + kw) * g.C + c8 * 8, ok, zeros);
 }
 
 // ------------------------------------------------------------------ forward / dgrad kernel
@@ -140,6 +148,7 @@ __global__ __launch_bounds__(256) void igemm_kernel(PtrTab ws, CPtrTab wts, IGem
 
   const int z = blockIdx.z / g.splits, sp = blockIdx.z % g.splits;
   const bf16_t* act = (const bf16_t*)ws.p[z] + g.a_off;
+  const bf16_t* zeros = (const bf16_t*)ws.p[z] + g.zero_off;
   const bf16_t* Bm = (const bf16_t*)wts.p[z] + g.b_off;
   const int m0 = blockIdx.x * BM, n0 = blockIdx.y * BN;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -156,26 +165,23 @@ __global__ __launch_bounds__(256) void igemm_kernel(PtrTab ws, CPtrTab wts, IGem
   uint4 ra[A_LOADS], rb[B_LOADS];
   auto load_regs = [&](int ks) {
 #pragma unroll
-    for (int i = 0; i < A_LOADS; i++)
-      if (lrow + 64 * i < BM) ra[i] = gather_chunk(rp[i], g, ks * 4 + cc);
+    for (int i = 0; i < A_LOADS; i++) ra[i] = gather_chunk(rp[i], g, ks * 4 + cc, zeros);
     if (!BT) {
 #pragma unroll
       for (int i = 0; i < B_LOADS; i++) {
-        int r = lrow + 64 * i;
-        int n = n0 + r;
-        int q = ks * 4 + cc;
-        rb[i] = make_uint4(0, 0, 0, 0);
-        if (r < BN && n < g.Ncols && q * 8 < g.ldb) rb[i] = *reinterpret_cast<const uint4*>(Bm + (int64_t)n * g.ldb + q * 8);
+        const int r = lrow + 64 * i;
+        const int n = n0 + r;
+        const int q = ks * 4 + cc;
+        rb[i] = ld16_or_zero(Bm + (int64_t)n * g.ldb + q * 8, r < BN && n < g.Ncols && q * 8 < g.ldb, zeros);
       }
     } else {
       constexpr int CPR = BN / 8;   // chunks per tile row
 #pragma unroll
       for (int i = 0; i < B_LOADS; i++) {
-        int idx = tid + 256 * i;
-        int r = idx / CPR, ch = idx % CPR;
-        int k = ks * BK + r, n = n0 + ch * 8;
-        rb[i] = make_uint4(0, 0, 0, 0);
-        if (r < BK && k < g.Kchunks * 8 && n < g.Ncols) rb[i] = *reinterpret_cast<const uint4*>(Bm + (int64_t)k * g.ldb + n);
+        const int idx = tid + 256 * i;
+        const int r = idx / CPR, ch = idx % CPR;
+        const int k = ks * BK + r, n = n0 + ch * 8;
+        rb[i] = ld16_or_zero(Bm + (int64_t)k * g.ldb + n, r < BK && k < g.Kchunks * 8 && n < g.Ncols, zeros);
       }
     }
   };
@@ -299,76 +305,89 @@ __global__ __launch_bounds__(256) void igemm_kernel(PtrTab ws, CPtrTab wts, IGem
 // Same tiling as igemm_kernel, but only the gathered im2col tile goes through LDS; the filter operand comes
 // from the fragment-packed copy, one coalesced 1 KiB read per MFMA operand, prefetched one step ahead.  This
 // halves the LDS traffic per MFMA, which is what bounds the LDS-only variant.
-template <int BM, int BN, int WM, int WN>
+typedef int v4i_t __attribute__((ext_vector_type(4)));
+constexpr uint32_t kOutOfRange = 0x80000000u;   // buffer offset beyond any tensor: the load returns zeros
+
+template <int BM, int BN, int WM, int WN, int BKT>
 __global__ __launch_bounds__(256) void igemm_frag_kernel(PtrTab ws, CPtrTab wts, IGemm g, Epilogue ep) {
   constexpr int WAVES_N = BN / WN;
   constexpr int TM = WM / 32, TN = WN / 32;
-  constexpr int A_ELEMS = BM * LDA;
+  constexpr int LDF = BKT + 8;                 // 80 or 144 byte rows: conflict-free 16-byte reads
+  constexpr int CPS = BKT / 8;                 // chunks per contraction step
+  constexpr int KK = BKT / 16;                 // MFMA k-blocks per step
+  constexpr int A_ELEMS = BM * LDF;
   __shared__ __attribute__((aligned(16))) bf16_t lds[2 * A_ELEMS];
 
   const int z = blockIdx.z / g.splits, sp = blockIdx.z % g.splits;
   const bf16_t* act = (const bf16_t*)ws.p[z] + g.a_off;
   const bf16_t* Bf = (const bf16_t*)wts.p[z] + g.b_off;
+  // Buffer resources: an offset at or beyond the size reads as zero in hardware, so padding taps, ragged rows
+  // and ragged columns need no branch, no select on the data and no 64-bit address arithmetic.
+  const __amdgpu_buffer_rsrc_t rsrc_a = __builtin_amdgcn_make_buffer_rsrc((void*)act, 0, (int)g.a_bytes, 0x00020000);
+  const __amdgpu_buffer_rsrc_t rsrc_b = __builtin_amdgcn_make_buffer_rsrc((void*)Bf, 0, (int)g.b_bytes, 0x00020000);
   const int m0 = blockIdx.x * BM, n0 = blockIdx.y * BN;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm0 = (wave / WAVES_N) * WM, wn0 = (wave % WAVES_N) * WN;
   const int KB16 = g.ldb / 16;
   const int NB = (g.Ncols + 31) / 32;
 
-  constexpr int A_LOADS = (BM * 4 + 255) / 256;
-  const int cc = tid & 3, lrow = tid >> 2;
-  RowPos rp[A_LOADS];
+  constexpr int A_LOADS = (BM * CPS + 255) / 256;
+  constexpr int RPP = 256 / CPS;               // tile rows covered per loader pass
+  const int cc = tid % CPS, lrow = tid / CPS;
+  // per tile row handled by this thread: byte offset of its window origin, and the origin's coordinates
+  int row_off[A_LOADS], row_oh[A_LOADS], row_ow[A_LOADS];
 #pragma unroll
-  for (int i = 0; i < A_LOADS; i++) rp[i] = row_pos(act, g, m0 + lrow + 64 * i);
+  for (int i = 0; i < A_LOADS; i++) {
+    const RowPos r = row_pos(act, g, m0 + lrow + RPP * i);
+    row_off[i] = (int)((r.base - act) * 2);
+    row_oh[i] = r.valid ? r.oh : -0x40000000;  // an invalid row fails every bounds test below
+    row_ow[i] = r.ow;
+  }
 
-  const int all_steps = (g.Kchunks + 3) / 4;
+  const int all_steps = (g.Kchunks + CPS - 1) / CPS;
   const int per = (all_steps + g.splits - 1) / g.splits;
   const int ks_begin = sp * per;
   const int ksteps = min(all_steps, ks_begin + per);
 
-  // running position of this thread's chunk q = 4 ks + cc inside the filter window
-  int q = ks_begin * 4 + cc;
-  int tap = q / g.CPT, c8 = q - tap * g.CPT;
-  int kh = tap / g.ks, kw = tap - kh * g.ks;
-  auto advance = [&]() {
-    q += 4;
-    c8 += 4;
-    while (c8 >= g.CPT) {
-      c8 -= g.CPT;
-      if (++kw == g.ks) { kw = 0; ++kh; }
-    }
-  };
-
-  uint4 ra[A_LOADS];
-  auto load_a = [&]() {
-    const int koff = (kh * g.W + kw) * g.C + c8 * 8;
+  v4i_t ra[A_LOADS];
+  auto load_a = [&](int ks) {
+    const int q = ks * CPS + cc;
+    const uint32_t tap = fastdiv((uint32_t)q, g.CPT, g.mg_cpt);
+    const int c8 = q - (int)tap * g.CPT;
+    const int kh = (int)fastdiv(tap, g.ks, g.mg_ks), kw = (int)tap - kh * g.ks;
+    const int koff = ((kh * g.W + kw) * g.C + c8 * 8) * 2;
+    const bool qok = q < g.Kchunks;
 #pragma unroll
     for (int i = 0; i < A_LOADS; i++) {
-      ra[i] = make_uint4(0, 0, 0, 0);
-      if (lrow + 64 * i < BM && rp[i].valid && q < g.Kchunks) {
-        const int ih = rp[i].oh + kh, iw = rp[i].ow + kw;
-        if (ih >= 0 && ih < g.H && iw >= 0 && iw < g.W) ra[i] = *reinterpret_cast<const uint4*>(rp[i].base + koff);
-      }
+      const bool ok = qok && (unsigned)(row_oh[i] + kh) < (unsigned)g.H && (unsigned)(row_ow[i] + kw) < (unsigned)g.W;
+      ra[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_a, ok ? (row_off[i] + koff) : (int)kOutOfRange, 0, 0);
     }
   };
   auto store_a = [&](int buf) {
     bf16_t* A = lds + buf * A_ELEMS;
 #pragma unroll
     for (int i = 0; i < A_LOADS; i++)
-      if (lrow + 64 * i < BM) *reinterpret_cast<uint4*>(A + (lrow + 64 * i) * LDA + cc * 8) = ra[i];
+      if (lrow + RPP * i < BM) *reinterpret_cast<v4i_t*>(A + (lrow + RPP * i) * LDF + cc * 8) = ra[i];
   };
-  bf16x8 bn[2][TN];
-  auto load_b = [&](int ks) {
+  // B fragments: one byte offset per column block of this wavefront, advanced by a constant every step
+  uint32_t boff[TN];
 #pragma unroll
-    for (int kk = 0; kk < 2; kk++)
+  for (int j = 0; j < TN; j++) {
+    const int nb = (n0 + wn0) / 32 + j;
+    boff[j] = nb < NB ? (uint32_t)((((int64_t)nb * KB16 + ks_begin * KK) * 512 + lane * 8) * 2) : kOutOfRange;
+  }
+  bf16x8 bn[KK][TN];
+  auto load_b = [&]() {
+#pragma unroll
+    for (int kk = 0; kk < KK; kk++)
 #pragma unroll
       for (int j = 0; j < TN; j++) {
-        const int nb = (n0 + wn0) / 32 + j;
-        if (nb < NB) bn[kk][j] = *reinterpret_cast<const bf16x8*>(Bf + ((int64_t)nb * KB16 + ks * 2 + kk) * 512 + lane * 8);
-        else
-#pragma unroll
-          for (int t = 0; t < 8; t++) bn[kk][j][t] = 0;
+        union { v4i_t u; bf16x8 v; } f;
+        f.u = __builtin_amdgcn_raw_buffer_load_b128(rsrc_b, (int)(boff[j] + kk * 1024), 0, 0);
+        bn[kk][j] = f.v;
       }
+#pragma unroll
+    for (int j = 0; j < TN; j++) boff[j] += KK * 1024;
   };
 
   floatx16 acc[TM][TN];
@@ -380,30 +399,29 @@ __global__ __launch_bounds__(256) void igemm_frag_kernel(PtrTab ws, CPtrTab wts,
       for (int r = 0; r < 16; r++) acc[i][j][r] = 0.f;
 
   if (ks_begin < ksteps) {
-    load_a();
-    load_b(ks_begin);
+    load_a(ks_begin);
+    load_b();
     store_a(ks_begin & 1);
   }
   __syncthreads();
   for (int ks = ks_begin; ks < ksteps; ks++) {
     const int buf = ks & 1;
-    bf16x8 bc[2][TN];
+    bf16x8 bc[KK][TN];
 #pragma unroll
-    for (int kk = 0; kk < 2; kk++)
+    for (int kk = 0; kk < KK; kk++)
 #pragma unroll
       for (int j = 0; j < TN; j++) bc[kk][j] = bn[kk][j];
     if (ks + 1 < ksteps) {
-      advance();
-      load_a();
-      load_b(ks + 1);
+      load_a(ks + 1);
+      load_b();
     }
     const bf16_t* A = lds + buf * A_ELEMS;
 #pragma unroll
-    for (int kk = 0; kk < 2; kk++) {
+    for (int kk = 0; kk < KK; kk++) {
       bf16x8 a[TM];
 #pragma unroll
       for (int i = 0; i < TM; i++)
-        a[i] = *reinterpret_cast<const bf16x8*>(A + (wm0 + 32 * i + (lane & 31)) * LDA + 16 * kk + 8 * (lane >> 5));
+        a[i] = *reinterpret_cast<const bf16x8*>(A + (wm0 + 32 * i + (lane & 31)) * LDF + 16 * kk + 8 * (lane >> 5));
 #pragma unroll
       for (int i = 0; i < TM; i++)
 #pragma unroll
@@ -495,7 +513,9 @@ static void launch_igemm_t(const PtrTab& ws, const CPtrTab& wts, const IGemm& g,
 template <int BM, int BN, int WM, int WN>
 static void launch_frag_t(const PtrTab& ws, const CPtrTab& wts, const IGemm& g, const Epilogue& ep, int count, hipStream_t s) {
   dim3 grid((unsigned)((g.M + BM - 1) / BM), (unsigned)((g.Ncols + BN - 1) / BN), (unsigned)(count * g.splits));
-  hipLaunchKernelGGL((igemm_frag_kernel<BM, BN, WM, WN>), grid, dim3(256), 0, s, ws, wts, g, ep);
+  static const int bk = getenv("SASGD_FRAG_BK") ? atoi(getenv("SASGD_FRAG_BK")) : 32;
+  if (bk == 64) hipLaunchKernelGGL((igemm_frag_kernel<BM, BN, WM, WN, 64>), grid, dim3(256), 0, s, ws, wts, g, ep);
+  else hipLaunchKernelGGL((igemm_frag_kernel<BM, BN, WM, WN, 32>), grid, dim3(256), 0, s, ws, wts, g, ep);
   if (g.splits > 1) {
     int64_t total = (int64_t)g.M * g.Ncols;
     unsigned blocks = (unsigned)((total + 255) / 256 < 1024 ? (total + 255) / 256 : 1024);
@@ -547,6 +567,7 @@ __global__ __launch_bounds__(256) void igemm_wgrad_kernel(PtrTab ws, PtrTab grad
 
   const int z = blockIdx.z / g.splits, sp = blockIdx.z % g.splits;
   const bf16_t* x = (const bf16_t*)ws.p[z] + g.a_off;
+  const bf16_t* zeros = (const bf16_t*)ws.p[z] + g.zero_off;
   const bf16_t* dy = (const bf16_t*)ws.p[z] + dy_off;
   const int n0 = blockIdx.x * BMG, k0 = blockIdx.y * BNG;   // output-channel and im2col-column origins
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -558,26 +579,21 @@ __global__ __launch_bounds__(256) void igemm_wgrad_kernel(PtrTab ws, PtrTab grad
   auto load_regs = [&](int ms) {
 #pragma unroll
     for (int i = 0; i < A_LOADS; i++) {
-      int idx = tid + 256 * i;
-      int r = idx / CPR_A, ch = idx % CPR_A;
-      int m = ms * BK + r, n = n0 + ch * 8;
-      ra[i] = make_uint4(0, 0, 0, 0);
-      if (r < BK && m < g.M && n < g.Ncols) ra[i] = *reinterpret_cast<const uint4*>(dy + (int64_t)m * g.Ncols + n);
+      const int idx = tid + 256 * i;
+      const int r = idx / CPR_A, ch = idx % CPR_A;
+      const int m = ms * BK + r, n = n0 + ch * 8;
+      ra[i] = ld16_or_zero(dy + (int64_t)m * g.Ncols + n, r < BK && m < g.M && n < g.Ncols, zeros);
     }
 #pragma unroll
     for (int i = 0; i < B_LOADS; i++) {
-      int idx = tid + 256 * i;
-      int r = idx / CPR_B, ch = idx % CPR_B;
-      rb[i] = make_uint4(0, 0, 0, 0);
-      if (r < BK) {
-        const int q = k0 / 8 + ch;
-        if (q == g.Kchunks) {            // the bias column: im2col value 1 for every real output position
-          if (ms * BK + r < g.M) rb[i].x = 0x3F80u;
-        } else {
-          RowPos rp = row_pos(x, g, ms * BK + r);
-          rb[i] = gather_chunk(rp, g, q);
-        }
-      }
+      const int idx = tid + 256 * i;
+      const int r = idx / CPR_B, ch = idx % CPR_B;
+      const int q = k0 / 8 + ch;
+      RowPos rp = row_pos(x, g, ms * BK + r);
+      // the bias column (chunk index Kchunks) reads the constant chunk {1, 0, ...} for every real output position
+      const bool ones = q == g.Kchunks && rp.valid;
+      rp.valid = rp.valid && !ones;
+      rb[i] = gather_chunk(rp, g, q, ones ? zeros + 128 : zeros);
     }
   };
   auto store_lds = [&](int buf) {

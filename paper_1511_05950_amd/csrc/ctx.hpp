@@ -44,7 +44,8 @@ int net_create(const sasgd_config& cfg, Net** out, int64_t* out_P, size_t* out_p
 void net_destroy(Net* net);
 // Device memory the net needs per learner, in bytes (activations, gradient activations, argmax).
 size_t net_workspace_bytes(const Net* net);
-void net_set_workspace(Net* net, int learner, void* ws);
+// Registers a learner's workspace and initialises it (zeros, plus the constant blocks the kernels read).
+hipError_t net_set_workspace(Net* net, int learner, void* ws, hipStream_t stream);
 // Per weight version: derive the kernel-friendly copies (bf16 repacked conv filters) from the flat vector.
 hipError_t net_prepare_version(Net* net, const void* flat, void* packed, hipStream_t stream);
 hipError_t net_calc_gradient(Net* net, const int* learners, const LearnerBind* binds, int count,

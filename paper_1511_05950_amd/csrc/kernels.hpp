@@ -55,7 +55,26 @@ struct IGemm {
   // them in split order and applies the epilogue, so the result does not depend on scheduling.
   int splits;
   size_t scratch_off;
+  // multipliers for division by CPT, ks, OW, OH without a divide (set by igemm_set_magics)
+  uint32_t mg_cpt, mg_ks, mg_ow, mg_oh;
+  // 256 bytes of zeros inside the workspace (elements of bf16 from its base): the address out-of-range chunk
+  // loads are redirected to, so that no load is conditional and no loaded value needs patching
+  size_t zero_off;
+  // byte sizes of the gathered tensor (one learner) and of the fragment-packed B, for hardware-bounds-checked
+  // buffer loads (both below 2 GiB)
+  uint32_t a_bytes, b_bytes;
 };
+
+// floor(n / d) == (n * magic(d)) >> 32 for all 0 <= n with n * d < 2^32 (d >= 2); d == 1 is handled apart.
+inline uint32_t magic_u32(int d) { return d <= 1 ? 0u : (uint32_t)((((uint64_t)1) << 32) / (uint32_t)d + 1u); }
+inline void igemm_set_magics(IGemm& g) {
+  if (g.OH > 0 && g.OW > 0) g.a_bytes = (uint32_t)((int64_t)(g.M / (g.OH * g.OW)) * g.H * g.W * g.C * 2);
+  g.b_bytes = (uint32_t)((int64_t)((g.Ncols + 31) & ~31) * g.ldb * 2);
+  g.mg_cpt = magic_u32(g.CPT);
+  g.mg_ks = magic_u32(g.ks);
+  g.mg_ow = magic_u32(g.OW);
+  g.mg_oh = magic_u32(g.OH);
+}
 
 struct Epilogue {
   size_t out_off, mask_off; // elements of bf16 from the workspace base

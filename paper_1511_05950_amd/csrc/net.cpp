@@ -54,6 +54,7 @@ struct Net {
   size_t pack_elems = 0;
   size_t grad_a = 0, grad_b = 0, grad_elems = 0;   // two gradient-activation buffers (element offsets)
   size_t ws_bytes = 0;
+  size_t zero_off = 0;         // 256 zero bytes (element offset), target of out-of-range loads
   size_t scratch_off = 0, scratch_bytes = 0;   // split-contraction partials (bytes from the workspace base)
   void* ws[kMaxLearners] = {nullptr};
 };
@@ -244,6 +245,7 @@ int net_create(const sasgd_config& cfg, Net** out, int64_t* out_P, size_t* out_p
   net->pack_elems = pack_cursor;
   for (Op& op : net->ops) {
     if (!op.mfma) continue;
+    op.gf.zero_off = op.gd.zero_off = 0;   // filled below, once the arena is laid out
     const Tensor& ti = net->tensors[(size_t)op.in_t];
     op.gf.a_off = ti.off;
     if (!op.dgrad_bt) {
@@ -251,6 +253,8 @@ int net_create(const sasgd_config& cfg, Net** out, int64_t* out_P, size_t* out_p
       op.gf.ldb = op.Kp;
       if (op.pack_bwd >= 0) { op.gd.b_off = (int64_t)(net->Ppad + (size_t)op.pack_bwd); op.gd.ldb = op.Kpt; }
     }
+    igemm_set_magics(op.gf);
+    igemm_set_magics(op.gd);
   }
   size_t maxe = 0;
   for (const Tensor& t : net->tensors) maxe = t.elems > maxe ? t.elems : maxe;
@@ -258,6 +262,9 @@ int net_create(const sasgd_config& cfg, Net** out, int64_t* out_P, size_t* out_p
   net->grad_a = cursor;
   net->grad_b = cursor + net->grad_elems;
   cursor += 2 * net->grad_elems;
+  net->zero_off = cursor;
+  cursor += 256;
+  for (Op& op : net->ops) op.gf.zero_off = op.gd.zero_off = net->zero_off;
   const size_t esz = net->bf16 ? 2 : 4;
   size_t bytes = (cursor * esz + 255) & ~(size_t)255;
   for (Op& op : net->ops) op.arg_off += bytes;
@@ -288,7 +295,14 @@ int net_create(const sasgd_config& cfg, Net** out, int64_t* out_P, size_t* out_p
 
 void net_destroy(Net* net) { delete net; }
 size_t net_workspace_bytes(const Net* net) { return net->ws_bytes; }
-void net_set_workspace(Net* net, int learner, void* ws) { net->ws[learner] = ws; }
+hipError_t net_set_workspace(Net* net, int learner, void* ws, hipStream_t stream) {
+  net->ws[learner] = ws;
+  hipError_t e = hipMemsetAsync(ws, 0, net->ws_bytes, stream);
+  if (e != hipSuccess || !net->bf16) return e;
+  // second half of the constant block: one 16-byte chunk holding bf16 1.0 followed by zeros (the im2col "bias column")
+  static const uint16_t one = 0x3F80;
+  return hipMemcpyAsync((char*)ws + (net->zero_off + 128) * 2, &one, 2, hipMemcpyHostToDevice, stream);
+}
 
 #define TRY(x) do { hipError_t e__ = (x); if (e__ != hipSuccess) return e__; } while (0)
 
