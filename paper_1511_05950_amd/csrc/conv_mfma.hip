@@ -491,7 +491,7 @@ __global__ __launch_bounds__(256) void igemm_finish_kernel(PtrTab ws, CPtrTab wt
 }
 
 int choose_splits(int64_t tiles, int count, int steps, size_t bytes_per_split, size_t scratch_bytes) {
-  const int64_t target = 1024;                       // about four workgroups per compute unit
+  const int64_t target = 600;                        // a little over two workgroups per compute unit
   int64_t sp = (target + tiles * count - 1) / (tiles * count);
   if (sp > steps / 4) sp = steps / 4;                // keep at least four contraction steps per workgroup
   if (bytes_per_split > 0 && (int64_t)(scratch_bytes / bytes_per_split) < sp) sp = (int64_t)(scratch_bytes / bytes_per_split);
@@ -685,6 +685,27 @@ __global__ __launch_bounds__(256) void igemm_wgrad_kernel(PtrTab ws, PtrTab grad
   }
   float* dw = (float*)grads.p[z] + w_off;
   float* db = (float*)grads.p[z] + b_off;
+  if (v.ks == 1 && v.s2d == 1 && v.C == v.Creal) {
+    // fully connected layer: dW[n][k] is the tile itself, row length C; 32 lanes write 128 contiguous bytes
+#pragma unroll
+    for (int j = 0; j < TN; j++) {
+      const int k = k0 + wn0 + 32 * j + (lane & 31);
+      if (k > kcols) continue;
+#pragma unroll
+      for (int i = 0; i < TM; i++) {
+        const int nb = n0 + wm0 + 32 * i + 4 * (lane >> 5);
+        float* row = dw + (int64_t)nb * v.C + k;
+#pragma unroll
+        for (int r = 0; r < 16; r++) {
+          const int dn = 8 * (r >> 2) + (r & 3);
+          if (nb + dn >= g.Ncols) continue;
+          if (k == kcols) db[nb + dn] = acc[i][j][r];
+          else row[(int64_t)dn * v.C] = acc[i][j][r];
+        }
+      }
+    }
+    return;
+  }
 #pragma unroll
   for (int j = 0; j < TN; j++) {
     const int k = k0 + wn0 + 32 * j + (lane & 31);       // im2col column = tap * C + cp; column kcols = bias
