@@ -50,44 +50,44 @@ __host__ __device__ inline int64_t filter_src(const VConv& v, int n, int tap, in
 //   frag[(nb * KB16 + kb) * 512 + lane * 8 + t] = B[row 32 nb + lane%32][k = 16 kb + 8 (lane/32) + t]
 // fwd: B = Wp[n][tap][cp] (k = tap * C + cp, Kp = padded ks*ks*C);   rows beyond K and k beyond the filter are zero
 // bwd: B = Wt[c][tap'][n] (k = tap' * K + n, tap' = flipped tap, Kpt = padded ks*ks*K), stride-1 layers only
-__global__ __launch_bounds__(256) void pack_filters_kernel(const bf16_t* __restrict__ flat, bf16_t* __restrict__ packed, VConv v,
-                                                           int64_t w_off, int64_t fwd_off, int64_t bwd_off, int Kp, int Kpt,
-                                                           int want_bwd) {
-  const int64_t nf = (int64_t)((v.K + 31) & ~31) * Kp;
-  const int64_t nb = want_bwd ? (int64_t)((v.C + 31) & ~31) * Kpt : 0;
-  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < nf + nb; i += (int64_t)gridDim.x * 256) {
+__global__ __launch_bounds__(256) void pack_filters_kernel(const bf16_t* __restrict__ flat, bf16_t* __restrict__ packed, PackTable t) {
+  for (int64_t gi = (int64_t)blockIdx.x * 256 + threadIdx.x; gi < t.total; gi += (int64_t)gridDim.x * 256) {
+    int li = 0;                                   // layer this element belongs to
+    while (li + 1 < t.count && gi >= t.job[li + 1].start) li++;
+    const PackJob& jb = t.job[li];
+    const VConv& v = jb.v;
+    const int64_t i = gi - jb.start;
+    const int64_t nf = (int64_t)((v.K + 31) & ~31) * jb.Kp;
     const bool fwd = i < nf;
     const int64_t e = fwd ? i : i - nf;
-    const int KB16 = (fwd ? Kp : Kpt) / 16;
-    const int t = (int)(e & 7), lane = (int)((e >> 3) & 63);
+    const int KB16 = (fwd ? jb.Kp : jb.Kpt) / 16;
+    const int t8 = (int)(e & 7), lane = (int)((e >> 3) & 63);
     const int64_t blk = e >> 9;
     const int kb = (int)(blk % KB16), rb = (int)(blk / KB16);
-    const int row = 32 * rb + (lane & 31), k = 16 * kb + 8 * (lane >> 5) + t;
+    const int row = 32 * rb + (lane & 31), k = 16 * kb + 8 * (lane >> 5) + t8;
     bf16_t val = 0;
     if (fwd) {
       int tap = k / v.C, cp = k % v.C;
       if (row < v.K && tap < v.ks * v.ks) {
         int64_t src = filter_src(v, row, tap, cp);
-        if (src >= 0) val = flat[w_off + src];
+        if (src >= 0) val = flat[jb.w_off + src];
       }
-      packed[fwd_off + e] = val;
+      packed[jb.fwd_off + e] = val;
     } else {
       int tap = k / v.K, n = k % v.K;
       if (row < v.C && tap < v.ks * v.ks) {
         int64_t src = filter_src(v, n, v.ks * v.ks - 1 - tap, row);   // flipped tap (ks-1-kh, ks-1-kw)
-        if (src >= 0) val = flat[w_off + src];
+        if (src >= 0) val = flat[jb.w_off + src];
       }
-      packed[bwd_off + e] = val;
+      packed[jb.bwd_off + e] = val;
     }
   }
 }
 
-hipError_t launch_pack_filters(const void* flat, void* packed, const VConv& v, int64_t w_off, int64_t fwd_off, int64_t bwd_off,
-                               int Kp, int Kpt, bool want_bwd, hipStream_t s) {
-  int64_t total = (int64_t)((v.K + 31) & ~31) * Kp + (want_bwd ? (int64_t)((v.C + 31) & ~31) * Kpt : 0);
-  int blocks = (int)((total + 255) / 256 < 2048 ? (total + 255) / 256 : 2048);
-  hipLaunchKernelGGL(pack_filters_kernel, dim3(blocks), dim3(256), 0, s, (const bf16_t*)flat, (bf16_t*)packed, v, w_off, fwd_off,
-                     bwd_off, Kp, Kpt, want_bwd ? 1 : 0);
+hipError_t launch_pack_filters(const void* flat, void* packed, const PackTable& t, hipStream_t s) {
+  if (t.count == 0 || t.total == 0) return hipSuccess;
+  int blocks = (int)((t.total + 255) / 256 < 4096 ? (t.total + 255) / 256 : 4096);
+  hipLaunchKernelGGL(pack_filters_kernel, dim3(blocks), dim3(256), 0, s, (const bf16_t*)flat, (bf16_t*)packed, t);
   return hipGetLastError();
 }
 
@@ -555,10 +555,10 @@ hipError_t launch_igemm(const PtrTab& ws, const CPtrTab& wts, const IGemm& g, co
 // dW tile [BMG output channels][BNG im2col columns], contraction over output positions m in steps of 32.
 // dy tile  [32 m][BMG n]  and  im2col tile [32 m][BNG k]  are staged as they lie in memory (rows = m) and
 // read with the transpose load.  The result is scattered into the flat fp32 gradient through filter_src().
-template <int BMG, int BNG>
+template <int BMG, int BNG, int WMG, int WNG>
 __global__ __launch_bounds__(256) void igemm_wgrad_kernel(PtrTab ws, PtrTab grads, IGemm g, VConv v, size_t dy_off, int64_t w_off,
                                                           int64_t b_off) {
-  constexpr int WMG = BMG / 2, WNG = BNG / 2;          // 2 x 2 wavefronts
+  constexpr int WAVES_NG = BNG / WNG;                  // four wavefronts: (BMG / WMG) x (BNG / WNG)
   constexpr int TM = WMG / 32, TN = WNG / 32;
   constexpr int LDT_A = BMG + 32 - (BMG == 32 ? 32 : 0);
   constexpr int LDT_B = BNG + 32 - (BNG == 32 ? 32 : 0);
@@ -571,7 +571,7 @@ __global__ __launch_bounds__(256) void igemm_wgrad_kernel(PtrTab ws, PtrTab grad
   const bf16_t* dy = (const bf16_t*)ws.p[z] + dy_off;
   const int n0 = blockIdx.x * BMG, k0 = blockIdx.y * BNG;   // output-channel and im2col-column origins
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm0 = (wave >> 1) * WMG, wn0 = (wave & 1) * WNG;
+  const int wm0 = (wave / WAVES_NG) * WMG, wn0 = (wave % WAVES_NG) * WNG;
 
   constexpr int CPR_A = BMG / 8, CPR_B = BNG / 8;
   constexpr int A_LOADS = (BK * CPR_A + 255) / 256, B_LOADS = (BK * CPR_B + 255) / 256;
@@ -746,12 +746,15 @@ hipError_t launch_igemm_wgrad(const PtrTab& ws, const PtrTab& grads, const IGemm
                               int64_t b_off, int count, hipStream_t s) {
   if (g.C % 8 || g.Ncols % 8 || g.splits < 1) return hipErrorInvalidValue;
   const int cols = g.Kchunks * 8 + 1;          // im2col columns plus the bias column
-  if (g.Ncols <= 64) {
-    dim3 grid((unsigned)((g.Ncols + 63) / 64), (unsigned)((cols + 127) / 128), (unsigned)(count * g.splits));
-    hipLaunchKernelGGL((igemm_wgrad_kernel<64, 128>), grid, dim3(256), 0, s, ws, grads, g, v, dy_off, w_off, b_off);
+  if (g.Ncols <= 32) {
+    dim3 grid(1, (unsigned)((cols + 127) / 128), (unsigned)(count * g.splits));
+    hipLaunchKernelGGL((igemm_wgrad_kernel<32, 128, 32, 32>), grid, dim3(256), 0, s, ws, grads, g, v, dy_off, w_off, b_off);
+  } else if (g.Ncols <= 64) {
+    dim3 grid(1, (unsigned)((cols + 127) / 128), (unsigned)(count * g.splits));
+    hipLaunchKernelGGL((igemm_wgrad_kernel<64, 128, 32, 64>), grid, dim3(256), 0, s, ws, grads, g, v, dy_off, w_off, b_off);
   } else {
     dim3 grid((unsigned)((g.Ncols + 127) / 128), (unsigned)((cols + 127) / 128), (unsigned)(count * g.splits));
-    hipLaunchKernelGGL((igemm_wgrad_kernel<128, 128>), grid, dim3(256), 0, s, ws, grads, g, v, dy_off, w_off, b_off);
+    hipLaunchKernelGGL((igemm_wgrad_kernel<128, 128, 64, 64>), grid, dim3(256), 0, s, ws, grads, g, v, dy_off, w_off, b_off);
   }
   if (g.splits > 1) {
     int64_t total = (int64_t)g.Ncols * cols;

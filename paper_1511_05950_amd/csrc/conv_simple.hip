@@ -48,6 +48,31 @@ __global__ __launch_bounds__(256) void conv_fwd_simple_kernel(PtrTab ws, CPtrTab
   }
 }
 
+// Fully connected forward with a long contraction: one wavefront per output element, lanes stride over the
+// inputs (both operands contiguous), butterfly sum.  Same result order for every launch shape.
+template <typename T>
+__global__ __launch_bounds__(256) void fc_fwd_wave_kernel(PtrTab ws, CPtrTab wts, size_t x_off, size_t y_off, int64_t w_off,
+                                                          int64_t b_off, int N, int C, int K, int relu, int out_f32) {
+  const T* x = (const T*)ws.p[blockIdx.z] + x_off;
+  T* y = (T*)ws.p[blockIdx.z] + y_off;
+  const T* w = (const T*)wts.p[blockIdx.z] + w_off;
+  const T* b = (const T*)wts.p[blockIdx.z] + b_off;
+  const int o = blockIdx.x * 4 + (threadIdx.x >> 6);      // output element index n * K + k
+  const int lane = threadIdx.x & 63;
+  if (o >= N * K) return;
+  const int n = o / K, k = o - n * K;
+  const T* xp = x + (int64_t)n * C;
+  const T* wp = w + (int64_t)k * C;
+  float acc = 0.f;
+  for (int c = lane; c < C; c += 64) acc = fmaf(ldf(xp + c), ldf(wp + c), acc);
+  acc = wave_sum(acc) + ldf(b + k);
+  if (relu) acc = fmaxf(acc, 0.f);
+  if (lane == 0) {
+    if (out_f32) reinterpret_cast<float*>(y)[o] = acc;
+    else stf(y + o, acc);
+  }
+}
+
 // ------------------------------------------------------------------ input gradient
 // dx[n][ih][iw][c] = sum_{kh,kw,k} dy[n][oh][ow][k] * w[k][c][kh][kw],  oh*stride + kh - pad = ih.
 template <typename T>
@@ -140,8 +165,14 @@ static inline dim3 grid1(int64_t total, int count) {
 
 hipError_t launch_conv_fwd_simple(bool is_bf16, const PtrTab& ws, const CPtrTab& wts, size_t x_off, size_t y_off, int64_t w_off,
                                   int64_t b_off, const ConvShape& sh, bool relu, bool out_f32, int count, hipStream_t s) {
-  dim3 g = grid1((int64_t)sh.N * sh.OH * sh.OW * sh.K, count);
   int r = relu ? 1 : 0, of = out_f32 ? 1 : 0;
+  if (sh.ks == 1 && sh.H == 1 && sh.W == 1 && sh.C >= 256 && (int64_t)sh.N * sh.K < (1 << 22)) {
+    dim3 gw((unsigned)(((int64_t)sh.N * sh.K + 3) / 4), 1, (unsigned)count);
+    if (is_bf16) hipLaunchKernelGGL(fc_fwd_wave_kernel<bf16_t>, gw, dim3(256), 0, s, ws, wts, x_off, y_off, w_off, b_off, sh.N, sh.C, sh.K, r, of);
+    else hipLaunchKernelGGL(fc_fwd_wave_kernel<float>, gw, dim3(256), 0, s, ws, wts, x_off, y_off, w_off, b_off, sh.N, sh.C, sh.K, r, of);
+    return hipGetLastError();
+  }
+  dim3 g = grid1((int64_t)sh.N * sh.OH * sh.OW * sh.K, count);
   if (is_bf16) hipLaunchKernelGGL(conv_fwd_simple_kernel<bf16_t>, g, dim3(256), 0, s, ws, wts, x_off, y_off, w_off, b_off, sh, r, of);
   else hipLaunchKernelGGL(conv_fwd_simple_kernel<float>, g, dim3(256), 0, s, ws, wts, x_off, y_off, w_off, b_off, sh, r, of);
   return hipGetLastError();

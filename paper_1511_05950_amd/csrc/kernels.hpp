@@ -87,8 +87,20 @@ hipError_t launch_pack_input(bool is_bf16, const CPtrTab& images, const PtrTab& 
                              const InPack& ip, hipStream_t s);
 
 // ---- bf16 MFMA path (conv_mfma.hip)
-hipError_t launch_pack_filters(const void* flat, void* packed, const VConv& v, int64_t w_off, int64_t fwd_off, int64_t bwd_off,
-                               int Kp, int Kpt, bool want_bwd, hipStream_t s);
+// One launch repacks the filters of every MFMA convolution of a weight version.
+struct PackJob {
+  VConv v;
+  int64_t w_off, fwd_off, bwd_off;   // flat source, fragment destinations (elements)
+  int64_t start;                     // first global element index of this layer in the launch
+  int Kp, Kpt;                       // padded row lengths; Kpt == 0: no transposed copy
+};
+constexpr int kMaxPackJobs = 24;
+struct PackTable {
+  PackJob job[kMaxPackJobs];
+  int count;
+  int64_t total;
+};
+hipError_t launch_pack_filters(const void* flat, void* packed, const PackTable& t, hipStream_t s);
 hipError_t launch_igemm_frag(const PtrTab& ws, const CPtrTab& wts, const IGemm& g, const Epilogue& ep, int count, hipStream_t s);
 hipError_t launch_igemm(const PtrTab& ws, const CPtrTab& wts, const IGemm& g, const Epilogue& ep, bool b_transposed, int count,
                         hipStream_t s);

@@ -51,6 +51,7 @@ struct Net {
   int inC = 0, inH = 0, inW = 0;
   InPack inpack{};
   size_t Ppad = 0;             // start of the packed-filter region inside a version slot (elements)
+  PackTable pack{};            // filter repacking jobs of one weight version
   size_t pack_elems = 0;
   size_t grad_a = 0, grad_b = 0, grad_elems = 0;   // two gradient-activation buffers (element offsets)
   size_t ws_bytes = 0;
@@ -265,6 +266,19 @@ int net_create(const sasgd_config& cfg, Net** out, int64_t* out_P, size_t* out_p
   net->zero_off = cursor;
   cursor += 256;
   for (Op& op : net->ops) op.gf.zero_off = op.gd.zero_off = net->zero_off;
+  for (const Op& op : net->ops) {
+    if (!op.mfma || op.pack_fwd < 0) continue;
+    if (net->pack.count == kMaxPackJobs) { delete net; err = "too many convolution layers for the MFMA path"; return SASGD_EINVAL; }
+    PackJob& jb = net->pack.job[net->pack.count++];
+    jb.v = op.vc;
+    jb.w_off = op.w_off;
+    jb.fwd_off = op.pack_fwd;
+    jb.bwd_off = op.pack_bwd < 0 ? 0 : op.pack_bwd;
+    jb.Kp = op.Kp;
+    jb.Kpt = op.pack_bwd < 0 ? 0 : op.Kpt;
+    jb.start = net->pack.total;
+    net->pack.total += (int64_t)((op.vc.K + 31) & ~31) * op.Kp + (op.pack_bwd < 0 ? 0 : (int64_t)((op.vc.C + 31) & ~31) * op.Kpt);
+  }
   const size_t esz = net->bf16 ? 2 : 4;
   size_t bytes = (cursor * esz + 255) & ~(size_t)255;
   for (Op& op : net->ops) op.arg_off += bytes;
@@ -308,12 +322,8 @@ hipError_t net_set_workspace(Net* net, int learner, void* ws, hipStream_t stream
 
 // Derive the packed bf16 filters of every MFMA convolution from the flat bf16 copy of one weight version.
 hipError_t net_prepare_version(Net* net, const void* flat, void* packed, hipStream_t stream) {
-  for (const Op& op : net->ops) {
-    if (!op.mfma || op.pack_fwd < 0) continue;
-    TRY(launch_pack_filters(flat, packed, op.vc, op.w_off, op.pack_fwd, op.pack_bwd < 0 ? 0 : op.pack_bwd, op.Kp, op.Kpt,
-                            op.pack_bwd >= 0, stream));
-  }
-  return hipSuccess;
+  if (net->pack.count == 0) return hipSuccess;
+  return launch_pack_filters(flat, packed, net->pack, stream);
 }
 
 static void set_splits(const Net* net, IGemm& g, int steps, int count) {
