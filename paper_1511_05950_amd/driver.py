@@ -84,3 +84,14 @@ def run_softsync_batched(ctx, schedule, batch_of, lam, loss_out=None, first_upda
         ctx.sumGradients()
         ctx.applyUpdate()
     return log, calls
+
+
+def run_hardsync(ctx, K, batch_of, lam, loss_out=None):
+    """Hardsync / SSGD (paper Section 2.2, hardsync rule): every update averages the gradients of all lambda
+    learners computed on the current weights (staleness 0) and applies the constant rate.
+
+    The context must have been created with n = 1 (so c = lambda) and lr_mode "constant".  Returns the log of
+    run_softsync (every staleness is 0)."""
+    if ctx.c != lam:
+        raise ValueError("hardsync needs n = 1 (c = lambda)")
+    return run_softsync(ctx, [[0] * lam for _ in range(K)], batch_of, lam, loss_out)

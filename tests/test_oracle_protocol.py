@@ -216,3 +216,24 @@ def test_workload_schedules_have_the_stated_shape():
     assert s3.shape == (100, 18) and set(np.unique(s3)) == {0, 1, 2}
     s4 = wl.config(4)["schedule"]()
     assert s4.shape == (20, 1) and s4.min() >= 0 and s4.max() <= 36
+
+
+def test_staleness_dependent_rate_restores_stability():
+    # The paper's central observation (Section 4.3): with the rate kept at alpha0, large staleness makes
+    # training fail; dividing the rate by the staleness restores it.  On linear least squares with constant
+    # delay p the iteration x_{i+1} = x_i - a * lambda_max * x_{i-p} is unstable once a*lambda_max exceeds
+    # 2 sin(pi / (2 (2p + 1))) (the classical delayed-gradient bound), far below the undelayed limit of 2.
+    A, b = lsq_problem(6, 60, 11)
+    lam_max = np.linalg.eigvalsh(A).max()
+    p = 15
+    alpha0 = 1.0 / lam_max                       # comfortably stable without delay (limit 2 / lam_max)
+    assert alpha0 * lam_max > 2 * np.sin(np.pi / (2 * (2 * p + 1)))
+    K = 600
+    sched = np.full((K, 1), p)
+    th0 = np.random.default_rng(1).standard_normal(6)
+    star = np.linalg.solve(A, b)
+    const = protocol.run(lsq_callback(A, b), th0, lambda i, l: None, sched, p, p, alpha0, mode=protocol.CONSTANT)
+    scaled = protocol.run(lsq_callback(A, b), th0, lambda i, l: None, sched, p, p, alpha0)
+    e0 = np.linalg.norm(th0 - star)
+    assert np.linalg.norm(const["theta"] - star) > 1e3 * e0          # diverged
+    assert np.linalg.norm(scaled["theta"] - star) < 1e-2 * e0        # converged
