@@ -132,6 +132,28 @@ def bench_server(args):
     return out
 
 
+def cpu_baseline_net(cfg, budget_s=10.0):
+    """The oracle's calcGradient, as it stands, on mini-batches of the same workload."""
+    import numpy as np
+    import workloads as wl
+    from oracle import cnn
+    net, mu = cfg["net"], cfg["mu"]
+    w0 = cfg["weights"]()
+    X = wl.images(net, mu, 123)
+    Y = wl.labels(net, mu, 124)
+    cnn.loss_and_gradient(net, w0, X[:1], Y[:1])                 # builds / loads the library
+    t0 = time.perf_counter()
+    n = 0
+    while time.perf_counter() - t0 < budget_s:
+        cnn.loss_and_gradient(net, w0, X, Y)
+        n += 1
+    dt = time.perf_counter() - t0
+    cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+    return {"value": n * mu / dt, "unit": "images/s", "cores": cores, "kind": "oracle",
+            "sample": "%d calcGradient calls of one mini-batch (mu = %d) by the fp64 C oracle with OpenMP; the server update "
+                      "is not included" % (n, mu)}
+
+
 def bench_net(args, cfg_id):
     """Whole hot path on BASELINE config 3 (CIFAR-shaped, bf16, 1-softsync) or 4 (AlexNet-shaped, bf16, 18-softsync):
     one step = one server update = c calcGradients (batched launches) + sumGradients + applyUpdate."""
@@ -189,6 +211,8 @@ def bench_net(args, cfg_id):
         "applyUpdate": {"avg_launch_us": round(ms_u / n_u * 1e3, 2), "bytes_per_launch": P * (4 * c + 18),
                         "achieved_GBs": round(P * (4 * c + 18) / (ms_u / n_u * 1e-3) / 1e9, 1)},
     }
+    if not args.no_cpu:
+        out["cpu_baseline"] = cpu_baseline_net(cfg)
     return out
 
 
