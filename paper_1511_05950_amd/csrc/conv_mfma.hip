@@ -308,8 +308,9 @@ __global__ __launch_bounds__(256) void igemm_kernel(PtrTab ws, CPtrTab wts, IGem
 typedef int v4i_t __attribute__((ext_vector_type(4)));
 constexpr uint32_t kOutOfRange = 0x80000000u;   // buffer offset beyond any tensor: the load returns zeros
 
-template <int BM, int BN, int WM, int WN, int BKT>
-__global__ __launch_bounds__(256) void igemm_frag_kernel(PtrTab ws, CPtrTab wts, IGemm g, Epilogue ep) {
+// NT = threads per workgroup = 64 x number of wave tiles.
+template <int BM, int BN, int WM, int WN, int BKT, int NT>
+__global__ __launch_bounds__(NT) void igemm_frag_kernel(PtrTab ws, CPtrTab wts, IGemm g, Epilogue ep) {
   constexpr int WAVES_N = BN / WN;
   constexpr int TM = WM / 32, TN = WN / 32;
   constexpr int LDF = BKT + 8;                 // 80 or 144 byte rows: conflict-free 16-byte reads
@@ -331,8 +332,8 @@ __global__ __launch_bounds__(256) void igemm_frag_kernel(PtrTab ws, CPtrTab wts,
   const int KB16 = g.ldb / 16;
   const int NB = (g.Ncols + 31) / 32;
 
-  constexpr int A_LOADS = (BM * CPS + 255) / 256;
-  constexpr int RPP = 256 / CPS;               // tile rows covered per loader pass
+  constexpr int A_LOADS = (BM * CPS + NT - 1) / NT;
+  constexpr int RPP = NT / CPS;                // tile rows covered per loader pass
   const int cc = tid % CPS, lrow = tid / CPS;
   // per tile row handled by this thread: byte offset of its window origin, and the origin's coordinates
   int row_off[A_LOADS], row_oh[A_LOADS], row_ow[A_LOADS];
@@ -513,9 +514,8 @@ static void launch_igemm_t(const PtrTab& ws, const CPtrTab& wts, const IGemm& g,
 template <int BM, int BN, int WM, int WN>
 static void launch_frag_t(const PtrTab& ws, const CPtrTab& wts, const IGemm& g, const Epilogue& ep, int count, hipStream_t s) {
   dim3 grid((unsigned)((g.M + BM - 1) / BM), (unsigned)((g.Ncols + BN - 1) / BN), (unsigned)(count * g.splits));
-  static const int bk = getenv("SASGD_FRAG_BK") ? atoi(getenv("SASGD_FRAG_BK")) : 32;
-  if (bk == 64) hipLaunchKernelGGL((igemm_frag_kernel<BM, BN, WM, WN, 64>), grid, dim3(256), 0, s, ws, wts, g, ep);
-  else hipLaunchKernelGGL((igemm_frag_kernel<BM, BN, WM, WN, 32>), grid, dim3(256), 0, s, ws, wts, g, ep);
+  constexpr int NT = 64 * (BM / WM) * (BN / WN);
+  hipLaunchKernelGGL((igemm_frag_kernel<BM, BN, WM, WN, 32, NT>), grid, dim3(NT), 0, s, ws, wts, g, ep);
   if (g.splits > 1) {
     int64_t total = (int64_t)g.M * g.Ncols;
     unsigned blocks = (unsigned)((total + 255) / 256 < 1024 ? (total + 255) / 256 : 1024);
@@ -526,6 +526,8 @@ static void launch_frag_t(const PtrTab& ws, const CPtrTab& wts, const IGemm& g, 
 // Convolution forward / input gradient with fragment-packed filters (g.b_off points at the fragment copy).
 hipError_t launch_igemm_frag(const PtrTab& ws, const CPtrTab& wts, const IGemm& g, const Epilogue& ep, int count, hipStream_t s) {
   if (g.C % 8 || g.ldb % 32 || g.splits < 1) return hipErrorInvalidValue;
+  // A 256 x 256 tile with 512 threads (wave tile 128 x 64) was measured 10-25 % slower than 128 x 128 on the
+  // AlexNet-shaped layers (two wavefronts per SIMD no longer hide the load latency), so it is not instantiated.
   if (g.Ncols <= 32) launch_frag_t<128, 32, 32, 32>(ws, wts, g, ep, count, s);
   else if (g.Ncols <= 64) launch_frag_t<128, 64, 64, 32>(ws, wts, g, ep, count, s);
   else launch_frag_t<128, 128, 64, 64>(ws, wts, g, ep, count, s);

@@ -159,6 +159,9 @@ def test_one_gradient_per_step_decomposition():
             tilde = tilde - a0 / (c * max(p_t, 1)) * (A @ snapshot - b)
             t += 1
         np.testing.assert_allclose(tilde, out["thetas"][i + 1], rtol=1e-12, atol=1e-14)
+    # learners take turns: any lambda consecutive gradients come from lambda different learners
+    order = [learner for (_, _, learner, _, _) in out["log"]]
+    assert all(sorted(order[k:k + lam]) == list(range(lam)) for k in range(len(order) - lam + 1))
     # the footnote's counting: in the decomposed form the staleness of the not-yet-applied
     # gradients grows by one per applied gradient, tau~_t = p_t + r_t
     g = gold()
