@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the staleness-aware n-softsync ASGD hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload server|cifar|alex]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload server|cifar|alex|cifar-fp32-c4|cifar-fp32-c1]
 
 Default workload "server" is BASELINE config 1, the parameter-server microbenchmark: P = 60 M fp32
 parameters, lambda = 54 gradients resident in HBM, momentum 0.9, weight decay 5e-4.  One step consumes every
@@ -168,8 +168,11 @@ def bench_net(args, cfg_id):
     torch.cuda.set_device(dev)
     K = args.warmup + args.steps
     rng = np.random.default_rng(wl.SEED0 + 1000 * cfg_id + 3)
-    hi = {3: 2, 4: 36}[cfg_id]
-    sched = rng.integers(0, hi + 1, size=(K, c)).astype(np.int32)
+    hi = {0: 4, 2: 60, 3: 2, 4: 36}[cfg_id]
+    if cfg_id == 2:
+        sched = wl.jitter_schedule(K, c, n, wl.SEED0 + 2003)
+    else:
+        sched = rng.integers(0, hi + 1, size=(K, c)).astype(np.int32)
     R = hi + 1
     pool = min(cfg["n_images"], 4096)
     pool -= pool % mu
@@ -195,18 +198,21 @@ def bench_net(args, cfg_id):
     P = ctx.P
     ctx.destroy()
     images = args.steps * c * mu
-    flop_img = {3: 68.87424e6, 4: 6.585512448e9}[cfg_id]     # forward + backward MACs x 2 per image
+    flop_img = {0: 68.87424e6, 2: 68.87424e6, 3: 68.87424e6, 4: 6.585512448e9}[cfg_id]   # forward + backward MACs x 2 per image
+    fp32 = cfg["compute"] == "fp32"
+    peak = 157.3 if fp32 else 2500.0
     t_grad = ms_g * 1e-3                                      # all calcGradient calls of the timed region, seconds
     ach = images * flop_img / t_grad / 1e12
     out = {
         "metric": "training images/sec per GPU", "value": round(images / dt, 1), "unit": "images/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(dt / args.steps * 1e3, 4),
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": "BASELINE config %d: %s net, lambda=%d, mu=%d, %d-softsync (c=%d), bf16 compute, fp32 master"
-                               % (cfg_id, net["name"], lam, mu, n, c), "num_params": P},
-        "roofline": {"bound": "mfma", "kernel": "calcGradient phase (every launch of its %d batched calls; algorithmic "
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32" if fp32 else "bf16", "data": "synthetic",
+        "config": {"workload": "BASELINE config %d: %s net, lambda=%d, mu=%d, %d-softsync (c=%d), %s"
+                               % (cfg_id, net["name"], lam, mu, n, c, "fp32 compute" if fp32 else "bf16 compute, fp32 master"),
+                   "num_params": P},
+        "roofline": {"bound": "alu" if fp32 else "mfma", "kernel": "calcGradient phase (every launch of its %d batched calls; algorithmic "
                                                 "flop = 2 x forward+backward MACs of %d images)" % (n_g, images),
-                     "achieved": round(ach, 2), "peak": 2500.0, "unit": "TFLOP/s", "frac": round(ach / 2500.0, 5),
+                     "achieved": round(ach, 2), "peak": peak, "unit": "TFLOP/s", "frac": round(ach / peak, 5),
                      "traffic": None, "avg_call_us": round(t_grad / n_g * 1e6, 1), "learners_per_call": round(images / mu / n_g, 2)},
         "applyUpdate": {"avg_launch_us": round(ms_u / n_u * 1e3, 2), "bytes_per_launch": P * (4 * c + 18),
                         "achieved_GBs": round(P * (4 * c + 18) / (ms_u / n_u * 1e-3) / 1e9, 1)},
@@ -232,8 +238,8 @@ def main():
         sys.exit(2)
     if args.workload == "server":
         out = bench_server(args)
-    elif args.workload in ("cifar", "alex"):
-        out = bench_net(args, 3 if args.workload == "cifar" else 4)
+    elif args.workload in ("cifar", "alex", "cifar-fp32-c4", "cifar-fp32-c1"):
+        out = bench_net(args, {"cifar": 3, "alex": 4, "cifar-fp32-c4": 0, "cifar-fp32-c1": 2}[args.workload])
     else:
         raise SystemExit("unknown workload " + args.workload)
     print(json.dumps(out))

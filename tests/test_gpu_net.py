@@ -240,6 +240,32 @@ def test_alex8_gradient_full_size():
     assert rel(g, eg) < 1.5e-1 and cosine(g, eg) > 0.99
 
 
+def test_config4_first_updates():
+    """BASELINE config 4 as bench.py runs it (AlexNet-shaped, bf16, 18-softsync, ring of 37 versions, batched
+    driver): the first 4 updates.  Bookkeeping must be exact; the update (theta_K - theta_0) is compared at the
+    flip-limited level explained in test_alex8_gradient_full_size."""
+    from paper_1511_05950_amd import binding, driver
+    cfgd = wl.config(4)
+    net, lam, mu, n = cfgd["net"], cfgd["lam"], cfgd["mu"], cfgd["n"]
+    K = 4
+    sched = cfgd["schedule"]()[:K]
+    X, Y, w0 = wl.images(net, K * mu, 5), wl.labels(net, K * mu, 6), cfgd["weights"]()
+    Xd, Yd = torch.from_numpy(X).cuda(), torch.from_numpy(Y).cuda()
+    ctx = binding.Sasgd(lam, mu, n, 37, net="alex8", compute="bf16", alpha0=cfgd["alpha0"], momentum=cfgd["momentum"],
+                        weight_decay=cfgd["weight_decay"], init_weights=w0)
+    log, calls = driver.run_softsync_batched(ctx, sched, lambda i, l: (Xd[i * mu:(i + 1) * mu], Yd[i * mu:(i + 1) * mu]), lam)
+    w = ctx.copyWeights()
+    old = ctx.copyWeights(K - 1)                      # bf16 copy of the previous version, from the ring
+    ctx.destroy()
+    ref = protocol.run(cnn.make_callback(net, round_bf16=True), w0, lambda i, l: (X[i * mu:(i + 1) * mu], Y[i * mu:(i + 1) * mu]),
+                       sched, lam, n, cfgd["alpha0"], cfgd["momentum"], cfgd["weight_decay"])
+    assert log == ref["log"] and calls == 1           # all four gradients read theta_0: one batched call
+    assert rel(w, ref["theta"]) < 1e-3
+    assert rel(w - w0, ref["theta"] - w0) < 1.5e-1 and cosine(w - w0, ref["theta"] - w0) > 0.99
+    assert rel(old, ref["thetas"][K - 1]) < 5e-3      # bf16 rounding of the ring copy: 2^-9 per element
+    assert np.all((old.view(np.uint32) & 0xFFFF) == 0)
+
+
 def test_learner_protocol_errors():
     from paper_1511_05950_amd import binding
     net = TINY["avg_clipped"]
