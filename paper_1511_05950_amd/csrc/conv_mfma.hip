@@ -25,25 +25,6 @@ typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
 constexpr int BK = 32;           // contraction elements per step (4 chunks)
 constexpr int LDA = BK + 8;      // row stride (elements) of k-contiguous LDS tiles: 80 B, conflict-free 16 B reads
 
-// Source index, in the flat [K][Creal][ksr][ksr] filter, of packed element (n, tap, cp) of a virtual
-// stride-1 layer, or -1 for padding.  s2d > 1: the layer is a strided one seen through a
-// space-to-depth input: channel cp = (dy*s2d + dx)*Creal + c, tap = (KY, KX), kh = s2d*KY + dy.
-__host__ __device__ inline int64_t filter_src(const VConv& v, int n, int tap, int cp) {
-  int kh, kw, c;
-  if (v.s2d == 1) {
-    if (cp >= v.Creal) return -1;
-    c = cp; kh = tap / v.ks; kw = tap % v.ks;
-  } else {
-    int g = cp / v.Creal;
-    c = cp % v.Creal;
-    if (g >= v.s2d * v.s2d) return -1;
-    kh = v.s2d * (tap / v.ks) + g / v.s2d;
-    kw = v.s2d * (tap % v.ks) + g % v.s2d;
-    if (kh >= v.ksr || kw >= v.ksr) return -1;
-  }
-  return (((int64_t)n * v.Creal + c) * v.ksr + kh) * v.ksr + kw;
-}
-
 // ------------------------------------------------------------------ filter packing (once per weight version)
 // Filters are stored in MFMA operand ("fragment") order so that a wavefront fetches the B operand of one
 // 32x32x16 MFMA as one contiguous 1 KiB read, straight into registers:

@@ -41,6 +41,25 @@ struct VConv {
   int C, ks, K, s2d, Creal, ksr;
 };
 
+// Source index, in the flat [K][Creal][ksr][ksr] filter, of packed element (n, tap, cp) of a virtual
+// stride-1 layer, or -1 for padding.  s2d > 1: the layer is a strided one seen through a
+// space-to-depth input: channel cp = (dy*s2d + dx)*Creal + c, tap = (KY, KX), kh = s2d*KY + dy.
+__host__ __device__ inline int64_t filter_src(const VConv& v, int n, int tap, int cp) {
+  int kh, kw, c;
+  if (v.s2d == 1) {
+    if (cp >= v.Creal) return -1;
+    c = cp; kh = tap / v.ks; kw = tap % v.ks;
+  } else {
+    int g = cp / v.Creal;
+    c = cp % v.Creal;
+    if (g >= v.s2d * v.s2d) return -1;
+    kh = v.s2d * (tap / v.ks) + g / v.s2d;
+    kw = v.s2d * (tap % v.ks) + g % v.s2d;
+    if (kh >= v.ksr || kw >= v.ksr) return -1;
+  }
+  return (((int64_t)n * v.Creal + c) * v.ksr + kh) * v.ksr + kw;
+}
+
 // One implicit GEMM: D[m][n] = sum_k im2col(t)[m][k] * B(n, k).  t = NHWC tensor [*][H][W][C] at a_off (elements
 // of bf16 from the workspace base), output positions OH x OW, window ks, zero padding pad, stride 1.
 struct IGemm {
@@ -67,8 +86,8 @@ struct IGemm {
 
 // floor(n / d) == (n * magic(d)) >> 32 for all 0 <= n with n * d < 2^32 (d >= 2); d == 1 is handled apart.
 inline uint32_t magic_u32(int d) { return d <= 1 ? 0u : (uint32_t)((((uint64_t)1) << 32) / (uint32_t)d + 1u); }
-inline void igemm_set_magics(IGemm& g) {
-  if (g.OH > 0 && g.OW > 0) g.a_bytes = (uint32_t)((int64_t)(g.M / (g.OH * g.OW)) * g.H * g.W * g.C * 2);
+inline void igemm_set_magics(IGemm& g, int elem_bytes) {
+  if (g.OH > 0 && g.OW > 0) g.a_bytes = (uint32_t)((int64_t)(g.M / (g.OH * g.OW)) * g.H * g.W * g.C * elem_bytes);
   g.b_bytes = (uint32_t)((int64_t)((g.Ncols + 31) & ~31) * g.ldb * 2);
   g.mg_cpt = magic_u32(g.CPT);
   g.mg_ks = magic_u32(g.ks);
@@ -101,6 +120,11 @@ struct PackTable {
   int64_t total;
 };
 hipError_t launch_pack_filters(const void* flat, void* packed, const PackTable& t, hipStream_t s);
+// ---- fp32 MFMA path (conv_mfma_f32.hip); dgrad: g gathers over dy, the filter is read transposed and flipped
+hipError_t launch_igemm_f32(const PtrTab& ws, const CPtrTab& wts, const IGemm& g, const VConv& v, const Epilogue& ep, int64_t w_off,
+                            bool dgrad, int count, hipStream_t s);
+hipError_t launch_igemm_wgrad_f32(const PtrTab& ws, const PtrTab& grads, const IGemm& g, const VConv& v, size_t dy_off, int64_t w_off,
+                                  int64_t b_off, int count, hipStream_t s);
 hipError_t launch_igemm_frag(const PtrTab& ws, const CPtrTab& wts, const IGemm& g, const Epilogue& ep, int count, hipStream_t s);
 hipError_t launch_igemm(const PtrTab& ws, const CPtrTab& wts, const IGemm& g, const Epilogue& ep, bool b_transposed, int count,
                         hipStream_t s);

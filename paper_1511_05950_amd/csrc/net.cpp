@@ -111,26 +111,28 @@ int net_create(const sasgd_config& cfg, Net** out, int64_t* out_P, size_t* out_p
     net->tensors.push_back(t);
     return (int)net->tensors.size() - 1;
   };
-  // Input re-layout.  For bf16 compute the first convolution runs on the MFMA path when it can: its input is
-  // channel-padded to a multiple of 8 (stride 1) or space-to-depth transformed (stride s, no padding).
+  // The MFMA kernels gather 16-byte chunks of `chunk` channels (8 bf16 or 4 fp32).  The first convolution runs on
+  // the MFMA path when it can: its input is channel-padded to a multiple of the chunk (stride 1) or
+  // space-to-depth transformed (stride s, no padding).
+  const int chunk = net->bf16 ? 8 : 4;
+  const bool allow_mfma = getenv("SASGD_NO_MFMA") == nullptr;
+  auto round_chunk = [&](int x) { return (x + chunk - 1) / chunk * chunk; };
   net->inpack = InPack{C, H, W, C, H, W, 1};
   bool first_mfma = false;
-  if (net->bf16 && layers[0].kind == SASGD_CONV && layers[0].units % 8 == 0 && layers[0].window >= 1 && layers[0].stride >= 1 &&
-      getenv("SASGD_NO_MFMA") == nullptr) {
+  if (allow_mfma && layers[0].kind == SASGD_CONV && layers[0].units % chunk == 0 && layers[0].window >= 1 && layers[0].stride >= 1) {
     const sasgd_layer& L0 = layers[0];
     if (L0.stride == 1) {
-      net->inpack.Cp = (C + 7) & ~7;
+      net->inpack.Cp = round_chunk(C);
       first_mfma = true;
     } else if (L0.pad == 0 && L0.window <= H && L0.window <= W) {
       const int sd = L0.stride;
-      net->inpack = InPack{C, H, W, (sd * sd * C + 7) & ~7, (H + sd - 1) / sd, (W + sd - 1) / sd, sd};
+      net->inpack = InPack{C, H, W, round_chunk(sd * sd * C), (H + sd - 1) / sd, (W + sd - 1) / sd, sd};
       first_mfma = true;
     }
   }
   int cur = new_tensor((size_t)N * net->inpack.Cp * net->inpack.Hp * net->inpack.Wp);
   bool flat = false;       // current tensor already in (C,H,W)-flattened order (after a flatten or an fc)
   size_t pack_cursor = 0;
-  const bool allow_mfma = net->bf16 && getenv("SASGD_NO_MFMA") == nullptr;
   auto round32 = [](int x) { return (x + 31) & ~31; };
   int64_t P = 0;
   size_t arg_bytes = 0;
@@ -160,23 +162,27 @@ int net_create(const sasgd_config& cfg, Net** out, int64_t* out_P, size_t* out_p
         op.mfma = true;
         op.vc = VConv{ip.Cp, kse, L.units, ip.s2d, C, L.window};
         op.gf = IGemm{0, 0, N * op.cs.OH * op.cs.OW, L.units, ip.Hp, ip.Wp, ip.Cp, op.cs.OH, op.cs.OW, kse, ip.s2d == 1 ? L.pad : 0,
-                      kse * kse * ip.Cp / 8, ip.Cp / 8, 0};
-        op.Kp = round32(kse * kse * ip.Cp);
-        op.pack_fwd = (int64_t)pack_cursor;
-        pack_cursor += (size_t)round32(L.units) * op.Kp;
-      } else if (cur != 0 && allow_mfma && L.stride == 1 && C % 8 == 0 && L.units % 8 == 0) {
+                      kse * kse * ip.Cp / chunk, ip.Cp / chunk, 0};
+        if (net->bf16) {
+          op.Kp = round32(kse * kse * ip.Cp);
+          op.pack_fwd = (int64_t)pack_cursor;
+          pack_cursor += (size_t)round32(L.units) * op.Kp;
+        }
+      } else if (cur != 0 && allow_mfma && L.stride == 1 && C % chunk == 0 && L.units % chunk == 0) {
         op.mfma = true;
         op.vc = VConv{C, L.window, L.units, 1, C, L.window};
-        op.gf = IGemm{0, 0, N * op.cs.OH * op.cs.OW, L.units, H, W, C, op.cs.OH, op.cs.OW, L.window, L.pad, L.window * L.window * C / 8,
-                      C / 8, 0};
+        op.gf = IGemm{0, 0, N * op.cs.OH * op.cs.OW, L.units, H, W, C, op.cs.OH, op.cs.OW, L.window, L.pad,
+                      L.window * L.window * C / chunk, C / chunk, 0};
         op.gd = IGemm{0, 0, N * H * W, C, op.cs.OH, op.cs.OW, L.units, H, W, L.window, L.window - 1 - L.pad,
-                      L.window * L.window * L.units / 8, L.units / 8, 0};
-        op.Kp = round32(L.window * L.window * C);
-        op.Kpt = round32(L.window * L.window * L.units);
-        op.pack_fwd = (int64_t)pack_cursor;
-        pack_cursor += (size_t)round32(L.units) * op.Kp;
-        op.pack_bwd = (int64_t)pack_cursor;
-        pack_cursor += (size_t)round32(C) * op.Kpt;
+                      L.window * L.window * L.units / chunk, L.units / chunk, 0};
+        if (net->bf16) {
+          op.Kp = round32(L.window * L.window * C);
+          op.Kpt = round32(L.window * L.window * L.units);
+          op.pack_fwd = (int64_t)pack_cursor;
+          pack_cursor += (size_t)round32(L.units) * op.Kp;
+          op.pack_bwd = (int64_t)pack_cursor;
+          pack_cursor += (size_t)round32(C) * op.Kpt;
+        }
       }
       C = L.units; H = op.cs.OH; W = op.cs.OW;
       cur = op.out_t = new_tensor((size_t)N * C * H * W);
@@ -207,14 +213,14 @@ int net_create(const sasgd_config& cfg, Net** out, int64_t* out_P, size_t* out_p
       op.b_off = P;
       P += L.units;
       op.in_t = cur;
-      if (cur != 0 && allow_mfma && in % 8 == 0 && L.units % 8 == 0 && op.w_off % 8 == 0) {
+      if (cur != 0 && allow_mfma && in % chunk == 0 && L.units % chunk == 0 && (!net->bf16 || op.w_off % 8 == 0)) {
         // fully connected: the flat weight matrix [out][in] is the B operand as it lies (forward), and is read
         // transposed for the input gradient; no packed copy
         op.mfma = true;
         op.dgrad_bt = true;
         op.vc = VConv{in, 1, L.units, 1, in, 1};
-        op.gf = IGemm{0, op.w_off, N, L.units, 1, 1, in, 1, 1, 1, 0, in / 8, in / 8, in};
-        op.gd = IGemm{0, op.w_off, N, in, 1, 1, L.units, 1, 1, 1, 0, L.units / 8, L.units / 8, in};
+        op.gf = IGemm{0, op.w_off, N, L.units, 1, 1, in, 1, 1, 1, 0, in / chunk, in / chunk, in};
+        op.gd = IGemm{0, op.w_off, N, in, 1, 1, L.units, 1, 1, 1, 0, L.units / chunk, L.units / chunk, in};
       }
       C = L.units; H = 1; W = 1;
       flat = true;
@@ -249,13 +255,15 @@ int net_create(const sasgd_config& cfg, Net** out, int64_t* out_P, size_t* out_p
     op.gf.zero_off = op.gd.zero_off = 0;   // filled below, once the arena is laid out
     const Tensor& ti = net->tensors[(size_t)op.in_t];
     op.gf.a_off = ti.off;
-    if (!op.dgrad_bt) {
+    if (!op.dgrad_bt && net->bf16) {
       op.gf.b_off = (int64_t)(net->Ppad + (size_t)op.pack_fwd);
       op.gf.ldb = op.Kp;
       if (op.pack_bwd >= 0) { op.gd.b_off = (int64_t)(net->Ppad + (size_t)op.pack_bwd); op.gd.ldb = op.Kpt; }
     }
-    igemm_set_magics(op.gf);
-    igemm_set_magics(op.gd);
+    igemm_set_magics(op.gf, net->bf16 ? 2 : 4);
+    igemm_set_magics(op.gd, net->bf16 ? 2 : 4);
+    if (!net->bf16)   // the fp32 kernels read the flat filter itself: its byte size bounds their loads
+      op.gf.b_bytes = op.gd.b_bytes = (uint32_t)((int64_t)op.vc.K * op.vc.Creal * op.vc.ksr * op.vc.ksr * 4);
   }
   size_t maxe = 0;
   for (const Tensor& t : net->tensors) maxe = t.elems > maxe ? t.elems : maxe;
@@ -286,7 +294,7 @@ int net_create(const sasgd_config& cfg, Net** out, int64_t* out_P, size_t* out_p
   // scratch for split contractions: room for 8 partial copies of the largest output, within 16..128 MiB
   size_t need = 0;
   for (const Op& op : net->ops) {
-    if (!op.mfma) continue;
+    if (!op.mfma || !net->bf16) continue;
     size_t fwd = (size_t)op.gf.M * op.gf.Ncols * 4, wg = (size_t)op.gf.Ncols * (op.gf.Kchunks * 8 + 8) * 4;
     size_t dg = (size_t)op.gd.M * op.gd.Ncols * 4;
     need = fwd > need ? fwd : need;
@@ -312,10 +320,12 @@ size_t net_workspace_bytes(const Net* net) { return net->ws_bytes; }
 hipError_t net_set_workspace(Net* net, int learner, void* ws, hipStream_t stream) {
   net->ws[learner] = ws;
   hipError_t e = hipMemsetAsync(ws, 0, net->ws_bytes, stream);
-  if (e != hipSuccess || !net->bf16) return e;
-  // second half of the constant block: one 16-byte chunk holding bf16 1.0 followed by zeros (the im2col "bias column")
-  static const uint16_t one = 0x3F80;
-  return hipMemcpyAsync((char*)ws + (net->zero_off + 128) * 2, &one, 2, hipMemcpyHostToDevice, stream);
+  if (e != hipSuccess) return e;
+  // second half of the constant block: one 16-byte chunk holding 1.0 followed by zeros (the im2col "bias column")
+  static const uint16_t one_bf16 = 0x3F80;
+  static const float one_f32 = 1.0f;
+  if (net->bf16) return hipMemcpyAsync((char*)ws + (net->zero_off + 128) * 2, &one_bf16, 2, hipMemcpyHostToDevice, stream);
+  return hipMemcpyAsync((char*)ws + (net->zero_off + 128) * 4, &one_f32, 4, hipMemcpyHostToDevice, stream);
 }
 
 #define TRY(x) do { hipError_t e__ = (x); if (e__ != hipSuccess) return e__; } while (0)
@@ -354,7 +364,10 @@ hipError_t net_calc_gradient(Net* net, const int* learners, const LearnerBind* b
     const size_t xi = T[(size_t)op.in_t].off, yo = T[(size_t)op.out_t].off;
     switch (op.kind) {
       case OP_CONV:
-        if (op.mfma) {
+        if (op.mfma && !bf) {
+          Epilogue ep{yo, 0, op.b_off, 1, op.relu ? 1 : 0, 0, 1};
+          TRY(launch_igemm_f32(ws, wts, op.gf, op.vc, ep, op.w_off, false, count, stream));
+        } else if (op.mfma) {
           Epilogue ep{yo, 0, op.b_off, 1, op.relu ? 1 : 0, 0, op.out_f32 ? 1 : 0};
           IGemm gf = op.gf;
           set_splits(net, gf, (gf.Kchunks + 3) / 4, count);
@@ -383,7 +396,15 @@ hipError_t net_calc_gradient(Net* net, const int* learners, const LearnerBind* b
     const bool need_dx = op.in_t != 0;          // the network input needs no gradient
     switch (op.kind) {
       case OP_CONV:
-        if (op.mfma) {
+        if (op.mfma && !bf) {
+          TRY(launch_igemm_wgrad_f32(ws, grads, op.gf, op.vc, dy, op.w_off, op.b_off, count, stream));
+          if (need_dx) {
+            IGemm gd = op.gd;
+            gd.a_off = dy;
+            Epilogue ep{dx, tin.off, 0, 0, 0, tin.relu ? 1 : 0, 1};
+            TRY(launch_igemm_f32(ws, wts, gd, op.vc, ep, op.w_off, true, count, stream));
+          }
+        } else if (op.mfma) {
           IGemm gw = op.gf;
           {
             const int64_t tiles = (int64_t)((gw.Ncols + 127) / 128) * ((gw.Kchunks * 8 + 1 + 127) / 128);
