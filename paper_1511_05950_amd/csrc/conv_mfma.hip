@@ -473,7 +473,7 @@ __global__ __launch_bounds__(256) void igemm_finish_kernel(PtrTab ws, CPtrTab wt
 }
 
 int choose_splits(int64_t tiles, int count, int steps, size_t bytes_per_split, size_t scratch_bytes) {
-  const int64_t target = 600;                        // a little over two workgroups per compute unit
+  const int64_t target = 600;   // workgroups wanted per launch; 384..1024 measured, 600-768 best at 6 and 18 learners
   int64_t sp = (target + tiles * count - 1) / (tiles * count);
   if (sp > steps / 4) sp = steps / 4;                // keep at least four contraction steps per workgroup
   if (bytes_per_split > 0 && (int64_t)(scratch_bytes / bytes_per_split) < sp) sp = (int64_t)(scratch_bytes / bytes_per_split);
@@ -707,21 +707,36 @@ __global__ __launch_bounds__(256) void igemm_wgrad_kernel(PtrTab ws, PtrTab grad
   }
 }
 
+// One workgroup per output channel n: the row of partial sums is added in split order into LDS (coalesced reads),
+// then written to the flat gradient in ITS order (coalesced writes), the im2col column of each filter element
+// being looked up on the way.
 __global__ __launch_bounds__(256) void wgrad_finish_kernel(PtrTab ws, PtrTab grads, IGemm g, VConv v, int64_t w_off, int64_t b_off) {
-  const int z = blockIdx.z;
+  extern __shared__ float row[];                 // kcols + 1 sums
+  const int z = blockIdx.z, n = blockIdx.x;
   const int kcols = g.Kchunks * 8, ldk = kcols + 8;
-  const float* part = reinterpret_cast<const float*>((const char*)ws.p[z] + g.scratch_off);
-  float* dw = (float*)grads.p[z] + w_off;
-  float* db = (float*)grads.p[z] + b_off;
-  const int64_t total = (int64_t)g.Ncols * (kcols + 1);
-  for (int64_t o = (int64_t)blockIdx.x * 256 + threadIdx.x; o < total; o += (int64_t)gridDim.x * 256) {
-    const int n = (int)(o / (kcols + 1)), k = (int)(o % (kcols + 1));
+  const float* part = reinterpret_cast<const float*>((const char*)ws.p[z] + g.scratch_off) + (int64_t)n * ldk;
+  const int64_t split_stride = (int64_t)g.Ncols * ldk;
+  for (int k = threadIdx.x; k <= kcols; k += 256) {
     float acc = 0.f;
-    for (int sp = 0; sp < g.splits; sp++) acc += part[((int64_t)sp * g.Ncols + n) * ldk + k];
-    if (k == kcols) { db[n] = acc; continue; }
-    const int tap = k / g.C, cp = k - tap * g.C;
-    const int64_t dst = filter_src(v, n, tap, cp);
-    if (dst >= 0) dw[dst] = acc;
+    for (int sp = 0; sp < g.splits; sp++) acc += part[sp * split_stride + k];
+    row[k] = acc;
+  }
+  __syncthreads();
+  float* dw = (float*)grads.p[z] + w_off + (int64_t)n * v.Creal * v.ksr * v.ksr;
+  if (threadIdx.x == 0) ((float*)grads.p[z] + b_off)[n] = row[kcols];
+  const int per_n = v.Creal * v.ksr * v.ksr;
+  for (int j = threadIdx.x; j < per_n; j += 256) {
+    const int kw = j % v.ksr, t = j / v.ksr;
+    const int kh = t % v.ksr, c = t / v.ksr;
+    int tap, cp;
+    if (v.s2d == 1) {
+      tap = kh * v.ks + kw;
+      cp = c;
+    } else {
+      tap = (kh / v.s2d) * v.ks + kw / v.s2d;
+      cp = ((kh % v.s2d) * v.s2d + kw % v.s2d) * v.Creal + c;
+    }
+    dw[j] = row[tap * g.C + cp];
   }
 }
 
@@ -729,6 +744,7 @@ hipError_t launch_igemm_wgrad(const PtrTab& ws, const PtrTab& grads, const IGemm
                               int64_t b_off, int count, hipStream_t s) {
   if (g.C % 8 || g.Ncols % 8 || g.splits < 1) return hipErrorInvalidValue;
   const int cols = g.Kchunks * 8 + 1;          // im2col columns plus the bias column
+  if (g.splits > 1 && (size_t)cols * sizeof(float) > 60 * 1024) return hipErrorInvalidValue;   // finish kernel keeps one row in LDS
   if (g.Ncols <= 32) {
     dim3 grid(1, (unsigned)((cols + 127) / 128), (unsigned)(count * g.splits));
     hipLaunchKernelGGL((igemm_wgrad_kernel<32, 128, 32, 32>), grid, dim3(256), 0, s, ws, grads, g, v, dy_off, w_off, b_off);
@@ -739,11 +755,9 @@ hipError_t launch_igemm_wgrad(const PtrTab& ws, const PtrTab& grads, const IGemm
     dim3 grid((unsigned)((g.Ncols + 127) / 128), (unsigned)((cols + 127) / 128), (unsigned)(count * g.splits));
     hipLaunchKernelGGL((igemm_wgrad_kernel<128, 128, 64, 64>), grid, dim3(256), 0, s, ws, grads, g, v, dy_off, w_off, b_off);
   }
-  if (g.splits > 1) {
-    int64_t total = (int64_t)g.Ncols * cols;
-    unsigned blocks = (unsigned)((total + 255) / 256 < 2048 ? (total + 255) / 256 : 2048);
-    hipLaunchKernelGGL(wgrad_finish_kernel, dim3(blocks, 1, (unsigned)count), dim3(256), 0, s, ws, grads, g, v, w_off, b_off);
-  }
+  if (g.splits > 1)
+    hipLaunchKernelGGL(wgrad_finish_kernel, dim3((unsigned)g.Ncols, 1, (unsigned)count), dim3(256), (size_t)cols * sizeof(float), s, ws,
+                       grads, g, v, w_off, b_off);
   return hipGetLastError();
 }
 

@@ -158,7 +158,8 @@ hipError_t launch_flatten_bwd(bool is_bf16, const PtrTab& ws, size_t dy_off, siz
 
 // loss[l] = mean_n -log softmax(z_n)[label_n];  dz = (softmax(z) - onehot) / N.  loss_out may be null.
 // z_f32: the scores at z_off (an offset in elements of T) are fp32; dz is always of type T.
-hipError_t launch_softmax_ce(bool is_bf16, bool z_f32, const PtrTab& ws, const CPtrTab& labels, size_t z_off, size_t dz_off, int N,
-                             int K, float* loss_out, int count, hipStream_t s);
+// loss_byte_off: N floats of per-image losses in the workspace (bytes from its base).
+hipError_t launch_softmax_ce(bool is_bf16, bool z_f32, const PtrTab& ws, const CPtrTab& labels, size_t z_off, size_t dz_off,
+                             size_t loss_byte_off, int N, int K, float* loss_out, int count, hipStream_t s);
 
 }  // namespace sasgd

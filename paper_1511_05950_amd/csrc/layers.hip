@@ -379,51 +379,53 @@ hipError_t launch_flatten_bwd(bool is_bf16, const PtrTab& ws, size_t dy_off, siz
 }
 
 // ------------------------------------------------------------------ softmax cross-entropy
-// One workgroup per learner, one wavefront per image (images strided over the four wavefronts).  The
-// per-image losses are summed in image order by lane 0 of the workgroup so the result does not depend on
-// scheduling.  dz = (softmax(z) - onehot(label)) / N, i.e. the gradient of the MEAN loss: this is where
-// the division by the mini-batch size enters (Section 2.1).
+// One workgroup per image: dz = (softmax(z) - onehot(label)) / N, i.e. the gradient of the MEAN loss: this is
+// where the division by the mini-batch size enters (Section 2.1).  The per-image losses go to a small array and
+// are summed in image order by a second tiny kernel, so the result does not depend on scheduling.
 template <typename T, typename Z>
-__global__ __launch_bounds__(256) void softmax_ce_kernel(PtrTab ws, CPtrTab labels, size_t z_off, size_t dz_off, int N, int K,
-                                                         float* loss_out) {
-  extern __shared__ float img_loss[];   // [N]
-  const int l = blockIdx.x;
-  const Z* z = reinterpret_cast<const Z*>((const T*)ws.p[l] + z_off);
-  T* dz = (T*)ws.p[l] + dz_off;
-  const int32_t* lab = (const int32_t*)labels.p[l];
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const float invN = 1.0f / (float)N;
-  for (int n = wave; n < N; n += 4) {
-    const Z* zn = z + (int64_t)n * K;
-    float m = -INFINITY;
-    for (int j = lane; j < K; j += 64) m = fmaxf(m, ldf(zn + j));
-    m = wave_max(m);
-    float sum = 0.f;
-    for (int j = lane; j < K; j += 64) sum += expf(ldf(zn + j) - m);
-    sum = wave_sum(sum);
-    const int y = lab[n];
-    const bool valid = y >= 0 && y < K;
-    const float inv = 1.0f / sum;
-    for (int j = lane; j < K; j += 64) {
-      float p = expf(ldf(zn + j) - m) * inv;
-      stf(dz + (int64_t)n * K + j, (p - (j == y ? 1.f : 0.f)) * invN);
-    }
-    if (lane == 0) img_loss[n] = valid ? -(ldf(zn + y) - m - logf(sum)) : NAN;   // a label outside [0,K) poisons the loss
-  }
+__global__ __launch_bounds__(256) void softmax_ce_kernel(PtrTab ws, CPtrTab labels, size_t z_off, size_t dz_off, size_t loss_byte_off,
+                                                         int N, int K) {
+  __shared__ float red[4];
+  const int l = blockIdx.z, n = blockIdx.x;
+  const Z* zn = reinterpret_cast<const Z*>((const T*)ws.p[l] + z_off) + (int64_t)n * K;
+  T* dz = (T*)ws.p[l] + dz_off + (int64_t)n * K;
+  float* img_loss = reinterpret_cast<float*>((char*)ws.p[l] + loss_byte_off);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  float m = -INFINITY;
+  for (int j = threadIdx.x; j < K; j += 256) m = fmaxf(m, ldf(zn + j));
+  m = wave_max(m);
+  if (lane == 0) red[wave] = m;
   __syncthreads();
-  if (threadIdx.x == 0 && loss_out) {
-    float tot = 0.f;
-    for (int n = 0; n < N; n++) tot += img_loss[n];
-    loss_out[l] = tot * invN;
-  }
+  m = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+  __syncthreads();
+  float sum = 0.f;
+  for (int j = threadIdx.x; j < K; j += 256) sum += expf(ldf(zn + j) - m);
+  sum = wave_sum(sum);
+  if (lane == 0) red[wave] = sum;
+  __syncthreads();
+  sum = (red[0] + red[1]) + (red[2] + red[3]);
+  const int y = ((const int32_t*)labels.p[l])[n];
+  const float inv = 1.0f / sum, invN = 1.0f / (float)N;
+  for (int j = threadIdx.x; j < K; j += 256) stf(dz + j, (expf(ldf(zn + j) - m) * inv - (j == y ? 1.f : 0.f)) * invN);
+  if (threadIdx.x == 0) img_loss[n] = (y >= 0 && y < K) ? -(ldf(zn + y) - m - logf(sum)) : NAN;   // a bad label poisons the loss
 }
 
-hipError_t launch_softmax_ce(bool is_bf16, bool z_f32, const PtrTab& ws, const CPtrTab& labels, size_t z_off, size_t dz_off, int N,
-                             int K, float* loss_out, int count, hipStream_t s) {
-  size_t shm = (size_t)N * sizeof(float);
-  if (is_bf16 && z_f32) hipLaunchKernelGGL((softmax_ce_kernel<bf16_t, float>), dim3(count), dim3(256), shm, s, ws, labels, z_off, dz_off, N, K, loss_out);
-  else if (is_bf16) hipLaunchKernelGGL((softmax_ce_kernel<bf16_t, bf16_t>), dim3(count), dim3(256), shm, s, ws, labels, z_off, dz_off, N, K, loss_out);
-  else hipLaunchKernelGGL((softmax_ce_kernel<float, float>), dim3(count), dim3(256), shm, s, ws, labels, z_off, dz_off, N, K, loss_out);
+__global__ void loss_mean_kernel(PtrTab ws, size_t loss_byte_off, int N, float* loss_out) {
+  const int l = blockIdx.x;
+  if (threadIdx.x != 0) return;
+  const float* img_loss = reinterpret_cast<const float*>((const char*)ws.p[l] + loss_byte_off);
+  float tot = 0.f;
+  for (int n = 0; n < N; n++) tot += img_loss[n];
+  loss_out[l] = tot / (float)N;
+}
+
+hipError_t launch_softmax_ce(bool is_bf16, bool z_f32, const PtrTab& ws, const CPtrTab& labels, size_t z_off, size_t dz_off,
+                             size_t loss_byte_off, int N, int K, float* loss_out, int count, hipStream_t s) {
+  dim3 g((unsigned)N, 1, (unsigned)count);
+  if (is_bf16 && z_f32) hipLaunchKernelGGL((softmax_ce_kernel<bf16_t, float>), g, dim3(256), 0, s, ws, labels, z_off, dz_off, loss_byte_off, N, K);
+  else if (is_bf16) hipLaunchKernelGGL((softmax_ce_kernel<bf16_t, bf16_t>), g, dim3(256), 0, s, ws, labels, z_off, dz_off, loss_byte_off, N, K);
+  else hipLaunchKernelGGL((softmax_ce_kernel<float, float>), g, dim3(256), 0, s, ws, labels, z_off, dz_off, loss_byte_off, N, K);
+  if (loss_out) hipLaunchKernelGGL(loss_mean_kernel, dim3(count), dim3(64), 0, s, ws, loss_byte_off, N, loss_out);
   return hipGetLastError();
 }
 

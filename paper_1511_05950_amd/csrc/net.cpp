@@ -55,6 +55,7 @@ struct Net {
   size_t pack_elems = 0;
   size_t grad_a = 0, grad_b = 0, grad_elems = 0;   // two gradient-activation buffers (element offsets)
   size_t ws_bytes = 0;
+  size_t loss_off = 0;         // per-image losses, mu floats (byte offset)
   size_t zero_off = 0;         // 256 zero bytes (element offset), target of out-of-range loads
   size_t scratch_off = 0, scratch_bytes = 0;   // split-contraction partials (bytes from the workspace base)
   void* ws[kMaxLearners] = {nullptr};
@@ -291,6 +292,8 @@ int net_create(const sasgd_config& cfg, Net** out, int64_t* out_P, size_t* out_p
   size_t bytes = (cursor * esz + 255) & ~(size_t)255;
   for (Op& op : net->ops) op.arg_off += bytes;
   bytes += arg_bytes;
+  net->loss_off = bytes;
+  bytes += ((size_t)N * 4 + 255) & ~(size_t)255;
   // scratch for split contractions: room for 8 partial copies of the largest output, within 16..128 MiB
   size_t need = 0;
   for (const Op& op : net->ops) {
@@ -388,7 +391,8 @@ hipError_t net_calc_gradient(Net* net, const int* learners, const LearnerBind* b
   }
   // ---- loss and its gradient with respect to the class scores
   size_t dy = net->grad_a, dx = net->grad_b;
-  TRY(launch_softmax_ce(bf, net->scores_f32, ws, labs, T[(size_t)net->ops.back().out_t].off, dy, net->mu, net->classes, out_loss_dev, count, stream));
+  TRY(launch_softmax_ce(bf, net->scores_f32, ws, labs, T[(size_t)net->ops.back().out_t].off, dy, net->loss_off, net->mu, net->classes,
+                        out_loss_dev, count, stream));
   // ---- backward
   for (int k = (int)net->ops.size() - 1; k >= 0; k--) {
     const Op& op = net->ops[(size_t)k];
@@ -410,6 +414,7 @@ hipError_t net_calc_gradient(Net* net, const int* learners, const LearnerBind* b
             const int64_t tiles = (int64_t)((gw.Ncols + 127) / 128) * ((gw.Kchunks * 8 + 1 + 127) / 128);
             gw.scratch_off = net->scratch_off;
             gw.splits = choose_splits(tiles, count, (gw.M + 31) / 32, (size_t)gw.Ncols * (gw.Kchunks * 8 + 8) * 4, net->scratch_bytes);
+            if ((size_t)(gw.Kchunks * 8 + 1) * 4 > 60 * 1024) gw.splits = 1;   // the second pass keeps one filter row in LDS
           }
           TRY(launch_igemm_wgrad(ws, grads, gw, op.vc, dy, op.w_off, op.b_off, count, stream));
           if (need_dx) {
