@@ -550,7 +550,6 @@ __global__ __launch_bounds__(256) void igemm_wgrad_kernel(PtrTab ws, PtrTab grad
 
   const int z = blockIdx.z / g.splits, sp = blockIdx.z % g.splits;
   const bf16_t* x = (const bf16_t*)ws.p[z] + g.a_off;
-  const bf16_t* zeros = (const bf16_t*)ws.p[z] + g.zero_off;
   const bf16_t* dy = (const bf16_t*)ws.p[z] + dy_off;
   const int n0 = blockIdx.x * BMG, k0 = blockIdx.y * BNG;   // output-channel and im2col-column origins
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -558,25 +557,60 @@ __global__ __launch_bounds__(256) void igemm_wgrad_kernel(PtrTab ws, PtrTab grad
 
   constexpr int CPR_A = BMG / 8, CPR_B = BNG / 8;
   constexpr int A_LOADS = (BK * CPR_A + 255) / 256, B_LOADS = (BK * CPR_B + 255) / 256;
-  uint4 ra[A_LOADS], rb[B_LOADS];
+  const int all_steps = (g.M + BK - 1) / BK;
+  const int per = (all_steps + g.splits - 1) / g.splits;
+  const int ms_begin = sp * per;
+  const int msteps = min(all_steps, ms_begin + per);
+
+  // Hardware-bounds-checked buffer loads (an offset at or beyond the tensor reads as zero): rows beyond M, columns
+  // beyond the layer and taps in the zero padding need no branch and no patching of loaded data.
+  const __amdgpu_buffer_rsrc_t rsrc_dy = __builtin_amdgcn_make_buffer_rsrc((void*)dy, 0, (int)((int64_t)g.M * g.Ncols * 2), 0x00020000);
+  const __amdgpu_buffer_rsrc_t rsrc_x = __builtin_amdgcn_make_buffer_rsrc((void*)x, 0, (int)g.a_bytes, 0x00020000);
+  // dy tile: chunk (row r, 8 channels from n) per thread; its offset advances by a constant every step
+  uint32_t a_off[A_LOADS];
+#pragma unroll
+  for (int i = 0; i < A_LOADS; i++) {
+    const int idx = tid + 256 * i;
+    const int r = idx / CPR_A, n = n0 + (idx % CPR_A) * 8;
+    a_off[i] = (r < BK && n < g.Ncols) ? (uint32_t)((((int64_t)ms_begin * BK + r) * g.Ncols + n) * 2) : kOutOfRange;
+  }
+  // im2col tile: the filter tap of a thread's chunk is fixed, only the output position changes from step to step
+  int b_row[B_LOADS], b_kh[B_LOADS], b_kw[B_LOADS], b_koff[B_LOADS];
+  bool b_ok[B_LOADS], b_ones[B_LOADS];
+#pragma unroll
+  for (int i = 0; i < B_LOADS; i++) {
+    const int idx = tid + 256 * i;
+    const int q = k0 / 8 + idx % CPR_B;
+    const uint32_t tap = fastdiv((uint32_t)q, g.CPT, g.mg_cpt);
+    const int c8 = q - (int)tap * g.CPT;
+    b_row[i] = idx / CPR_B;
+    b_kh[i] = (int)fastdiv(tap, g.ks, g.mg_ks);
+    b_kw[i] = (int)tap - b_kh[i] * g.ks;
+    b_koff[i] = ((b_kh[i] * g.W + b_kw[i]) * g.C + c8 * 8) * 2;
+    b_ok[i] = b_row[i] < BK && q < g.Kchunks;
+    b_ones[i] = b_row[i] < BK && q == g.Kchunks;   // the bias column: im2col value 1 for every real output position
+  }
+  v4i_t ra[A_LOADS], rb[B_LOADS];
+  uint32_t bias_one[B_LOADS];
   auto load_regs = [&](int ms) {
 #pragma unroll
     for (int i = 0; i < A_LOADS; i++) {
-      const int idx = tid + 256 * i;
-      const int r = idx / CPR_A, ch = idx % CPR_A;
-      const int m = ms * BK + r, n = n0 + ch * 8;
-      ra[i] = ld16_or_zero(dy + (int64_t)m * g.Ncols + n, r < BK && m < g.M && n < g.Ncols, zeros);
+      ra[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_dy, (int)a_off[i], 0, 0);
+      a_off[i] += (uint32_t)(BK * g.Ncols * 2);
     }
 #pragma unroll
     for (int i = 0; i < B_LOADS; i++) {
-      const int idx = tid + 256 * i;
-      const int r = idx / CPR_B, ch = idx % CPR_B;
-      const int q = k0 / 8 + ch;
-      RowPos rp = row_pos(x, g, ms * BK + r);
-      // the bias column (chunk index Kchunks) reads the constant chunk {1, 0, ...} for every real output position
-      const bool ones = q == g.Kchunks && rp.valid;
-      rp.valid = rp.valid && !ones;
-      rb[i] = gather_chunk(rp, g, q, ones ? zeros + 128 : zeros);
+      const int m = ms * BK + b_row[i];
+      const bool valid = m < g.M;
+      const uint32_t mm = valid ? (uint32_t)m : 0u;
+      const uint32_t rest = fastdiv(mm, g.OW, g.mg_ow);
+      const int ow = (int)(mm - rest * (uint32_t)g.OW) - g.pad + b_kw[i];
+      const uint32_t n = fastdiv(rest, g.OH, g.mg_oh);
+      const int oh = (int)(rest - n * (uint32_t)g.OH) - g.pad + b_kh[i];
+      const bool ok = b_ok[i] && valid && (unsigned)oh < (unsigned)g.H && (unsigned)ow < (unsigned)g.W;
+      const int off = (int)(((n * (uint32_t)g.H + (uint32_t)(oh - b_kh[i])) * (uint32_t)g.W + (uint32_t)(ow - b_kw[i])) * (uint32_t)g.C * 2u) + b_koff[i];
+      rb[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_x, ok ? off : (int)kOutOfRange, 0, 0);
+      bias_one[i] = (b_ones[i] && valid) ? 0x3F80u : 0u;
     }
   };
   auto store_lds = [&](int buf) {
@@ -586,13 +620,15 @@ __global__ __launch_bounds__(256) void igemm_wgrad_kernel(PtrTab ws, PtrTab grad
     for (int i = 0; i < A_LOADS; i++) {
       int idx = tid + 256 * i;
       int r = idx / CPR_A, ch = idx % CPR_A;
-      if (r < BK) *reinterpret_cast<uint4*>(A + r * LDT_A + ch * 8) = ra[i];
+      if (r < BK) *reinterpret_cast<v4i_t*>(A + r * LDT_A + ch * 8) = ra[i];
     }
 #pragma unroll
     for (int i = 0; i < B_LOADS; i++) {
       int idx = tid + 256 * i;
       int r = idx / CPR_B, ch = idx % CPR_B;
-      if (r < BK) *reinterpret_cast<uint4*>(B + r * LDT_B + ch * 8) = rb[i];
+      v4i_t val = rb[i];
+      val.x |= (int)bias_one[i];                 // the chunk of the bias column loads as zeros; its first element becomes 1.0
+      if (r < BK) *reinterpret_cast<v4i_t*>(B + r * LDT_B + ch * 8) = val;
     }
   };
 
@@ -604,10 +640,6 @@ __global__ __launch_bounds__(256) void igemm_wgrad_kernel(PtrTab ws, PtrTab grad
 #pragma unroll
       for (int r = 0; r < 16; r++) acc[i][j][r] = 0.f;
 
-  const int all_steps = (g.M + BK - 1) / BK;
-  const int per = (all_steps + g.splits - 1) / g.splits;
-  const int ms_begin = sp * per;
-  const int msteps = min(all_steps, ms_begin + per);
   if (ms_begin < msteps) {
     load_regs(ms_begin);
     store_lds(ms_begin & 1);

@@ -268,6 +268,8 @@ int net_create(const sasgd_config& cfg, Net** out, int64_t* out_P, size_t* out_p
   }
   size_t maxe = 0;
   for (const Tensor& t : net->tensors) maxe = t.elems > maxe ? t.elems : maxe;
+  // the kernels address an activation tensor through 32-bit byte offsets with the top bit reserved for "out of range"
+  if (maxe * 4 >= ((size_t)1 << 31)) { delete net; err = "an activation tensor of mu images exceeds 2 GiB: lower mu"; return SASGD_ERANGE; }
   net->grad_elems = (maxe + 63) & ~(size_t)63;
   net->grad_a = cursor;
   net->grad_b = cursor + net->grad_elems;
