@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the staleness-aware n-softsync ASGD hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload server|cifar|alex|cifar-fp32-c4|cifar-fp32-c1]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload server|cifar|alex|cifar-fp32-c4|cifar-fp32-c1|alex-calc|cifar-calc]
 
 Default workload "server" is BASELINE config 1, the parameter-server microbenchmark: P = 60 M fp32
 parameters, lambda = 54 gradients resident in HBM, momentum 0.9, weight decay 5e-4.  One step consumes every
@@ -9,6 +9,8 @@ learner's gradient once in each of the two protocols the config names:
     54-softsync: 54 consecutive sumGradients+applyUpdate with c = 1   (20 B per parameter and update)
      1-softsync:  1 sumGradients+applyUpdate with c = 54              (232 B per parameter)
 The printed value is algorithmic HBM bytes (4 (c + 4) per parameter and update) over wall time of the step.
+The other workloads run the whole path (calcGradient + sumGradients + applyUpdate) on BASELINE configs 3, 4, 0, 2;
+"alex-calc" / "cifar-calc" time calcGradient alone with all lambda learners in one batched call.
 Prints ONE JSON line.
 """
 import argparse
@@ -222,6 +224,58 @@ def bench_net(args, cfg_id):
     return out
 
 
+def bench_calc(args, cfg_id):
+    """calcGradient alone (the learners' half of the path): all lambda learners of BASELINE config 3 or 4 on the
+    current weights in ONE batched call per step; no server update inside the timed region."""
+    import torch
+    import workloads as wl
+    from paper_1511_05950_amd import binding
+
+    cfg = wl.config(cfg_id)
+    net, lam, mu = cfg["net"], cfg["lam"], cfg["mu"]
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    X = torch.randn((lam * mu,) + net["input"], device=dev, generator=torch.Generator(device=dev).manual_seed(cfg_id))
+    Y = torch.randint(0, net["classes"], (lam * mu,), device=dev, dtype=torch.int32)
+    ctx = binding.Sasgd(lam, mu, lam, 1, net=net["name"], compute=cfg["compute"], init_weights=cfg["weights"]())
+    learners = list(range(lam))
+
+    def step():
+        for L in learners:
+            ctx.getMinibatch(L, X[L * mu:(L + 1) * mu], Y[L * mu:(L + 1) * mu])
+            ctx.pullWeights(L, 0)
+        ctx.calcGradient(learners)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ctx.setProfiling(True)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_g, n_g = ctx.phaseTime(0)
+    P = ctx.P
+    ctx.destroy()
+    images = args.steps * lam * mu
+    flop_img = {3: 68.87424e6, 4: 6.585512448e9}[cfg_id]
+    ach = images * flop_img / (ms_g * 1e-3) / 1e12
+    out = {
+        "metric": "calcGradient images/sec per GPU (no server update)", "value": round(images / dt, 1), "unit": "images/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(dt / args.steps * 1e3, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "calcGradient only, shapes of BASELINE config %d: %s net, %d learners x mu=%d in one batched call, "
+                               "bf16 compute" % (cfg_id, net["name"], lam, mu), "num_params": P},
+        "roofline": {"bound": "mfma", "kernel": "calcGradient (all launches of one batched call of %d learners)" % lam,
+                     "achieved": round(ach, 2), "peak": 2500.0, "unit": "TFLOP/s", "frac": round(ach / 2500.0, 5),
+                     "traffic": None, "avg_call_us": round(ms_g / n_g * 1e3, 1), "learners_per_call": lam},
+    }
+    if not args.no_cpu:
+        out["cpu_baseline"] = cpu_baseline_net(cfg)
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -240,6 +294,8 @@ def main():
         out = bench_server(args)
     elif args.workload in ("cifar", "alex", "cifar-fp32-c4", "cifar-fp32-c1"):
         out = bench_net(args, {"cifar": 3, "alex": 4, "cifar-fp32-c4": 0, "cifar-fp32-c1": 2}[args.workload])
+    elif args.workload in ("cifar-calc", "alex-calc"):
+        out = bench_calc(args, {"cifar-calc": 3, "alex-calc": 4}[args.workload])
     else:
         raise SystemExit("unknown workload " + args.workload)
     print(json.dumps(out))

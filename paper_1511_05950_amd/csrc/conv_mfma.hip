@@ -31,43 +31,56 @@ constexpr int LDA = BK + 8;      // row stride (elements) of k-contiguous LDS ti
 //   frag[(nb * KB16 + kb) * 512 + lane * 8 + t] = B[row 32 nb + lane%32][k = 16 kb + 8 (lane/32) + t]
 // fwd: B = Wp[n][tap][cp] (k = tap * C + cp, Kp = padded ks*ks*C);   rows beyond K and k beyond the filter are zero
 // bwd: B = Wt[c][tap'][n] (k = tap' * K + n, tap' = flipped tap, Kpt = padded ks*ks*K), stride-1 layers only
+// One thread produces one lane's 16-byte chunk (8 consecutive k of one row); index arithmetic is 32-bit.
 __global__ __launch_bounds__(256) void pack_filters_kernel(const bf16_t* __restrict__ flat, bf16_t* __restrict__ packed, PackTable t) {
-  for (int64_t gi = (int64_t)blockIdx.x * 256 + threadIdx.x; gi < t.total; gi += (int64_t)gridDim.x * 256) {
-    int li = 0;                                   // layer this element belongs to
-    while (li + 1 < t.count && gi >= t.job[li + 1].start) li++;
+  const int64_t chunks = t.total >> 3;
+  for (int64_t gc = (int64_t)blockIdx.x * 256 + threadIdx.x; gc < chunks; gc += (int64_t)gridDim.x * 256) {
+    int li = 0;                                   // layer this chunk belongs to
+    while (li + 1 < t.count && gc * 8 >= t.job[li + 1].start) li++;
     const PackJob& jb = t.job[li];
     const VConv& v = jb.v;
-    const int64_t i = gi - jb.start;
-    const int64_t nf = (int64_t)((v.K + 31) & ~31) * jb.Kp;
+    const uint32_t i = (uint32_t)(gc * 8 - jb.start);
+    const uint32_t nf = (uint32_t)((v.K + 31) & ~31) * (uint32_t)jb.Kp;
     const bool fwd = i < nf;
-    const int64_t e = fwd ? i : i - nf;
-    const int KB16 = (fwd ? jb.Kp : jb.Kpt) / 16;
-    const int t8 = (int)(e & 7), lane = (int)((e >> 3) & 63);
-    const int64_t blk = e >> 9;
-    const int kb = (int)(blk % KB16), rb = (int)(blk / KB16);
-    const int row = 32 * rb + (lane & 31), k = 16 * kb + 8 * (lane >> 5) + t8;
-    bf16_t val = 0;
+    const uint32_t e = fwd ? i : i - nf;
+    const uint32_t KB16 = (uint32_t)(fwd ? jb.Kp : jb.Kpt) / 16u;
+    const uint32_t lane = (e >> 3) & 63u, blk = e >> 9;
+    const uint32_t rb = blk / KB16, kb = blk - rb * KB16;
+    const int row = (int)(32u * rb + (lane & 31u));
+    const uint32_t k0 = 16u * kb + 8u * (lane >> 5);
+    const int taps = v.ks * v.ks;
+    union { bf16_t h[8]; uint4 q; } out;
+    out.q = make_uint4(0u, 0u, 0u, 0u);
     if (fwd) {
-      int tap = k / v.C, cp = k % v.C;
-      if (row < v.K && tap < v.ks * v.ks) {
-        int64_t src = filter_src(v, row, tap, cp);
-        if (src >= 0) val = flat[jb.w_off + src];
+      // k = tap * C + cp; C is a multiple of 8, so the 8 elements share the tap
+      const int tap = (int)(k0 / (uint32_t)v.C), cp0 = (int)(k0 - (uint32_t)tap * (uint32_t)v.C);
+      if (row < v.K && tap < taps) {
+#pragma unroll
+        for (int j = 0; j < 8; j++) {
+          const int64_t src = filter_src(v, row, tap, cp0 + j);
+          if (src >= 0) out.h[j] = flat[jb.w_off + src];
+        }
       }
-      packed[jb.fwd_off + e] = val;
+      *reinterpret_cast<uint4*>(packed + jb.fwd_off + e) = out.q;
     } else {
-      int tap = k / v.K, n = k % v.K;
-      if (row < v.C && tap < v.ks * v.ks) {
-        int64_t src = filter_src(v, n, v.ks * v.ks - 1 - tap, row);   // flipped tap (ks-1-kh, ks-1-kw)
-        if (src >= 0) val = flat[jb.w_off + src];
+      // k = tap' * K + n; K is a multiple of 8
+      const int tap = (int)(k0 / (uint32_t)v.K), n0 = (int)(k0 - (uint32_t)tap * (uint32_t)v.K);
+      if (row < v.C && tap < taps) {
+#pragma unroll
+        for (int j = 0; j < 8; j++) {
+          const int64_t src = filter_src(v, n0 + j, taps - 1 - tap, row);   // flipped tap (ks-1-kh, ks-1-kw)
+          if (src >= 0) out.h[j] = flat[jb.w_off + src];
+        }
       }
-      packed[jb.bwd_off + e] = val;
+      *reinterpret_cast<uint4*>(packed + jb.bwd_off + e) = out.q;
     }
   }
 }
 
 hipError_t launch_pack_filters(const void* flat, void* packed, const PackTable& t, hipStream_t s) {
   if (t.count == 0 || t.total == 0) return hipSuccess;
-  int blocks = (int)((t.total + 255) / 256 < 4096 ? (t.total + 255) / 256 : 4096);
+  const int64_t chunks = t.total / 8;
+  int blocks = (int)((chunks + 255) / 256 < 8192 ? (chunks + 255) / 256 : 8192);
   hipLaunchKernelGGL(pack_filters_kernel, dim3(blocks), dim3(256), 0, s, (const bf16_t*)flat, (bf16_t*)packed, t);
   return hipGetLastError();
 }
