@@ -143,6 +143,30 @@ int sasgd_sumGradients(sasgd_ctx* ctx, int32_t* out_pending);
  * overwritten holds a version some learner has pulled but not yet used. */
 int sasgd_applyUpdate(sasgd_ctx* ctx, int64_t* out_new_timestamp);
 
+/* ---- training-loop pieces around the hot path (Sections 4.1 - 4.3) ---------------------- */
+
+/* evaluate: forward pass only over the bound mini-batches of the listed learners, each on its
+ * bound weight version (the test / validation error curves of Section 4.3).  Nothing is
+ * consumed: bindings, gradients and the protocol state stay as they are.
+ * out_loss_dev: optional device float[count], mean loss per listed learner.
+ * out_rank_dev: device int32[count * mu]; entry k*mu + s is the number of classes that precede
+ * the true class of image s of learners[k] when the class scores are sorted in descending
+ * order (equal scores: lower class index first).  rank >= 1 is a top-1 error, rank >= 5 a
+ * top-5 error; a label outside [0, classes) gets rank = classes.
+ * Errors: ESTATE if a listed learner has no mini-batch or weights bound; EINVAL as calcGradient. */
+int sasgd_evaluate(sasgd_ctx* ctx, const int32_t* learners, int32_t count, float* out_loss_dev, int32_t* out_rank_dev);
+
+/* Step decay of the base learning rate alpha0 (Section 4.3 lowers it by a constant factor at
+ * fixed epochs).  Takes effect from the next sumGradients.  Errors: EINVAL unless finite and >= 0;
+ * ESTATE while a window is closed (its coefficients are already fixed). */
+int sasgd_setBaseRate(sasgd_ctx* ctx, float alpha0);
+
+/* Per-pixel mean (Section 4.1 preprocessing): mean_dev is device float32 [C][H][W], subtracted
+ * in fp32 from every image while calcGradient / evaluate re-lay out their input; NULL switches
+ * it off.  Caller-owned; must stay valid while in use.  Errors: EINVAL for NET_NONE or a
+ * pointer that is not 4-byte aligned. */
+int sasgd_setPixelMean(sasgd_ctx* ctx, const float* mean_dev);
+
 /* ---- getters -------------------------------------------------------------------------- */
 int sasgd_timestamp(sasgd_ctx* ctx, int64_t* out);
 int sasgd_numParams(sasgd_ctx* ctx, int64_t* out);

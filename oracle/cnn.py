@@ -32,6 +32,7 @@ def lib():
         build()
         _lib = ctypes.CDLL(_LIB)
         _lib.cnn_loss_and_gradient.restype = ctypes.c_double
+        _lib.cnn_class_scores.restype = ctypes.c_double
         _lib.cnn_num_params.restype = ctypes.c_long
         _lib.round_to_bf16.restype = ctypes.c_double
         _lib.round_to_bf16.argtypes = [ctypes.c_double]
@@ -90,3 +91,35 @@ def make_callback(net, round_bf16=False):
         loss, g = loss_and_gradient(net, theta, batch[0], batch[1], round_bf16=round_bf16)
         return g, loss
     return cb
+
+
+def class_scores(net, theta, x, label, round_bf16=False):
+    """(loss, scores[N][classes]) of a forward-only evaluation pass (Section 4.3: test / validation error)."""
+    t = _table(net)
+    c, h, w = net["input"]
+    theta = np.ascontiguousarray(theta, dtype=np.float64)
+    x = np.ascontiguousarray(x, dtype=np.float64)
+    label = np.ascontiguousarray(label, dtype=np.int32)
+    n = x.shape[0]
+    assert x.shape == (n, c, h, w) and label.shape == (n,)
+    scores = np.empty((n, net["classes"]), np.float64)
+    loss = lib().cnn_class_scores(
+        _dp(t), ctypes.c_int(len(t)), ctypes.c_int(c), ctypes.c_int(h), ctypes.c_int(w), ctypes.c_int(n),
+        _dp(theta), ctypes.c_long(theta.size), _dp(x), _dp(label), _dp(scores), ctypes.c_int(1 if round_bf16 else 0))
+    return float(loss), scores
+
+
+def label_rank(scores, label):
+    """Position of the true class when the classes are sorted by descending score (equal scores: lower index
+    first).  rank >= 1 is a top-1 error, rank >= 5 a top-5 error (the error measures of Section 4.3)."""
+    scores = np.asarray(scores)
+    out = np.empty(len(label), np.int32)
+    for s in range(len(label)):
+        y = int(label[s])
+        zy = scores[s, y]
+        before = 0
+        for j in range(scores.shape[1]):
+            if scores[s, j] > zy or (scores[s, j] == zy and j < y):
+                before += 1
+        out[s] = before
+    return out

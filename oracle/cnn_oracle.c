@@ -284,9 +284,9 @@ double softmax_ce(const double* z, const int* label, double* dz, int N, int K) {
  *   grad [P]       : output (may be NULL for a forward-only loss evaluation)
  * Returns the loss, or NaN when P does not match the network.
  */
-double cnn_loss_and_gradient(const olayer* layers, int nlayers, int C, int H, int W, int N,
-                             const double* theta_in, long P, const double* x, const int* label,
-                             double* grad, int round_bf16) {
+static double loss_gradient_scores(const olayer* layers, int nlayers, int C, int H, int W, int N,
+                                   const double* theta_in, long P, const double* x, const int* label,
+                                   double* grad, double* scores, int round_bf16) {
   double* theta = (double*)malloc(sizeof(double) * (size_t)P);
   memcpy(theta, theta_in, sizeof(double) * (size_t)P);
   round_array(theta, (size_t)P, round_bf16);
@@ -337,6 +337,7 @@ double cnn_loss_and_gradient(const olayer* layers, int nlayers, int C, int H, in
   if (pos == P) {
     int K = sc[3 * nlayers] * sc[3 * nlayers + 1] * sc[3 * nlayers + 2];
     double* d = (double*)malloc(sizeof(double) * (size_t)N * K);
+    if (scores) memcpy(scores, act[nlayers], sizeof(double) * (size_t)N * K);
     loss = softmax_ce(act[nlayers], label, d, N, K);
     round_array(d, (size_t)N * K, round_bf16);
     /* backward */
@@ -369,6 +370,23 @@ double cnn_loss_and_gradient(const olayer* layers, int nlayers, int C, int H, in
   for (int li = 0; li < nlayers; li++) free(argm[li]);
   free(act); free(argm); free(sc); free(off); free(theta);
   return loss;
+}
+
+double cnn_loss_and_gradient(const olayer* layers, int nlayers, int C, int H, int W, int N,
+                             const double* theta_in, long P, const double* x, const int* label,
+                             double* grad, int round_bf16) {
+  return loss_gradient_scores(layers, nlayers, C, H, W, N, theta_in, P, x, label, grad, NULL, round_bf16);
+}
+
+/*
+ * Evaluation pass (the test / validation error of Section 4.3): forward only.
+ *   scores [N][K] : output of the last layer (K classes), the input of the softmax
+ * Returns the mean loss, or NaN when P does not match the network.
+ */
+double cnn_class_scores(const olayer* layers, int nlayers, int C, int H, int W, int N,
+                        const double* theta_in, long P, const double* x, const int* label,
+                        double* scores, int round_bf16) {
+  return loss_gradient_scores(layers, nlayers, C, H, W, N, theta_in, P, x, label, NULL, scores, round_bf16);
 }
 
 /* number of parameters of a layer table (for the parameter-count pins) */

@@ -71,9 +71,24 @@ def server_update(theta, v, grads, taus, alpha0, momentum=0.0, weight_decay=0.0,
     return theta - v_next, v_next
 
 
+def step_decay(alpha0, boundaries, factor, K):
+    """Base rate of each of K updates when alpha0 is divided by `factor` once update index i has reached each
+    boundary (Section 4.3: the rate is lowered by a constant factor after fixed epochs)."""
+    out = np.empty(K, np.float64)
+    for i in range(K):
+        a = float(alpha0)
+        for b in boundaries:
+            if i >= b:
+                a = a / factor
+        out[i] = a
+    return out
+
+
 def run(grad_fn, theta0, batches, schedule, lam, n, alpha0, momentum=0.0, weight_decay=0.0,
         mode=PER_GRADIENT, keep=None, on_gradient=None):
     """Run K = len(schedule) server updates.
+
+    alpha0: the base rate, a scalar or an array of K values (one per update, e.g. from step_decay).
 
     grad_fn(theta, batch) -> (g, loss): a learner's calcGradient on weights theta.
     batches(i, l) -> batch of the l-th gradient of update i.
@@ -106,7 +121,8 @@ def run(grad_fn, theta0, batches, schedule, lam, n, alpha0, momentum=0.0, weight
             taus.append(tau)
             ls.append(loss)
             log.append((i, l, learner, j, tau))
-        theta, v = server_update(theta, v, grads, taus, alpha0, momentum, weight_decay, mode)
+        a_i = float(alpha0) if np.ndim(alpha0) == 0 else float(alpha0[i])
+        theta, v = server_update(theta, v, grads, taus, a_i, momentum, weight_decay, mode)
         i += 1
         thetas[i] = theta.copy()
         if keep is not None:

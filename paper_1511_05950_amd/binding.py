@@ -27,6 +27,7 @@ EXPORTS = [
     "sasgd_timestamp", "sasgd_numParams", "sasgd_gradientsPerUpdate", "sasgd_gradientTimestamp",
     "sasgd_copyWeights", "sasgd_copyGradient", "sasgd_copyMomentum", "sasgd_gradientPtr",
     "sasgd_setProfiling", "sasgd_phaseTime", "sasgd_last_error", "sasgd_version",
+    "sasgd_evaluate", "sasgd_setBaseRate", "sasgd_setPixelMean",
 ]
 
 
@@ -90,6 +91,9 @@ def load():
         lib.sasgd_gradientPtr.argtypes = [vp, i32, P(vp)]
         lib.sasgd_setProfiling.argtypes = [vp, i32]
         lib.sasgd_phaseTime.argtypes = [vp, i32, P(ctypes.c_double), P(i64)]
+        lib.sasgd_evaluate.argtypes = [vp, P(i32), i32, vp, vp]
+        lib.sasgd_setBaseRate.argtypes = [vp, ctypes.c_float]
+        lib.sasgd_setPixelMean.argtypes = [vp, vp]
         lib.sasgd_last_error.argtypes = [vp]
         lib.sasgd_last_error.restype = ctypes.c_char_p
         lib.sasgd_version.restype = ctypes.c_char_p
@@ -205,6 +209,18 @@ class Sasgd:
         tau = ctypes.c_int32()
         self._check(load().sasgd_pushGradientExternal(self._h, _addr(grad_dev), timestamp, ctypes.byref(tau)))
         return tau.value
+
+    # -- training-loop pieces around the hot path
+    def evaluate(self, learners, out_loss_dev, out_rank_dev):
+        arr = (ctypes.c_int32 * len(learners))(*learners)
+        self._check(load().sasgd_evaluate(self._h, arr, len(learners), _addr(out_loss_dev), _addr(out_rank_dev)))
+
+    def setBaseRate(self, alpha0):
+        self._check(load().sasgd_setBaseRate(self._h, alpha0))
+
+    def setPixelMean(self, mean_dev):
+        self._keep_mean = mean_dev          # the library reads it on every later calcGradient / evaluate
+        self._check(load().sasgd_setPixelMean(self._h, _addr(mean_dev)))
 
     # -- server side
     def sumGradients(self):

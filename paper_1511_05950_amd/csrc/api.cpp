@@ -5,6 +5,7 @@
 #include <string.h>
 
 #include <algorithm>
+#include <cmath>
 #include <new>
 
 #include "ctx.hpp"
@@ -259,7 +260,7 @@ int sasgd_calcGradient(sasgd_ctx* ctx, const int32_t* learners, int32_t count, f
     binds[k].grad = L.grad;
   }
   prof_begin(ctx, 0);
-  hipError_t e = net_calc_gradient(ctx->net, ids, binds, count, out_loss_dev, ctx->stream);
+  hipError_t e = net_calc_gradient(ctx->net, ids, binds, count, out_loss_dev, nullptr, ctx->stream);
   prof_end(ctx);
   if (e != hipSuccess) return fail_hip(ctx, e, "calcGradient");
   for (int k = 0; k < count; k++) {
@@ -270,6 +271,49 @@ int sasgd_calcGradient(sasgd_ctx* ctx, const int32_t* learners, int32_t count, f
     L.images = nullptr;
     L.labels = nullptr;
   }
+  return SASGD_OK;
+}
+
+int sasgd_evaluate(sasgd_ctx* ctx, const int32_t* learners, int32_t count, float* out_loss_dev, int32_t* out_rank_dev) {
+  if (!ctx) return SASGD_EINVAL;
+  if (!ctx->net) return fail(ctx, SASGD_EINVAL, "evaluate: context has no network");
+  if (!learners || count < 1 || count > ctx->cfg.lambda) return fail(ctx, SASGD_EINVAL, "evaluate: bad learner list");
+  if (!out_rank_dev || ((uintptr_t)out_rank_dev & 3)) return fail(ctx, SASGD_EINVAL, "evaluate: out_rank_dev must be a device int32 array");
+  bool seen[kMaxLearners] = {false};
+  LearnerBind binds[kMaxLearners];
+  int ids[kMaxLearners];
+  for (int k = 0; k < count; k++) {
+    const int l = learners[k];
+    if (l < 0 || l >= ctx->cfg.lambda || seen[l]) return fail(ctx, SASGD_EINVAL, "evaluate: bad or duplicate learner");
+    seen[l] = true;
+    const Learner& L = ctx->learners[(size_t)l];
+    if (!L.images || !L.has_weights) return fail(ctx, SASGD_ESTATE, "evaluate: learner has no mini-batch or no weights bound");
+    if (!version_in_ring(ctx, L.pulled_version)) return fail(ctx, SASGD_ERANGE, "evaluate: pulled version has left the ring");
+    ids[k] = l;
+    binds[k].images = L.images;
+    binds[k].labels = L.labels;
+    binds[k].weights = version_ptr(ctx, L.pulled_version);
+    binds[k].version = L.pulled_version;
+    binds[k].grad = nullptr;             // the evaluation pass writes no gradient
+  }
+  hipError_t e = net_calc_gradient(ctx->net, ids, binds, count, out_loss_dev, out_rank_dev, ctx->stream);
+  if (e != hipSuccess) return fail_hip(ctx, e, "evaluate");
+  return SASGD_OK;
+}
+
+int sasgd_setBaseRate(sasgd_ctx* ctx, float alpha0) {
+  if (!ctx) return SASGD_EINVAL;
+  if (!(alpha0 >= 0.f) || !std::isfinite(alpha0)) return fail(ctx, SASGD_EINVAL, "setBaseRate: alpha0 must be finite and not negative");
+  if (ctx->window_closed) return fail(ctx, SASGD_ESTATE, "setBaseRate: a window is closed; call applyUpdate first");
+  ctx->cfg.alpha0 = alpha0;
+  return SASGD_OK;
+}
+
+int sasgd_setPixelMean(sasgd_ctx* ctx, const float* mean_dev) {
+  if (!ctx) return SASGD_EINVAL;
+  if (!ctx->net) return fail(ctx, SASGD_EINVAL, "setPixelMean: context has no network");
+  if ((uintptr_t)mean_dev & 3) return fail(ctx, SASGD_EINVAL, "setPixelMean: pointer must be 4-byte aligned");
+  net_set_pixel_mean(ctx->net, mean_dev);
   return SASGD_OK;
 }
 

@@ -48,8 +48,12 @@ size_t net_workspace_bytes(const Net* net);
 hipError_t net_set_workspace(Net* net, int learner, void* ws, hipStream_t stream);
 // Per weight version: derive the kernel-friendly copies (bf16 repacked conv filters) from the flat vector.
 hipError_t net_prepare_version(Net* net, const void* flat, void* packed, hipStream_t stream);
+// out_rank_dev == nullptr: forward, loss, backward (gradients into binds[k].grad).
+// out_rank_dev != nullptr: evaluation pass, forward and loss only, plus the rank of each image's true class.
 hipError_t net_calc_gradient(Net* net, const int* learners, const LearnerBind* binds, int count,
-                             float* out_loss_dev, hipStream_t stream);
+                             float* out_loss_dev, int32_t* out_rank_dev, hipStream_t stream);
+void net_set_pixel_mean(Net* net, const float* mean_dev);
+void net_input_shape(const Net* net, int* C, int* H, int* W);
 
 // ---------------------------------------------------------------- context
 enum GradState { GRAD_NONE = 0, GRAD_COMPUTED = 1, GRAD_PENDING = 2 };

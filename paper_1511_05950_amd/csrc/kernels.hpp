@@ -103,7 +103,7 @@ struct Epilogue {
 
 // is_bf16 selects T.  All offsets are in elements of T from the learner's workspace base, except where noted.
 hipError_t launch_pack_input(bool is_bf16, const CPtrTab& images, const PtrTab& ws, size_t out_off, int count, int N,
-                             const InPack& ip, hipStream_t s);
+                             const InPack& ip, const float* mean, hipStream_t s);
 
 // ---- bf16 MFMA path (conv_mfma.hip)
 // One launch repacks the filters of every MFMA convolution of a weight version.
@@ -161,5 +161,7 @@ hipError_t launch_flatten_bwd(bool is_bf16, const PtrTab& ws, size_t dy_off, siz
 // loss_byte_off: N floats of per-image losses in the workspace (bytes from its base).
 hipError_t launch_softmax_ce(bool is_bf16, bool z_f32, const PtrTab& ws, const CPtrTab& labels, size_t z_off, size_t dz_off,
                              size_t loss_byte_off, int N, int K, float* loss_out, int count, hipStream_t s);
+hipError_t launch_label_rank(bool is_bf16, bool z_f32, const PtrTab& ws, const CPtrTab& labels, size_t z_off, int N, int K,
+                             int32_t* rank_out, int count, hipStream_t s);
 
 }  // namespace sasgd

@@ -32,7 +32,8 @@ __device__ __forceinline__ uint4 pack8(const float* f) {
 
 // ------------------------------------------------------------------ input NCHW fp32 -> NHWC T
 template <typename T>
-__global__ __launch_bounds__(256) void pack_input_kernel(CPtrTab images, PtrTab ws, size_t out_off, int N, InPack ip) {
+__global__ __launch_bounds__(256) void pack_input_kernel(CPtrTab images, PtrTab ws, size_t out_off, int N, InPack ip,
+                                                         const float* __restrict__ mean) {
   const float* in = (const float*)images.p[blockIdx.z];
   T* out = (T*)ws.p[blockIdx.z] + out_off;
   const int64_t total = (int64_t)N * ip.Hp * ip.Wp * ip.Cp;
@@ -45,11 +46,17 @@ __global__ __launch_bounds__(256) void pack_input_kernel(CPtrTab images, PtrTab 
     int n = (int)(r / ip.Hp);
     float v = 0.f;
     if (ip.s2d == 1) {
-      if (cp < ip.C) v = in[(((int64_t)n * ip.C + cp) * ip.H + Y) * ip.W + X];
+      if (cp < ip.C) {
+        const int64_t pix = ((int64_t)cp * ip.H + Y) * ip.W + X;
+        v = in[(int64_t)n * ip.C * ip.H * ip.W + pix] - (mean ? mean[pix] : 0.f);
+      }
     } else {
       int g = cp / ip.C, c = cp % ip.C;
       int h = ip.s2d * Y + g / ip.s2d, w = ip.s2d * X + g % ip.s2d;
-      if (g < ip.s2d * ip.s2d && h < ip.H && w < ip.W) v = in[(((int64_t)n * ip.C + c) * ip.H + h) * ip.W + w];
+      if (g < ip.s2d * ip.s2d && h < ip.H && w < ip.W) {
+        const int64_t pix = ((int64_t)c * ip.H + h) * ip.W + w;
+        v = in[(int64_t)n * ip.C * ip.H * ip.W + pix] - (mean ? mean[pix] : 0.f);
+      }
     }
     stf(out + i, v);
   }
@@ -57,7 +64,8 @@ __global__ __launch_bounds__(256) void pack_input_kernel(CPtrTab images, PtrTab 
 
 // One lane per destination pixel (bf16, Cp % 8 == 0): the Cp channels are assembled in registers and written as
 // 16-byte chunks; neighbouring lanes read neighbouring source columns.
-__global__ __launch_bounds__(256) void pack_input_pixel_kernel(CPtrTab images, PtrTab ws, size_t out_off, int N, InPack ip) {
+__global__ __launch_bounds__(256) void pack_input_pixel_kernel(CPtrTab images, PtrTab ws, size_t out_off, int N, InPack ip,
+                                                               const float* __restrict__ mean) {
   const float* in = (const float*)images.p[blockIdx.z];
   bf16_t* out = (bf16_t*)ws.p[blockIdx.z] + out_off;
   const int64_t total = (int64_t)N * ip.Hp * ip.Wp;
@@ -75,11 +83,17 @@ __global__ __launch_bounds__(256) void pack_input_pixel_kernel(CPtrTab images, P
         const int cp = c0 + e;
         float v = 0.f;
         if (ip.s2d == 1) {
-          if (cp < ip.C) v = src[cp * plane + (int64_t)Y * ip.W + X];
+          if (cp < ip.C) {
+            const int64_t pix = cp * plane + (int64_t)Y * ip.W + X;
+            v = src[pix] - (mean ? mean[pix] : 0.f);
+          }
         } else {
           int g = cp / ip.C, c = cp - g * ip.C;
           int h = ip.s2d * Y + g / ip.s2d, w = ip.s2d * X + g % ip.s2d;
-          if (g < ip.s2d * ip.s2d && h < ip.H && w < ip.W) v = src[c * plane + (int64_t)h * ip.W + w];
+          if (g < ip.s2d * ip.s2d && h < ip.H && w < ip.W) {
+            const int64_t pix = c * plane + (int64_t)h * ip.W + w;
+            v = src[pix] - (mean ? mean[pix] : 0.f);
+          }
         }
         f[e] = v;
       }
@@ -89,15 +103,15 @@ __global__ __launch_bounds__(256) void pack_input_pixel_kernel(CPtrTab images, P
 }
 
 hipError_t launch_pack_input(bool is_bf16, const CPtrTab& images, const PtrTab& ws, size_t out_off, int count, int N,
-                             const InPack& ip, hipStream_t s) {
+                             const InPack& ip, const float* mean, hipStream_t s) {
   if (is_bf16 && ip.Cp % 8 == 0 && out_off % 8 == 0) {
     dim3 gv = grid_for((int64_t)N * ip.Hp * ip.Wp, count, 16384);
-    hipLaunchKernelGGL(pack_input_pixel_kernel, gv, dim3(256), 0, s, images, ws, out_off, N, ip);
+    hipLaunchKernelGGL(pack_input_pixel_kernel, gv, dim3(256), 0, s, images, ws, out_off, N, ip, mean);
     return hipGetLastError();
   }
   dim3 g = grid_for((int64_t)N * ip.Cp * ip.Hp * ip.Wp, count);
-  if (is_bf16) hipLaunchKernelGGL(pack_input_kernel<bf16_t>, g, dim3(256), 0, s, images, ws, out_off, N, ip);
-  else hipLaunchKernelGGL(pack_input_kernel<float>, g, dim3(256), 0, s, images, ws, out_off, N, ip);
+  if (is_bf16) hipLaunchKernelGGL(pack_input_kernel<bf16_t>, g, dim3(256), 0, s, images, ws, out_off, N, ip, mean);
+  else hipLaunchKernelGGL(pack_input_kernel<float>, g, dim3(256), 0, s, images, ws, out_off, N, ip, mean);
   return hipGetLastError();
 }
 
@@ -426,6 +440,38 @@ hipError_t launch_softmax_ce(bool is_bf16, bool z_f32, const PtrTab& ws, const C
   else if (is_bf16) hipLaunchKernelGGL((softmax_ce_kernel<bf16_t, bf16_t>), g, dim3(256), 0, s, ws, labels, z_off, dz_off, loss_byte_off, N, K);
   else hipLaunchKernelGGL((softmax_ce_kernel<float, float>), g, dim3(256), 0, s, ws, labels, z_off, dz_off, loss_byte_off, N, K);
   if (loss_out) hipLaunchKernelGGL(loss_mean_kernel, dim3(count), dim3(64), 0, s, ws, loss_byte_off, N, loss_out);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ evaluation: rank of the true class
+// rank[n] = number of classes ordered before the label's class when scores are sorted in descending order (equal
+// scores: lower class index first).  rank < k  <=>  the label is among the k best: top-1 / top-5 errors (Section 4.3)
+// are counts of rank >= 1 / rank >= 5.  A label outside [0, K) gets rank K.  One workgroup per image.
+template <typename T, typename Z>
+__global__ __launch_bounds__(256) void label_rank_kernel(PtrTab ws, CPtrTab labels, size_t z_off, int N, int K, int32_t* rank_out) {
+  __shared__ int red[4];
+  const int l = blockIdx.z, n = blockIdx.x;
+  const Z* zn = reinterpret_cast<const Z*>((const T*)ws.p[l] + z_off) + (int64_t)n * K;
+  const int y = ((const int32_t*)labels.p[l])[n];
+  const bool ok = y >= 0 && y < K;
+  const float zy = ok ? ldf(zn + y) : 0.f;
+  int cnt = 0;
+  for (int j = threadIdx.x; j < K; j += 256) {
+    const float zj = ldf(zn + j);
+    cnt += (zj > zy || (zj == zy && j < y)) ? 1 : 0;
+  }
+  for (int o = 32; o > 0; o >>= 1) cnt += __shfl_down(cnt, o, 64);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = cnt;
+  __syncthreads();
+  if (threadIdx.x == 0) rank_out[(int64_t)l * N + n] = ok ? (red[0] + red[1]) + (red[2] + red[3]) : K;
+}
+
+hipError_t launch_label_rank(bool is_bf16, bool z_f32, const PtrTab& ws, const CPtrTab& labels, size_t z_off, int N, int K,
+                             int32_t* rank_out, int count, hipStream_t s) {
+  dim3 g((unsigned)N, 1, (unsigned)count);
+  if (is_bf16 && z_f32) hipLaunchKernelGGL((label_rank_kernel<bf16_t, float>), g, dim3(256), 0, s, ws, labels, z_off, N, K, rank_out);
+  else if (is_bf16) hipLaunchKernelGGL((label_rank_kernel<bf16_t, bf16_t>), g, dim3(256), 0, s, ws, labels, z_off, N, K, rank_out);
+  else hipLaunchKernelGGL((label_rank_kernel<float, float>), g, dim3(256), 0, s, ws, labels, z_off, N, K, rank_out);
   return hipGetLastError();
 }
 

@@ -59,6 +59,7 @@ struct Net {
   size_t zero_off = 0;         // 256 zero bytes (element offset), target of out-of-range loads
   size_t scratch_off = 0, scratch_bytes = 0;   // split-contraction partials (bytes from the workspace base)
   void* ws[kMaxLearners] = {nullptr};
+  const float* pixel_mean = nullptr;   // optional [C][H][W] fp32, subtracted while the input is re-laid out
 };
 
 static int pool_out_size(int n, int k, int s) {
@@ -348,8 +349,12 @@ static void set_splits(const Net* net, IGemm& g, int steps, int count) {
   g.splits = choose_splits(tiles, count, steps, (size_t)g.M * g.Ncols * 4, net->scratch_bytes);
 }
 
+void net_set_pixel_mean(Net* net, const float* mean_dev) { net->pixel_mean = mean_dev; }
+void net_input_shape(const Net* net, int* C, int* H, int* W) { *C = net->inC; *H = net->inH; *W = net->inW; }
+
+// Forward pass, loss and (unless out_rank_dev is given, which makes this an evaluation pass) backward pass.
 hipError_t net_calc_gradient(Net* net, const int* learners, const LearnerBind* binds, int count, float* out_loss_dev,
-                             hipStream_t stream) {
+                             int32_t* out_rank_dev, hipStream_t stream) {
   PtrTab ws, grads;
   CPtrTab wts, imgs, labs;
   memset(&ws, 0, sizeof(ws)); memset(&grads, 0, sizeof(grads));
@@ -364,7 +369,7 @@ hipError_t net_calc_gradient(Net* net, const int* learners, const LearnerBind* b
   const bool bf = net->bf16;
   const std::vector<Tensor>& T = net->tensors;
   // ---- forward
-  TRY(launch_pack_input(bf, imgs, ws, T[0].off, count, net->mu, net->inpack, stream));
+  TRY(launch_pack_input(bf, imgs, ws, T[0].off, count, net->mu, net->inpack, net->pixel_mean, stream));
   for (const Op& op : net->ops) {
     const size_t xi = T[(size_t)op.in_t].off, yo = T[(size_t)op.out_t].off;
     switch (op.kind) {
@@ -395,6 +400,9 @@ hipError_t net_calc_gradient(Net* net, const int* learners, const LearnerBind* b
   size_t dy = net->grad_a, dx = net->grad_b;
   TRY(launch_softmax_ce(bf, net->scores_f32, ws, labs, T[(size_t)net->ops.back().out_t].off, dy, net->loss_off, net->mu, net->classes,
                         out_loss_dev, count, stream));
+  if (out_rank_dev)
+    return launch_label_rank(bf, net->scores_f32, ws, labs, T[(size_t)net->ops.back().out_t].off, net->mu, net->classes, out_rank_dev,
+                             count, stream);
   // ---- backward
   for (int k = (int)net->ops.size() - 1; k >= 0; k--) {
     const Op& op = net->ops[(size_t)k];

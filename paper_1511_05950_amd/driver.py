@@ -8,8 +8,11 @@ at the start).  This realises the server-view update of the paper's Section 3 fo
 from __future__ import annotations
 
 
-def run_softsync(ctx, schedule, batch_of, lam, loss_out=None, on_gradient=None, first_update=0):
+def run_softsync(ctx, schedule, batch_of, lam, loss_out=None, on_gradient=None, first_update=0, base_rates=None):
     """Run len(schedule) server updates.
+
+    base_rates: optional sequence of len(schedule) base learning rates alpha0, one per update (step decay of
+    Section 4.3); set with setBaseRate before each update's window is closed.
 
     ctx: binding.Sasgd;  schedule: int [K][c] requested staleness;  batch_of(i, l) -> (images_dev, labels_dev).
     loss_out: optional device float tensor [c] receiving each update's per-gradient mean losses.
@@ -36,6 +39,8 @@ def run_softsync(ctx, schedule, batch_of, lam, loss_out=None, on_gradient=None, 
                 on_gradient(i, l, learners[l])
             tau = ctx.pushGradient(learners[l])
             log.append((i, l, learners[l], stamps[l], tau))
+        if base_rates is not None:
+            ctx.setBaseRate(float(base_rates[k]))
         ctx.sumGradients()
         ctx.applyUpdate()
     return log
@@ -95,3 +100,22 @@ def run_hardsync(ctx, K, batch_of, lam, loss_out=None):
     if ctx.c != lam:
         raise ValueError("hardsync needs n = 1 (c = lambda)")
     return run_softsync(ctx, [[0] * lam for _ in range(K)], batch_of, lam, loss_out)
+
+
+def evaluate(ctx, images_dev, labels_dev, lam, mu, loss_dev, rank_dev, staleness=0):
+    """Evaluation pass (test / validation error of Section 4.3) over len(images_dev) = B * mu images on the weight
+    version `staleness` updates old: forward only, in batched calls of up to lambda mini-batches.
+
+    loss_dev: device float tensor [B] (mean loss per mini-batch); rank_dev: device int32 tensor [B * mu] (rank of
+    the true class; >= 1 is a top-1 error, >= 5 a top-5 error).  Host sequencing only."""
+    total = int(images_dev.shape[0])
+    if total % mu:
+        raise ValueError("the evaluation set must be a whole number of mini-batches")
+    B = total // mu
+    for b0 in range(0, B, lam):
+        nb = min(lam, B - b0)
+        for k in range(nb):
+            s0 = (b0 + k) * mu
+            ctx.getMinibatch(k, images_dev[s0:s0 + mu], labels_dev[s0:s0 + mu])
+            ctx.pullWeights(k, staleness)
+        ctx.evaluate(list(range(nb)), loss_dev[b0:b0 + nb], rank_dev[b0 * mu:(b0 + nb) * mu])
