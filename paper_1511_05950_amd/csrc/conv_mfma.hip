@@ -303,7 +303,11 @@ typedef int v4i_t __attribute__((ext_vector_type(4)));
 constexpr uint32_t kOutOfRange = 0x80000000u;   // buffer offset beyond any tensor: the load returns zeros
 
 // NT = threads per workgroup = 64 x number of wave tiles.
-template <int BM, int BN, int WM, int WN, int BKT, int NT>
+// UNI: every contraction step stays inside one filter tap (channels per tap are a multiple of the step) and the
+// window has at most 32 taps.  Then the tap is wavefront-uniform and advances in scalar registers, the per-row
+// bounds test is one bit of a mask computed once, and a step costs a handful of vector instructions besides the
+// loads and MFMAs.  Otherwise (first layer, large windows) the tap is decoded per lane and step.
+template <int BM, int BN, int WM, int WN, int BKT, int NT, bool UNI>
 __global__ __launch_bounds__(NT) void igemm_frag_kernel(PtrTab ws, CPtrTab wts, IGemm g, Epilogue ep) {
   constexpr int WAVES_N = BN / WN;
   constexpr int TM = WM / 32, TN = WN / 32;
@@ -328,61 +332,108 @@ __global__ __launch_bounds__(NT) void igemm_frag_kernel(PtrTab ws, CPtrTab wts, 
 
   constexpr int A_LOADS = (BM * CPS + NT - 1) / NT;
   constexpr int RPP = NT / CPS;                // tile rows covered per loader pass
+  constexpr bool FULL = (BM % RPP) == 0;       // every loader pass lies inside the tile
   const int cc = tid % CPS, lrow = tid / CPS;
-  // per tile row handled by this thread: byte offset of its window origin, and the origin's coordinates
+  // per tile row handled by this thread: byte offset of its window origin (plus this thread's chunk in UNI mode),
+  // and either the origin's coordinates or (UNI) a mask with one bit per tap that falls outside the tensor
   int row_off[A_LOADS], row_oh[A_LOADS], row_ow[A_LOADS];
+  uint32_t row_bad[A_LOADS];
 #pragma unroll
   for (int i = 0; i < A_LOADS; i++) {
     const RowPos r = row_pos(act, g, m0 + lrow + RPP * i);
-    row_off[i] = (int)((r.base - act) * 2);
+    row_off[i] = (int)((r.base - act) * 2) + (UNI ? cc * 16 : 0);
     row_oh[i] = r.valid ? r.oh : -0x40000000;  // an invalid row fails every bounds test below
     row_ow[i] = r.ow;
+    if (UNI) {
+      uint32_t good = 0;
+      if (r.valid) {
+        const int kw_lo = max(0, -r.ow), kw_hi = min(g.ks, g.W - r.ow);              // valid kw: [kw_lo, kw_hi)
+        const uint32_t kwmask = kw_hi > kw_lo ? (((1u << kw_hi) - 1u) & ~((1u << kw_lo) - 1u)) : 0u;
+        for (int kh = 0; kh < g.ks; kh++)
+          if ((unsigned)(r.oh + kh) < (unsigned)g.H) good |= kwmask << (kh * g.ks);
+      }
+      row_bad[i] = ~good;
+    }
   }
 
   const int all_steps = (g.Kchunks + CPS - 1) / CPS;
   const int per = (all_steps + g.splits - 1) / g.splits;
-  const int ks_begin = sp * per;
-  const int ksteps = min(all_steps, ks_begin + per);
+  const int ks_begin = __builtin_amdgcn_readfirstlane(sp * per);
+  const int ksteps = __builtin_amdgcn_readfirstlane(min(all_steps, ks_begin + per));
+
+  // UNI: tap state of the step that load_a fetches next, kept in scalar registers
+  int u_tap = 0, u_c8 = 0, u_kw = 0, u_koff = 0;
+  if (UNI) {
+    const uint32_t q0 = (uint32_t)(ks_begin * CPS);
+    u_tap = (int)fastdiv(q0, g.CPT, g.mg_cpt);
+    u_c8 = (int)q0 - u_tap * g.CPT;
+    const int kh = (int)fastdiv((uint32_t)u_tap, g.ks, g.mg_ks);
+    u_kw = u_tap - kh * g.ks;
+    u_koff = ((kh * g.W + u_kw) * g.C + u_c8 * 8) * 2;
+    u_tap = __builtin_amdgcn_readfirstlane(u_tap);
+    u_c8 = __builtin_amdgcn_readfirstlane(u_c8);
+    u_kw = __builtin_amdgcn_readfirstlane(u_kw);
+    u_koff = __builtin_amdgcn_readfirstlane(u_koff);
+  }
+  const int u_row_step = __builtin_amdgcn_readfirstlane((g.W - g.ks) * g.C * 2);   // extra bytes when kw wraps to the next kh
 
   v4i_t ra[A_LOADS];
   auto load_a = [&](int ks) {
-    const int q = ks * CPS + cc;
-    const uint32_t tap = fastdiv((uint32_t)q, g.CPT, g.mg_cpt);
-    const int c8 = q - (int)tap * g.CPT;
-    const int kh = (int)fastdiv(tap, g.ks, g.mg_ks), kw = (int)tap - kh * g.ks;
-    const int koff = ((kh * g.W + kw) * g.C + c8 * 8) * 2;
-    const bool qok = q < g.Kchunks;
+    if (UNI) {
 #pragma unroll
-    for (int i = 0; i < A_LOADS; i++) {
-      const bool ok = qok && (unsigned)(row_oh[i] + kh) < (unsigned)g.H && (unsigned)(row_ow[i] + kw) < (unsigned)g.W;
-      ra[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_a, ok ? (row_off[i] + koff) : (int)kOutOfRange, 0, 0);
+      for (int i = 0; i < A_LOADS; i++) {
+        const int bad = __builtin_amdgcn_sbfe((int)row_bad[i], u_tap, 1);            // 0 or -1
+        const int off = (row_off[i] + u_koff) | (bad & (int)kOutOfRange);
+        ra[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_a, off, 0, 0);
+      }
+      // advance to the next step: CPS more chunks of the same tap, or the first chunks of the next tap
+      u_c8 += CPS;
+      u_koff += CPS * 16;
+      const bool next_tap = u_c8 >= g.CPT;
+      u_c8 = next_tap ? 0 : u_c8;
+      u_tap += next_tap ? 1 : 0;
+      u_kw += next_tap ? 1 : 0;
+      const bool next_row = u_kw == g.ks;
+      u_kw = next_row ? 0 : u_kw;
+      u_koff += next_row ? u_row_step : 0;
+    } else {
+      const int q = ks * CPS + cc;
+      const uint32_t tap = fastdiv((uint32_t)q, g.CPT, g.mg_cpt);
+      const int c8 = q - (int)tap * g.CPT;
+      const int kh = (int)fastdiv(tap, g.ks, g.mg_ks), kw = (int)tap - kh * g.ks;
+      const int koff = ((kh * g.W + kw) * g.C + c8 * 8) * 2;
+      const bool qok = q < g.Kchunks;
+#pragma unroll
+      for (int i = 0; i < A_LOADS; i++) {
+        const bool ok = qok && (unsigned)(row_oh[i] + kh) < (unsigned)g.H && (unsigned)(row_ow[i] + kw) < (unsigned)g.W;
+        ra[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_a, ok ? (row_off[i] + koff) : (int)kOutOfRange, 0, 0);
+      }
     }
   };
   auto store_a = [&](int buf) {
     bf16_t* A = lds + buf * A_ELEMS;
 #pragma unroll
     for (int i = 0; i < A_LOADS; i++)
-      if (lrow + RPP * i < BM) *reinterpret_cast<v4i_t*>(A + (lrow + RPP * i) * LDF + cc * 8) = ra[i];
+      if (FULL || lrow + RPP * i < BM) *reinterpret_cast<v4i_t*>(A + (lrow + RPP * i) * LDF + cc * 8) = ra[i];
   };
-  // B fragments: one byte offset per column block of this wavefront, advanced by a constant every step
+  // B fragments: one fixed byte offset per column block of this wavefront; the step advances a scalar offset
   uint32_t boff[TN];
 #pragma unroll
   for (int j = 0; j < TN; j++) {
     const int nb = (n0 + wn0) / 32 + j;
-    boff[j] = nb < NB ? (uint32_t)((((int64_t)nb * KB16 + ks_begin * KK) * 512 + lane * 8) * 2) : kOutOfRange;
+    boff[j] = nb < NB ? (uint32_t)(((int64_t)nb * KB16 * 512 + lane * 8) * 2) : kOutOfRange;
   }
-  bf16x8 bn[KK][TN];
-  auto load_b = [&]() {
+  int b_step = ks_begin * KK * 1024;           // scalar byte offset of the step that load_b fetches next
+  auto load_b = [&](bf16x8 (&bt)[KK][TN]) {
 #pragma unroll
     for (int kk = 0; kk < KK; kk++)
 #pragma unroll
       for (int j = 0; j < TN; j++) {
         union { v4i_t u; bf16x8 v; } f;
-        f.u = __builtin_amdgcn_raw_buffer_load_b128(rsrc_b, (int)(boff[j] + kk * 1024), 0, 0);
-        bn[kk][j] = f.v;
+        f.u = __builtin_amdgcn_raw_buffer_load_b128(rsrc_b, (int)(boff[j] + kk * 1024), b_step, 0);
+        bt[kk][j] = f.v;
       }
-#pragma unroll
-    for (int j = 0; j < TN; j++) boff[j] += KK * 1024;
+    b_step += KK * 1024;
   };
 
   floatx16 acc[TM][TN];
@@ -393,23 +444,16 @@ __global__ __launch_bounds__(NT) void igemm_frag_kernel(PtrTab ws, CPtrTab wts, 
 #pragma unroll
       for (int r = 0; r < 16; r++) acc[i][j][r] = 0.f;
 
-  if (ks_begin < ksteps) {
-    load_a(ks_begin);
-    load_b();
-    store_a(ks_begin & 1);
-  }
-  __syncthreads();
-  for (int ks = ks_begin; ks < ksteps; ks++) {
-    const int buf = ks & 1;
-    bf16x8 bc[KK][TN];
-#pragma unroll
-    for (int kk = 0; kk < KK; kk++)
-#pragma unroll
-      for (int j = 0; j < TN; j++) bc[kk][j] = bn[kk][j];
-    if (ks + 1 < ksteps) {
-      load_a(ks + 1);
-      load_b();
-    }
+  // One contraction step ks: the im2col chunks of step ks+1 (fetched during step ks-1, now in registers) go to the
+  // other LDS buffer, the chunks of step ks+2 and the fragments of step ks+1 (into `bnext`) are requested, then the
+  // MFMAs run on LDS buffer `buf` and the fragments `bcur`.  A global load thus has a whole step to arrive before
+  // anything waits for it.  The two fragment sets swap roles from step to step, so the loop is written two steps at
+  // a time and no register is copied.
+  auto step = [&](bf16x8 (&bcur)[KK][TN], bf16x8 (&bnext)[KK][TN], int ks, int buf, bool has1, bool has2) {
+    if (has1) store_a(buf ^ 1);
+    if (has2) load_a(ks + 2);
+    if (has1) load_b(bnext);
+    __builtin_amdgcn_sched_barrier(0);         // keep the requests ahead of the MFMAs: they need the whole step to land
     const bf16_t* A = lds + buf * A_ELEMS;
 #pragma unroll
     for (int kk = 0; kk < KK; kk++) {
@@ -420,11 +464,31 @@ __global__ __launch_bounds__(NT) void igemm_frag_kernel(PtrTab ws, CPtrTab wts, 
 #pragma unroll
       for (int i = 0; i < TM; i++)
 #pragma unroll
-        for (int j = 0; j < TN; j++) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], bc[kk][j], acc[i][j], 0, 0, 0);
+        for (int j = 0; j < TN; j++) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], bcur[kk][j], acc[i][j], 0, 0, 0);
     }
-    if (ks + 1 < ksteps) store_a(buf ^ 1);
     __syncthreads();
+  };
+
+  bf16x8 b0[KK][TN], b1[KK][TN];
+  int ks = ks_begin;
+  if (ks < ksteps) {
+    load_a(ks);
+    load_b(b0);
+    store_a(0);
+    if (ks + 1 < ksteps) load_a(ks + 1);
   }
+  __syncthreads();
+  // Inside the loop both steps prefetch unconditionally: a branch around the loads would make the compiler wait
+  // for the most pessimistic count of outstanding loads where the paths join.
+  for (; ks + 3 < ksteps; ks += 2) {
+    step(b0, b1, ks, 0, true, true);
+    step(b1, b0, ks + 1, 1, true, true);
+  }
+  for (; ks + 1 < ksteps; ks += 2) {          // at most once: two or three steps remain
+    step(b0, b1, ks, 0, true, ks + 2 < ksteps);
+    step(b1, b0, ks + 1, 1, ks + 2 < ksteps, false);
+  }
+  if (ks < ksteps) step(b0, b1, ks, 0, false, false);
 
   if (g.splits > 1) {
     float* part = reinterpret_cast<float*>((char*)ws.p[z] + g.scratch_off) + (int64_t)sp * g.M * g.Ncols;
@@ -509,7 +573,9 @@ template <int BM, int BN, int WM, int WN>
 static void launch_frag_t(const PtrTab& ws, const CPtrTab& wts, const IGemm& g, const Epilogue& ep, int count, hipStream_t s) {
   dim3 grid((unsigned)((g.M + BM - 1) / BM), (unsigned)((g.Ncols + BN - 1) / BN), (unsigned)(count * g.splits));
   constexpr int NT = 64 * (BM / WM) * (BN / WN);
-  hipLaunchKernelGGL((igemm_frag_kernel<BM, BN, WM, WN, 32, NT>), grid, dim3(NT), 0, s, ws, wts, g, ep);
+  const bool uni = g.CPT % 4 == 0 && g.ks * g.ks <= 32 && g.Kchunks % 4 == 0;
+  if (uni) hipLaunchKernelGGL((igemm_frag_kernel<BM, BN, WM, WN, 32, NT, true>), grid, dim3(NT), 0, s, ws, wts, g, ep);
+  else hipLaunchKernelGGL((igemm_frag_kernel<BM, BN, WM, WN, 32, NT, false>), grid, dim3(NT), 0, s, ws, wts, g, ep);
   if (g.splits > 1) {
     int64_t total = (int64_t)g.M * g.Ncols;
     unsigned blocks = (unsigned)((total + 255) / 256 < 1024 ? (total + 255) / 256 : 1024);
