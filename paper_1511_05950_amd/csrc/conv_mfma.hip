@@ -308,7 +308,7 @@ constexpr uint32_t kOutOfRange = 0x80000000u;   // buffer offset beyond any tens
 // bounds test is one bit of a mask computed once, and a step costs a handful of vector instructions besides the
 // loads and MFMAs.  Otherwise (first layer, large windows) the tap is decoded per lane and step.
 template <int BM, int BN, int WM, int WN, int BKT, int NT, bool UNI>
-__global__ __launch_bounds__(NT) void igemm_frag_kernel(PtrTab ws, CPtrTab wts, IGemm g, Epilogue ep) {
+__global__ __launch_bounds__(NT, (WM * WN > 64 * 64 ? 2 : 1)) void igemm_frag_kernel(PtrTab ws, CPtrTab wts, IGemm g, Epilogue ep) {
   constexpr int WAVES_N = BN / WN;
   constexpr int TM = WM / 32, TN = WN / 32;
   constexpr int LDF = BKT + 8;                 // 80 or 144 byte rows: conflict-free 16-byte reads
@@ -586,10 +586,12 @@ static void launch_frag_t(const PtrTab& ws, const CPtrTab& wts, const IGemm& g, 
 // Convolution forward / input gradient with fragment-packed filters (g.b_off points at the fragment copy).
 hipError_t launch_igemm_frag(const PtrTab& ws, const CPtrTab& wts, const IGemm& g, const Epilogue& ep, int count, hipStream_t s) {
   if (g.C % 8 || g.ldb % 32 || g.splits < 1) return hipErrorInvalidValue;
-  // A 256 x 256 tile with 512 threads (wave tile 128 x 64) was measured 10-25 % slower than 128 x 128 on the
-  // AlexNet-shaped layers (two wavefronts per SIMD no longer hide the load latency), so it is not instantiated.
+  // Wave tile 128 x 64 (two wavefronts per SIMD, accumulators in ordinary registers) wins where the columns fill
+  // whole 256-wide tiles: each B fragment then serves four MFMAs instead of two.  Measured slower: 256 x 128 blocks,
+  // 192-wide tiles of three wavefronts for 384 columns, 96-wide tiles for 96 columns.
   if (g.Ncols <= 32) launch_frag_t<128, 32, 32, 32>(ws, wts, g, ep, count, s);
   else if (g.Ncols <= 64) launch_frag_t<128, 64, 64, 32>(ws, wts, g, ep, count, s);
+  else if (g.Ncols % 256 == 0) launch_frag_t<128, 256, 128, 64>(ws, wts, g, ep, count, s);
   else launch_frag_t<128, 128, 64, 64>(ws, wts, g, ep, count, s);
   return hipGetLastError();
 }
@@ -617,7 +619,9 @@ hipError_t launch_igemm(const PtrTab& ws, const CPtrTab& wts, const IGemm& g, co
 // dW tile [BMG output channels][BNG im2col columns], contraction over output positions m in steps of 32.
 // dy tile  [32 m][BMG n]  and  im2col tile [32 m][BNG k]  are staged as they lie in memory (rows = m) and
 // read with the transpose load.  The result is scattered into the flat fp32 gradient through filter_src().
-template <int BMG, int BNG, int WMG, int WNG>
+// INCR: the output position (image, oh, ow) of a thread's tile row advances from step to step by additions and
+// two conditional wraps (possible when 32 / OW + 1 <= OH); otherwise it is decoded from the row index every step.
+template <int BMG, int BNG, int WMG, int WNG, bool INCR>
 __global__ __launch_bounds__(256) void igemm_wgrad_kernel(PtrTab ws, PtrTab grads, IGemm g, VConv v, size_t dy_off, int64_t w_off,
                                                           int64_t b_off) {
   constexpr int WAVES_NG = BNG / WNG;                  // four wavefronts: (BMG / WMG) x (BNG / WNG)
@@ -635,11 +639,13 @@ __global__ __launch_bounds__(256) void igemm_wgrad_kernel(PtrTab ws, PtrTab grad
   const int wm0 = (wave / WAVES_NG) * WMG, wn0 = (wave % WAVES_NG) * WNG;
 
   constexpr int CPR_A = BMG / 8, CPR_B = BNG / 8;
-  constexpr int A_LOADS = (BK * CPR_A + 255) / 256, B_LOADS = (BK * CPR_B + 255) / 256;
+  constexpr int TPR = 256 / BK;                        // threads per tile row of the im2col tile
+  constexpr int A_LOADS = (BK * CPR_A + 255) / 256, B_LOADS = CPR_B / TPR;
+  static_assert(CPR_B % TPR == 0, "im2col tile: whole chunks per thread");
   const int all_steps = (g.M + BK - 1) / BK;
   const int per = (all_steps + g.splits - 1) / g.splits;
-  const int ms_begin = sp * per;
-  const int msteps = min(all_steps, ms_begin + per);
+  const int ms_begin = __builtin_amdgcn_readfirstlane(sp * per);
+  const int msteps = __builtin_amdgcn_readfirstlane(min(all_steps, ms_begin + per));
 
   // Hardware-bounds-checked buffer loads (an offset at or beyond the tensor reads as zero): rows beyond M, columns
   // beyond the layer and taps in the zero padding need no branch and no patching of loaded data.
@@ -647,49 +653,73 @@ __global__ __launch_bounds__(256) void igemm_wgrad_kernel(PtrTab ws, PtrTab grad
   const __amdgpu_buffer_rsrc_t rsrc_x = __builtin_amdgcn_make_buffer_rsrc((void*)x, 0, (int)g.a_bytes, 0x00020000);
   // dy tile: chunk (row r, 8 channels from n) per thread; its offset advances by a constant every step
   uint32_t a_off[A_LOADS];
+  const uint32_t a_step = (uint32_t)(BK * g.Ncols * 2);
 #pragma unroll
   for (int i = 0; i < A_LOADS; i++) {
     const int idx = tid + 256 * i;
     const int r = idx / CPR_A, n = n0 + (idx % CPR_A) * 8;
     a_off[i] = (r < BK && n < g.Ncols) ? (uint32_t)((((int64_t)ms_begin * BK + r) * g.Ncols + n) * 2) : kOutOfRange;
   }
-  // im2col tile: the filter tap of a thread's chunk is fixed, only the output position changes from step to step
-  int b_row[B_LOADS], b_kh[B_LOADS], b_kw[B_LOADS], b_koff[B_LOADS];
+  // im2col tile: a thread owns B_LOADS chunks of ONE tile row; their filter taps are fixed, only the row's output
+  // position changes from step to step
+  const int b_row = tid / TPR;
+  int b_dkh[B_LOADS], b_dkw[B_LOADS], b_koff[B_LOADS];
   bool b_ok[B_LOADS], b_ones[B_LOADS];
 #pragma unroll
   for (int i = 0; i < B_LOADS; i++) {
-    const int idx = tid + 256 * i;
-    const int q = k0 / 8 + idx % CPR_B;
+    const int q = k0 / 8 + tid % TPR + TPR * i;
     const uint32_t tap = fastdiv((uint32_t)q, g.CPT, g.mg_cpt);
     const int c8 = q - (int)tap * g.CPT;
-    b_row[i] = idx / CPR_B;
-    b_kh[i] = (int)fastdiv(tap, g.ks, g.mg_ks);
-    b_kw[i] = (int)tap - b_kh[i] * g.ks;
-    b_koff[i] = ((b_kh[i] * g.W + b_kw[i]) * g.C + c8 * 8) * 2;
-    b_ok[i] = b_row[i] < BK && q < g.Kchunks;
-    b_ones[i] = b_row[i] < BK && q == g.Kchunks;   // the bias column: im2col value 1 for every real output position
+    const int kh = (int)fastdiv(tap, g.ks, g.mg_ks), kw = (int)tap - kh * g.ks;
+    b_dkh[i] = kh - g.pad;
+    b_dkw[i] = kw - g.pad;
+    b_koff[i] = ((b_dkh[i] * g.W + b_dkw[i]) * g.C + c8 * 8) * 2;
+    b_ok[i] = q < g.Kchunks;
+    b_ones[i] = q == g.Kchunks;                  // the bias column: im2col value 1 for every real output position
   }
+  // position of the row that load_regs fetches next: m, its (oh, ow) and the byte offset of x[image][oh][ow][0]
+  int r_m = ms_begin * BK + b_row, r_oh, r_ow, r_off;
+  auto decode_row = [&]() {
+    const uint32_t mm = r_m < g.M ? (uint32_t)r_m : 0u;
+    const uint32_t rest = fastdiv(mm, g.OW, g.mg_ow);
+    const uint32_t n = fastdiv(rest, g.OH, g.mg_oh);
+    r_ow = (int)(mm - rest * (uint32_t)g.OW);
+    r_oh = (int)(rest - n * (uint32_t)g.OH);
+    r_off = (int)(((n * (uint32_t)g.H + (uint32_t)r_oh) * (uint32_t)g.W + (uint32_t)r_ow) * (uint32_t)g.C * 2u);
+  };
+  decode_row();
+  const int d_ow = BK / g.OW, m_ow = BK - d_ow * g.OW;          // 32 rows further: d_ow lines down, m_ow positions right
+  const int inc0 = (d_ow * g.W + m_ow) * g.C * 2;               // the same in bytes of x
+  const int inc_w = (g.W - g.OW) * g.C * 2;                      // extra when ow wraps into the next line
+  const int inc_h = (g.H - g.OH) * g.W * g.C * 2;                // extra when oh wraps into the next image
+
   v4i_t ra[A_LOADS], rb[B_LOADS];
   uint32_t bias_one[B_LOADS];
-  auto load_regs = [&](int ms) {
+  auto load_regs = [&]() {
 #pragma unroll
     for (int i = 0; i < A_LOADS; i++) {
       ra[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_dy, (int)a_off[i], 0, 0);
-      a_off[i] += (uint32_t)(BK * g.Ncols * 2);
+      a_off[i] += a_step;
     }
+    const bool valid = r_m < g.M;
 #pragma unroll
     for (int i = 0; i < B_LOADS; i++) {
-      const int m = ms * BK + b_row[i];
-      const bool valid = m < g.M;
-      const uint32_t mm = valid ? (uint32_t)m : 0u;
-      const uint32_t rest = fastdiv(mm, g.OW, g.mg_ow);
-      const int ow = (int)(mm - rest * (uint32_t)g.OW) - g.pad + b_kw[i];
-      const uint32_t n = fastdiv(rest, g.OH, g.mg_oh);
-      const int oh = (int)(rest - n * (uint32_t)g.OH) - g.pad + b_kh[i];
-      const bool ok = b_ok[i] && valid && (unsigned)oh < (unsigned)g.H && (unsigned)ow < (unsigned)g.W;
-      const int off = (int)(((n * (uint32_t)g.H + (uint32_t)(oh - b_kh[i])) * (uint32_t)g.W + (uint32_t)(ow - b_kw[i])) * (uint32_t)g.C * 2u) + b_koff[i];
-      rb[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_x, ok ? off : (int)kOutOfRange, 0, 0);
+      const bool ok = b_ok[i] && valid && (unsigned)(r_oh + b_dkh[i]) < (unsigned)g.H && (unsigned)(r_ow + b_dkw[i]) < (unsigned)g.W;
+      rb[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_x, ok ? r_off + b_koff[i] : (int)kOutOfRange, 0, 0);
       bias_one[i] = (b_ones[i] && valid) ? 0x3F80u : 0u;
+    }
+    // advance the row by BK output positions
+    r_m += BK;
+    if (INCR) {
+      r_ow += m_ow;
+      const bool c1 = r_ow >= g.OW;
+      r_ow -= c1 ? g.OW : 0;
+      r_oh += d_ow + (c1 ? 1 : 0);
+      const bool c2 = r_oh >= g.OH;
+      r_oh -= c2 ? g.OH : 0;
+      r_off += inc0 + (c1 ? inc_w : 0) + (c2 ? inc_h : 0);
+    } else {
+      decode_row();
     }
   };
   auto store_lds = [&](int buf) {
@@ -699,15 +729,13 @@ __global__ __launch_bounds__(256) void igemm_wgrad_kernel(PtrTab ws, PtrTab grad
     for (int i = 0; i < A_LOADS; i++) {
       int idx = tid + 256 * i;
       int r = idx / CPR_A, ch = idx % CPR_A;
-      if (r < BK) *reinterpret_cast<v4i_t*>(A + r * LDT_A + ch * 8) = ra[i];
+      if (BK * CPR_A % 256 == 0 || r < BK) *reinterpret_cast<v4i_t*>(A + r * LDT_A + ch * 8) = ra[i];
     }
 #pragma unroll
     for (int i = 0; i < B_LOADS; i++) {
-      int idx = tid + 256 * i;
-      int r = idx / CPR_B, ch = idx % CPR_B;
       v4i_t val = rb[i];
       val.x |= (int)bias_one[i];                 // the chunk of the bias column loads as zeros; its first element becomes 1.0
-      if (r < BK) *reinterpret_cast<v4i_t*>(B + r * LDT_B + ch * 8) = val;
+      *reinterpret_cast<v4i_t*>(B + b_row * LDT_B + (tid % TPR + TPR * i) * 8) = val;
     }
   };
 
@@ -719,15 +747,14 @@ __global__ __launch_bounds__(256) void igemm_wgrad_kernel(PtrTab ws, PtrTab grad
 #pragma unroll
       for (int r = 0; r < 16; r++) acc[i][j][r] = 0.f;
 
-  if (ms_begin < msteps) {
-    load_regs(ms_begin);
-    store_lds(ms_begin & 1);
-  }
-  __syncthreads();
   const int j16 = lane & 15, half = (lane >> 4) & 1;
-  for (int ms = ms_begin; ms < msteps; ms++) {
-    const int buf = ms & 1;
-    if (ms + 1 < msteps) load_regs(ms + 1);
+  // One step: the tiles of step ms+1 (fetched during step ms-1) go to the other LDS buffer, the tiles of step ms+2 are
+  // requested, then the MFMAs run on buffer `buf`: a global load has a whole step to arrive.  Two steps per loop
+  // iteration make `buf` a constant.
+  auto step = [&](int buf, bool has1, bool has2) {
+    if (has1) store_lds(buf ^ 1);
+    if (has2) load_regs();
+    __builtin_amdgcn_sched_barrier(0);
     const bf16_t* A = lds + buf * (A_ELEMS + B_ELEMS);
     const bf16_t* B = A + A_ELEMS;
 #pragma unroll
@@ -755,9 +782,25 @@ __global__ __launch_bounds__(256) void igemm_wgrad_kernel(PtrTab ws, PtrTab grad
 #pragma unroll
         for (int j = 0; j < TN; j++) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
     }
-    if (ms + 1 < msteps) store_lds(buf ^ 1);
     __syncthreads();
+  };
+
+  int ms = ms_begin;
+  if (ms < msteps) {
+    load_regs();
+    store_lds(0);
+    if (ms + 1 < msteps) load_regs();
   }
+  __syncthreads();
+  for (; ms + 3 < msteps; ms += 2) {            // no branch around the loads inside the loop
+    step(0, true, true);
+    step(1, true, true);
+  }
+  for (; ms + 1 < msteps; ms += 2) {            // at most once: two or three steps remain
+    step(0, true, ms + 2 < msteps);
+    step(1, ms + 2 < msteps, false);
+  }
+  if (ms < msteps) step(0, false, false);
 
   const int kcols = g.Kchunks * 8;
   if (g.splits > 1) {   // fp32 partial [split][n][kcols + 8]; wgrad_finish_kernel adds and scatters
@@ -856,16 +899,23 @@ hipError_t launch_igemm_wgrad(const PtrTab& ws, const PtrTab& grads, const IGemm
   if (g.C % 8 || g.Ncols % 8 || g.splits < 1) return hipErrorInvalidValue;
   const int cols = g.Kchunks * 8 + 1;          // im2col columns plus the bias column
   if (g.splits > 1 && (size_t)cols * sizeof(float) > 60 * 1024) return hipErrorInvalidValue;   // finish kernel keeps one row in LDS
+  const bool incr = BK / g.OW + 1 <= g.OH;      // one wrap of oh per step at most
+#define SASGD_WGRAD(BMG, BNG, WMG, WNG)                                                                                          \
+  do {                                                                                                                           \
+    if (incr) hipLaunchKernelGGL((igemm_wgrad_kernel<BMG, BNG, WMG, WNG, true>), grid, dim3(256), 0, s, ws, grads, g, v, dy_off, w_off, b_off); \
+    else hipLaunchKernelGGL((igemm_wgrad_kernel<BMG, BNG, WMG, WNG, false>), grid, dim3(256), 0, s, ws, grads, g, v, dy_off, w_off, b_off);    \
+  } while (0)
   if (g.Ncols <= 32) {
     dim3 grid(1, (unsigned)((cols + 127) / 128), (unsigned)(count * g.splits));
-    hipLaunchKernelGGL((igemm_wgrad_kernel<32, 128, 32, 32>), grid, dim3(256), 0, s, ws, grads, g, v, dy_off, w_off, b_off);
+    SASGD_WGRAD(32, 128, 32, 32);
   } else if (g.Ncols <= 64) {
     dim3 grid(1, (unsigned)((cols + 127) / 128), (unsigned)(count * g.splits));
-    hipLaunchKernelGGL((igemm_wgrad_kernel<64, 128, 32, 64>), grid, dim3(256), 0, s, ws, grads, g, v, dy_off, w_off, b_off);
+    SASGD_WGRAD(64, 128, 32, 64);
   } else {
     dim3 grid((unsigned)((g.Ncols + 127) / 128), (unsigned)((cols + 127) / 128), (unsigned)(count * g.splits));
-    hipLaunchKernelGGL((igemm_wgrad_kernel<128, 128, 64, 64>), grid, dim3(256), 0, s, ws, grads, g, v, dy_off, w_off, b_off);
+    SASGD_WGRAD(128, 128, 64, 64);
   }
+#undef SASGD_WGRAD
   if (g.splits > 1)
     hipLaunchKernelGGL(wgrad_finish_kernel, dim3((unsigned)g.Ncols, 1, (unsigned)count), dim3(256), (size_t)cols * sizeof(float), s, ws,
                        grads, g, v, w_off, b_off);

@@ -343,7 +343,7 @@ hipError_t net_prepare_version(Net* net, const void* flat, void* packed, hipStre
 }
 
 static void set_splits(const Net* net, IGemm& g, int steps, int count) {
-  const int bm = g.M <= 32 ? 32 : 128, bn = g.M <= 32 ? 128 : (g.Ncols <= 32 ? 32 : (g.Ncols <= 64 ? 64 : 128));
+  const int bm = g.M <= 32 ? 32 : 128, bn = g.M <= 32 ? 128 : (g.Ncols <= 32 ? 32 : (g.Ncols <= 64 ? 64 : (g.Ncols % 256 == 0 ? 256 : 128)));
   const int64_t tiles = (int64_t)((g.M + bm - 1) / bm) * ((g.Ncols + bn - 1) / bn);
   g.scratch_off = net->scratch_off;
   g.splits = choose_splits(tiles, count, steps, (size_t)g.M * g.Ncols * 4, net->scratch_bytes);
