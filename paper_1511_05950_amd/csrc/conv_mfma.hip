@@ -444,32 +444,42 @@ __global__ __launch_bounds__(NT, (WM * WN > 64 * 64 ? 2 : 1)) void igemm_frag_ke
 #pragma unroll
       for (int r = 0; r < 16; r++) acc[i][j][r] = 0.f;
 
-  // One contraction step ks: the im2col chunks of step ks+1 (fetched during step ks-1, now in registers) go to the
-  // other LDS buffer, the chunks of step ks+2 and the fragments of step ks+1 (into `bnext`) are requested, then the
-  // MFMAs run on LDS buffer `buf` and the fragments `bcur`.  A global load thus has a whole step to arrive before
-  // anything waits for it.  The two fragment sets swap roles from step to step, so the loop is written two steps at
-  // a time and no register is copied.
-  auto step = [&](bf16x8 (&bcur)[KK][TN], bf16x8 (&bnext)[KK][TN], int ks, int buf, bool has1, bool has2) {
+  // One contraction step ks on LDS buffer `buf`.  At entry the A fragments of its first k-block (`a0`) are already in
+  // registers.  The im2col chunks of step ks+1 (fetched during step ks-1, now in staging registers) go to the other
+  // LDS buffer, the chunks of step ks+2 and the filter fragments of step ks+1 (into `bnext`) are requested, the A
+  // fragments of the second k-block are read, and the first k-block's MFMAs run.  The single barrier of the step
+  // sits in the middle: after it every wavefront has finished reading `buf` and writing the other buffer, so the
+  // first A fragments of step ks+1 (`a0n`) are read while the second k-block's MFMAs run, and nothing waits on LDS
+  // right after a barrier.  Fragment sets swap roles from step to step: two steps per loop iteration, no copies.
+  auto lds_frag = [&](int buf, int i, int kk) {
+    return *reinterpret_cast<const bf16x8*>(lds + buf * A_ELEMS + (wm0 + 32 * i + (lane & 31)) * LDF + 16 * kk + 8 * (lane >> 5));
+  };
+  auto step = [&](bf16x8 (&bcur)[KK][TN], bf16x8 (&bnext)[KK][TN], bf16x8 (&a0)[TM], bf16x8 (&a0n)[TM], int ks, int buf, bool has1,
+                  bool has2) {
+    static_assert(KK == 2, "two k-blocks per step");
     if (has1) store_a(buf ^ 1);
     if (has2) load_a(ks + 2);
     if (has1) load_b(bnext);
-    __builtin_amdgcn_sched_barrier(0);         // keep the requests ahead of the MFMAs: they need the whole step to land
-    const bf16_t* A = lds + buf * A_ELEMS;
+    bf16x8 a1[TM];
 #pragma unroll
-    for (int kk = 0; kk < KK; kk++) {
-      bf16x8 a[TM];
+    for (int i = 0; i < TM; i++) a1[i] = lds_frag(buf, i, 1);
+    __builtin_amdgcn_sched_barrier(0);         // requests and LDS traffic first: they need the step to complete
 #pragma unroll
-      for (int i = 0; i < TM; i++)
-        a[i] = *reinterpret_cast<const bf16x8*>(A + (wm0 + 32 * i + (lane & 31)) * LDF + 16 * kk + 8 * (lane >> 5));
+    for (int i = 0; i < TM; i++)
 #pragma unroll
-      for (int i = 0; i < TM; i++)
-#pragma unroll
-        for (int j = 0; j < TN; j++) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], bcur[kk][j], acc[i][j], 0, 0, 0);
-    }
+      for (int j = 0; j < TN; j++) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0[i], bcur[0][j], acc[i][j], 0, 0, 0);
     __syncthreads();
+    if (has1) {
+#pragma unroll
+      for (int i = 0; i < TM; i++) a0n[i] = lds_frag(buf ^ 1, i, 0);
+    }
+#pragma unroll
+    for (int i = 0; i < TM; i++)
+#pragma unroll
+      for (int j = 0; j < TN; j++) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1[i], bcur[1][j], acc[i][j], 0, 0, 0);
   };
 
-  bf16x8 b0[KK][TN], b1[KK][TN];
+  bf16x8 b0[KK][TN], b1[KK][TN], fa[TM], fb[TM];
   int ks = ks_begin;
   if (ks < ksteps) {
     load_a(ks);
@@ -478,17 +488,21 @@ __global__ __launch_bounds__(NT, (WM * WN > 64 * 64 ? 2 : 1)) void igemm_frag_ke
     if (ks + 1 < ksteps) load_a(ks + 1);
   }
   __syncthreads();
+  if (ks < ksteps) {
+#pragma unroll
+    for (int i = 0; i < TM; i++) fa[i] = lds_frag(0, i, 0);
+  }
   // Inside the loop both steps prefetch unconditionally: a branch around the loads would make the compiler wait
   // for the most pessimistic count of outstanding loads where the paths join.
   for (; ks + 3 < ksteps; ks += 2) {
-    step(b0, b1, ks, 0, true, true);
-    step(b1, b0, ks + 1, 1, true, true);
+    step(b0, b1, fa, fb, ks, 0, true, true);
+    step(b1, b0, fb, fa, ks + 1, 1, true, true);
   }
   for (; ks + 1 < ksteps; ks += 2) {          // at most once: two or three steps remain
-    step(b0, b1, ks, 0, true, ks + 2 < ksteps);
-    step(b1, b0, ks + 1, 1, ks + 2 < ksteps, false);
+    step(b0, b1, fa, fb, ks, 0, true, ks + 2 < ksteps);
+    step(b1, b0, fb, fa, ks + 1, 1, ks + 2 < ksteps, false);
   }
-  if (ks < ksteps) step(b0, b1, ks, 0, false, false);
+  if (ks < ksteps) step(b0, b1, fa, fb, ks, 0, false, false);
 
   if (g.splits > 1) {
     float* part = reinterpret_cast<float*>((char*)ws.p[z] + g.scratch_off) + (int64_t)sp * g.M * g.Ncols;
@@ -588,7 +602,9 @@ hipError_t launch_igemm_frag(const PtrTab& ws, const CPtrTab& wts, const IGemm& 
   if (g.C % 8 || g.ldb % 32 || g.splits < 1) return hipErrorInvalidValue;
   // Wave tile 128 x 64 (two wavefronts per SIMD, accumulators in ordinary registers) wins where the columns fill
   // whole 256-wide tiles: each B fragment then serves four MFMAs instead of two.  Measured slower: 256 x 128 blocks,
-  // 192-wide tiles of three wavefronts for 384 columns, 96-wide tiles for 96 columns.
+  // 192-wide tiles of three wavefronts for 384 columns, 96-wide tiles for 96 columns, and taking the filters
+  // through LDS as well (tiles 128 x 128 to 256 x 256, staging registers two steps deep): with both operands in
+  // LDS its bandwidth becomes the limit instead of the vector L1's.
   if (g.Ncols <= 32) launch_frag_t<128, 32, 32, 32>(ws, wts, g, ep, count, s);
   else if (g.Ncols <= 64) launch_frag_t<128, 64, 64, 32>(ws, wts, g, ep, count, s);
   else if (g.Ncols % 256 == 0) launch_frag_t<128, 256, 128, 64>(ws, wts, g, ep, count, s);
