@@ -464,19 +464,23 @@ __global__ __launch_bounds__(NT, (WM * WN > 64 * 64 ? 2 : 1)) void igemm_frag_ke
 #pragma unroll
     for (int i = 0; i < TM; i++) a1[i] = lds_frag(buf, i, 1);
     __builtin_amdgcn_sched_barrier(0);         // requests and LDS traffic first: they need the step to complete
+    __builtin_amdgcn_s_setprio(1);             // a wavefront in its MFMA phase keeps the matrix pipe; others issue memory work
 #pragma unroll
     for (int i = 0; i < TM; i++)
 #pragma unroll
       for (int j = 0; j < TN; j++) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0[i], bcur[0][j], acc[i][j], 0, 0, 0);
+    __builtin_amdgcn_s_setprio(0);
     __syncthreads();
     if (has1) {
 #pragma unroll
       for (int i = 0; i < TM; i++) a0n[i] = lds_frag(buf ^ 1, i, 0);
     }
+    __builtin_amdgcn_s_setprio(1);
 #pragma unroll
     for (int i = 0; i < TM; i++)
 #pragma unroll
       for (int j = 0; j < TN; j++) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1[i], bcur[1][j], acc[i][j], 0, 0, 0);
+    __builtin_amdgcn_s_setprio(0);
   };
 
   bf16x8 b0[KK][TN], b1[KK][TN], fa[TM], fb[TM];

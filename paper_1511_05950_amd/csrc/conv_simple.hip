@@ -156,6 +156,28 @@ __global__ __launch_bounds__(256) void conv_wgrad_simple_kernel(PtrTab ws, PtrTa
   }
 }
 
+// Fully connected layer (1 x 1 window on a 1 x 1 input): dW[k][c] = sum_n dy[n][k] x[n][c].  One thread per input
+// unit c and one workgroup row per output unit k: neighbouring lanes read neighbouring x, dy[n][k] is a broadcast.
+// The thread of c = 0 also accumulates the bias gradient.
+template <typename T>
+__global__ __launch_bounds__(256) void fc_wgrad_simple_kernel(PtrTab ws, PtrTab grads, size_t x_off, size_t dy_off, int64_t w_off,
+                                                              int64_t b_off, int N, int C, int K) {
+  const T* x = (const T*)ws.p[blockIdx.z] + x_off;
+  const T* dy = (const T*)ws.p[blockIdx.z] + dy_off;
+  float* dw = (float*)grads.p[blockIdx.z] + w_off;
+  float* db = (float*)grads.p[blockIdx.z] + b_off;
+  const int c = blockIdx.x * 256 + threadIdx.x, k = blockIdx.y;
+  if (c >= C) return;
+  float acc = 0.f, bsum = 0.f;
+  for (int n = 0; n < N; n++) {
+    const float d = ldf(dy + (int64_t)n * K + k);
+    acc = fmaf(d, ldf(x + (int64_t)n * C + c), acc);
+    bsum += d;
+  }
+  dw[(int64_t)k * C + c] = acc;
+  if (c == 0) db[k] = bsum;
+}
+
 static inline dim3 grid1(int64_t total, int count) {
   int64_t b = (total + 255) / 256;
   if (b > 8192) b = 8192;
@@ -189,6 +211,12 @@ hipError_t launch_conv_dgrad_simple(bool is_bf16, const PtrTab& ws, const CPtrTa
 
 hipError_t launch_conv_wgrad_simple(bool is_bf16, const PtrTab& ws, const PtrTab& grads, size_t x_off, size_t dy_off, int64_t w_off,
                                     int64_t b_off, const ConvShape& sh, int count, hipStream_t s) {
+  if (sh.ks == 1 && sh.H == 1 && sh.W == 1 && sh.pad == 0 && sh.K <= 65535) {
+    dim3 g((unsigned)((sh.C + 255) / 256), (unsigned)sh.K, (unsigned)count);
+    if (is_bf16) hipLaunchKernelGGL(fc_wgrad_simple_kernel<bf16_t>, g, dim3(256), 0, s, ws, grads, x_off, dy_off, w_off, b_off, sh.N, sh.C, sh.K);
+    else hipLaunchKernelGGL(fc_wgrad_simple_kernel<float>, g, dim3(256), 0, s, ws, grads, x_off, dy_off, w_off, b_off, sh.N, sh.C, sh.K);
+    return hipGetLastError();
+  }
   const int64_t elems = (int64_t)sh.K * sh.C * sh.ks * sh.ks + sh.K;
   const int64_t blocks = (elems + 3) / 4;
   if (blocks > 0x7fffffff) return hipErrorInvalidValue;

@@ -102,8 +102,59 @@ __global__ __launch_bounds__(256) void pack_input_pixel_kernel(CPtrTab images, P
   }
 }
 
+// Space-to-depth by 4 of a 3-channel image (the 11 x 11 / 4 first layer): one lane per destination pixel reads twelve
+// aligned float4 (channel c, row 4Y + dh, columns 4X .. 4X+3) and writes its 48 channels (dh * 4 + dw) * 3 + c as six
+// 16-byte chunks.  Needs W % 4 == 0 and 16-byte aligned images (and mean).
+__global__ __launch_bounds__(256) void pack_input_s2d4_kernel(CPtrTab images, PtrTab ws, size_t out_off, int N, InPack ip,
+                                                              const float* __restrict__ mean) {
+  const float* in = (const float*)images.p[blockIdx.z];
+  bf16_t* out = (bf16_t*)ws.p[blockIdx.z] + out_off;
+  const int64_t total = (int64_t)N * ip.Hp * ip.Wp;
+  const int64_t plane = (int64_t)ip.H * ip.W;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
+    uint32_t r = (uint32_t)i;
+    const int X = (int)(r % (uint32_t)ip.Wp);
+    r /= (uint32_t)ip.Wp;
+    const int Y = (int)(r % (uint32_t)ip.Hp);
+    const int n = (int)(r / (uint32_t)ip.Hp);
+    const float* src = in + (int64_t)n * 3 * plane;
+    float f[48];
+#pragma unroll
+    for (int dh = 0; dh < 4; dh++) {
+      const int h = 4 * Y + dh;
+#pragma unroll
+      for (int c = 0; c < 3; c++) {
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (h < ip.H && 4 * X < ip.W) {
+          const int64_t pix = c * plane + (int64_t)h * ip.W + 4 * X;
+          v = *reinterpret_cast<const float4*>(src + pix);
+          if (mean) {
+            const float4 mv = *reinterpret_cast<const float4*>(mean + pix);
+            v.x -= mv.x; v.y -= mv.y; v.z -= mv.z; v.w -= mv.w;
+          }
+        }
+        f[(dh * 4 + 0) * 3 + c] = v.x;
+        f[(dh * 4 + 1) * 3 + c] = v.y;
+        f[(dh * 4 + 2) * 3 + c] = v.z;
+        f[(dh * 4 + 3) * 3 + c] = v.w;
+      }
+    }
+#pragma unroll
+    for (int c0 = 0; c0 < 48; c0 += 8) *reinterpret_cast<uint4*>(out + i * 48 + c0) = pack8(f + c0);
+  }
+}
+
 hipError_t launch_pack_input(bool is_bf16, const CPtrTab& images, const PtrTab& ws, size_t out_off, int count, int N,
                              const InPack& ip, const float* mean, hipStream_t s) {
+  if (is_bf16 && ip.s2d == 4 && ip.C == 3 && ip.Cp == 48 && ip.W % 4 == 0 && out_off % 8 == 0 && ((uintptr_t)mean & 15) == 0) {
+    bool aligned = true;
+    for (int k = 0; k < count; k++) aligned = aligned && ((uintptr_t)images.p[k] & 15) == 0;
+    if (aligned) {
+      dim3 gv = grid_for((int64_t)N * ip.Hp * ip.Wp, count, 16384);
+      hipLaunchKernelGGL(pack_input_s2d4_kernel, gv, dim3(256), 0, s, images, ws, out_off, N, ip, mean);
+      return hipGetLastError();
+    }
+  }
   if (is_bf16 && ip.Cp % 8 == 0 && out_off % 8 == 0) {
     dim3 gv = grid_for((int64_t)N * ip.Hp * ip.Wp, count, 16384);
     hipLaunchKernelGGL(pack_input_pixel_kernel, gv, dim3(256), 0, s, images, ws, out_off, N, ip, mean);
@@ -203,12 +254,14 @@ __global__ __launch_bounds__(256) void pool_fwd_vec8_kernel(PtrTab ws, size_t x_
   const int C8 = sh.C / 8;
   const int64_t total = (int64_t)sh.N * sh.OH * sh.OW * C8;
   for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
-    int c8 = (int)(i % C8);
-    int64_t r = i / C8;
-    int ow = (int)(r % sh.OW);
-    r /= sh.OW;
-    int oh = (int)(r % sh.OH);
-    int n = (int)(r / sh.OH);
+    // 32-bit index arithmetic: a tensor of one learner has fewer than 2^31 elements
+    uint32_t r = (uint32_t)i;
+    const int c8 = (int)(r % (uint32_t)C8);
+    r /= (uint32_t)C8;
+    const int ow = (int)(r % (uint32_t)sh.OW);
+    r /= (uint32_t)sh.OW;
+    const int oh = (int)(r % (uint32_t)sh.OH);
+    const int n = (int)(r / (uint32_t)sh.OH);
     const int h0 = oh * sh.stride, w0 = ow * sh.stride;
     float acc[8];
     int best[8];
@@ -255,12 +308,13 @@ __global__ __launch_bounds__(256) void pool_bwd_vec8_kernel(PtrTab ws, size_t dy
   const int C8 = sh.C / 8;
   const int64_t total = (int64_t)sh.N * sh.H * sh.W * C8;
   for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
-    int c8 = (int)(i % C8);
-    int64_t r = i / C8;
-    int iw = (int)(r % sh.W);
-    r /= sh.W;
-    int ih = (int)(r % sh.H);
-    int n = (int)(r / sh.H);
+    uint32_t r = (uint32_t)i;
+    const int c8 = (int)(r % (uint32_t)C8);
+    r /= (uint32_t)C8;
+    const int iw = (int)(r % (uint32_t)sh.W);
+    r /= (uint32_t)sh.W;
+    const int ih = (int)(r % (uint32_t)sh.H);
+    const int n = (int)(r / (uint32_t)sh.H);
     float acc[8];
 #pragma unroll
     for (int e = 0; e < 8; e++) acc[e] = 0.f;
