@@ -551,24 +551,49 @@ __global__ __launch_bounds__(NT, (WM * WN > 64 * 64 ? 2 : 1)) void igemm_frag_ke
 // Sum of the split partials in split order, then bias / ReLU / mask / conversion.
 __global__ __launch_bounds__(256) void igemm_finish_kernel(PtrTab ws, CPtrTab wts, IGemm g, Epilogue ep) {
   const int z = blockIdx.z;
-  const float* part = reinterpret_cast<const float*>((const char*)ws.p[z] + g.scratch_off);
+  const float4* part = reinterpret_cast<const float4*>((const char*)ws.p[z] + g.scratch_off);
   bf16_t* out = (bf16_t*)ws.p[z] + ep.out_off;
   const bf16_t* mask = (const bf16_t*)ws.p[z] + ep.mask_off;
   const bf16_t* bias = (const bf16_t*)wts.p[z] + ep.bias_off;
-  const int64_t total = (int64_t)g.M * g.Ncols;
-  for (int64_t o = (int64_t)blockIdx.x * 256 + threadIdx.x; o < total; o += (int64_t)gridDim.x * 256) {
-    float v = 0.f;
-    for (int sp = 0; sp < g.splits; sp++) v += part[(int64_t)sp * total + o];
-    if (ep.has_bias) v += bf2f(bias[o % g.Ncols]);
-    if (ep.relu) v = fmaxf(v, 0.f);
-    if (ep.use_mask && !(bf2f(mask[o]) > 0.f)) v = 0.f;
-    if (ep.out_f32) reinterpret_cast<float*>(out)[o] = v;
-    else out[o] = f2bf(v);
+  // four consecutive columns per thread (the column count is a multiple of 8)
+  const uint32_t total4 = (uint32_t)(((int64_t)g.M * g.Ncols) >> 2);
+  for (uint32_t o4 = blockIdx.x * 256 + threadIdx.x; o4 < total4; o4 += gridDim.x * 256) {
+    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int sp = 0; sp < g.splits; sp++) {
+      const float4 p = part[(size_t)sp * total4 + o4];
+      v.x += p.x; v.y += p.y; v.z += p.z; v.w += p.w;
+    }
+    const int64_t o = (int64_t)o4 * 4;
+    float f[4] = {v.x, v.y, v.z, v.w};
+    if (ep.has_bias) {
+      const int n = (int)((o4 * 4u) % (uint32_t)g.Ncols);
+#pragma unroll
+      for (int e = 0; e < 4; e++) f[e] += bf2f(bias[n + e]);
+    }
+    if (ep.relu) {
+#pragma unroll
+      for (int e = 0; e < 4; e++) f[e] = fmaxf(f[e], 0.f);
+    }
+    if (ep.use_mask) {
+      const uint2 mk = *reinterpret_cast<const uint2*>(mask + o);
+      const bf16_t m4[4] = {(bf16_t)(mk.x & 0xffffu), (bf16_t)(mk.x >> 16), (bf16_t)(mk.y & 0xffffu), (bf16_t)(mk.y >> 16)};
+#pragma unroll
+      for (int e = 0; e < 4; e++)
+        if (!(bf2f(m4[e]) > 0.f)) f[e] = 0.f;
+    }
+    if (ep.out_f32) {
+      reinterpret_cast<float4*>(out)[o4] = make_float4(f[0], f[1], f[2], f[3]);
+    } else {
+      uint2 w;
+      w.x = (uint32_t)f2bf(f[0]) | ((uint32_t)f2bf(f[1]) << 16);
+      w.y = (uint32_t)f2bf(f[2]) | ((uint32_t)f2bf(f[3]) << 16);
+      *reinterpret_cast<uint2*>(out + o) = w;
+    }
   }
 }
 
 int choose_splits(int64_t tiles, int count, int steps, size_t bytes_per_split, size_t scratch_bytes) {
-  const int64_t target = 600;   // workgroups wanted per launch; 384..1024 measured, 600-768 best at 6 and 18 learners
+  const int64_t target = 600;   // workgroups wanted per launch; 256..1024 measured, flat between 400 and 768 at 6 and 18 learners
   int64_t sp = (target + tiles * count - 1) / (tiles * count);
   if (sp > steps / 4) sp = steps / 4;                // keep at least four contraction steps per workgroup
   if (bytes_per_split > 0 && (int64_t)(scratch_bytes / bytes_per_split) < sp) sp = (int64_t)(scratch_bytes / bytes_per_split);
@@ -581,8 +606,8 @@ static void launch_igemm_t(const PtrTab& ws, const CPtrTab& wts, const IGemm& g,
   dim3 grid((unsigned)((g.M + BM - 1) / BM), (unsigned)((g.Ncols + BN - 1) / BN), (unsigned)(count * g.splits));
   hipLaunchKernelGGL((igemm_kernel<BM, BN, WM, WN, BT>), grid, dim3(256), 0, s, ws, wts, g, ep);
   if (g.splits > 1) {
-    int64_t total = (int64_t)g.M * g.Ncols;
-    unsigned blocks = (unsigned)((total + 255) / 256 < 1024 ? (total + 255) / 256 : 1024);
+    int64_t total = ((int64_t)g.M * g.Ncols) >> 2;
+    unsigned blocks = (unsigned)((total + 255) / 256 < 2048 ? (total + 255) / 256 : 2048);
     hipLaunchKernelGGL(igemm_finish_kernel, dim3(blocks, 1, (unsigned)count), dim3(256), 0, s, ws, wts, g, ep);
   }
 }
@@ -595,8 +620,8 @@ static void launch_frag_t(const PtrTab& ws, const CPtrTab& wts, const IGemm& g, 
   if (uni) hipLaunchKernelGGL((igemm_frag_kernel<BM, BN, WM, WN, 32, NT, true>), grid, dim3(NT), 0, s, ws, wts, g, ep);
   else hipLaunchKernelGGL((igemm_frag_kernel<BM, BN, WM, WN, 32, NT, false>), grid, dim3(NT), 0, s, ws, wts, g, ep);
   if (g.splits > 1) {
-    int64_t total = (int64_t)g.M * g.Ncols;
-    unsigned blocks = (unsigned)((total + 255) / 256 < 1024 ? (total + 255) / 256 : 1024);
+    int64_t total = ((int64_t)g.M * g.Ncols) >> 2;
+    unsigned blocks = (unsigned)((total + 255) / 256 < 2048 ? (total + 255) / 256 : 2048);
     hipLaunchKernelGGL(igemm_finish_kernel, dim3(blocks, 1, (unsigned)count), dim3(256), 0, s, ws, wts, g, ep);
   }
 }
