@@ -198,13 +198,18 @@ def bench_net(args, cfg_id):
     ms_g, n_g = ctx.phaseTime(0)
     ms_u, n_u = ctx.phaseTime(1)
     P = ctx.P
+    Wf = ctx.factoredParams()      # fully connected weights whose gradient is formed inside applyUpdate from its factors
     ctx.destroy()
     images = args.steps * c * mu
     flop_img = {0: 68.87424e6, 2: 68.87424e6, 3: 68.87424e6, 4: 6.585512448e9}[cfg_id]   # forward + backward MACs x 2 per image
+    flop_img -= 2.0 * Wf           # those weight-gradient MACs are not done by calcGradient
     fp32 = cfg["compute"] == "fp32"
     peak = 157.3 if fp32 else 2500.0
     t_grad = ms_g * 1e-3                                      # all calcGradient calls of the timed region, seconds
     ach = images * flop_img / t_grad / 1e12
+    # algorithmic bytes of one update: theta, v read and written, a 2-byte copy in bf16 compute, and 4 bytes per pending
+    # gradient for every parameter whose gradient is a written-out vector
+    upd_bytes = P * (16 + (0 if fp32 else 2)) + (P - Wf) * 4 * c
     out = {
         "metric": "training images/sec per GPU", "value": round(images / dt, 1), "unit": "images/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(dt / args.steps * 1e3, 4),
@@ -216,8 +221,8 @@ def bench_net(args, cfg_id):
                                                 "flop = 2 x forward+backward MACs of %d images)" % (n_g, images),
                      "achieved": round(ach, 2), "peak": peak, "unit": "TFLOP/s", "frac": round(ach / peak, 5),
                      "traffic": None, "avg_call_us": round(t_grad / n_g * 1e6, 1), "learners_per_call": round(images / mu / n_g, 2)},
-        "applyUpdate": {"avg_launch_us": round(ms_u / n_u * 1e3, 2), "bytes_per_launch": P * (4 * c + 18),
-                        "achieved_GBs": round(P * (4 * c + 18) / (ms_u / n_u * 1e-3) / 1e9, 1)},
+        "applyUpdate": {"avg_launch_us": round(ms_u / n_u * 1e3, 2), "bytes_per_launch": upd_bytes,
+                        "achieved_GBs": round(upd_bytes / (ms_u / n_u * 1e-3) / 1e9, 1), "factored_fc_weights": Wf},
     }
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline_net(cfg)
@@ -257,9 +262,10 @@ def bench_calc(args, cfg_id):
     dt = time.perf_counter() - t0
     ms_g, n_g = ctx.phaseTime(0)
     P = ctx.P
+    Wf = ctx.factoredParams()
     ctx.destroy()
     images = args.steps * lam * mu
-    flop_img = {3: 68.87424e6, 4: 6.585512448e9}[cfg_id]
+    flop_img = {3: 68.87424e6, 4: 6.585512448e9}[cfg_id] - 2.0 * Wf   # factored fc weight gradients are formed by applyUpdate
     ach = images * flop_img / (ms_g * 1e-3) / 1e12
     out = {
         "metric": "calcGradient images/sec per GPU (no server update)", "value": round(images / dt, 1), "unit": "images/s",

@@ -51,6 +51,8 @@ enum { SASGD_NET_NONE = 0, SASGD_NET_CIFAR3 = 1, SASGD_NET_ALEX8 = 2, SASGD_NET_
 enum { SASGD_FP32 = 0, SASGD_BF16 = 1 };
 enum { SASGD_LR_PER_GRADIENT = 0, SASGD_LR_MEAN_STALENESS = 1, SASGD_LR_CONSTANT = 2 };
 enum { SASGD_CONV = 0, SASGD_MAXPOOL = 1, SASGD_AVGPOOL = 2, SASGD_RELU = 3, SASGD_FC = 4 };
+/* flags */
+enum { SASGD_FLAG_FLAT_FC_GRADIENT = 1 };   /* see sasgd_config.flags */
 
 /* One layer of a custom network (SASGD_NET_CUSTOM).  The loss, softmax cross-entropy averaged
  * over the mini-batch, follows the last layer implicitly.
@@ -75,7 +77,13 @@ typedef struct {
   int32_t lr_mode;      /* PER_GRADIENT: alpha0 / tau_l for each gradient (Section 2.4);
                            MEAN_STALENESS: alpha0 / mean_l(tau_l); CONSTANT: alpha0.  A staleness
                            of 0 uses alpha0 unmodulated in every mode.                               */
-  int32_t reserved0;
+  int32_t flags;        /* 0, or SASGD_FLAG_FLAT_FC_GRADIENT.  By default (BF16 compute, mu <= 32) the weight
+                           gradient of a fully connected layer is not written out: with a mini-batch of mu
+                           images it is the rank-mu product dy^T x, so calcGradient keeps the two factors
+                           (mu x out and mu x in values) and applyUpdate forms the product on the fly in the
+                           same fp32 arithmetic.  The 4 bytes per weight of gradient written by the learner
+                           and read by the server disappear; copyGradient / gradientPtr expand the product on
+                           demand.  The flag forces the written-out gradient instead.                        */
   int64_t num_params;   /* NET_NONE: length P of the parameter vector; otherwise 0 or the expected
                            P, checked against the network                                            */
   float alpha0;         /* base learning rate                                                        */
@@ -171,6 +179,8 @@ int sasgd_setPixelMean(sasgd_ctx* ctx, const float* mean_dev);
 int sasgd_timestamp(sasgd_ctx* ctx, int64_t* out);
 int sasgd_numParams(sasgd_ctx* ctx, int64_t* out);
 int sasgd_gradientsPerUpdate(sasgd_ctx* ctx, int32_t* out_c);
+/* Number of parameters (fully connected weights) whose gradients are kept as factors (see flags); 0 if none. */
+int sasgd_factoredParams(sasgd_ctx* ctx, int64_t* out);
 /* Timestamp of the learner's last computed gradient (-1 if none). */
 int sasgd_gradientTimestamp(sasgd_ctx* ctx, int32_t learner, int64_t* out);
 /* Blocking copies to host float[P].  copyWeights: version must be in the ring; with BF16 compute
@@ -178,7 +188,9 @@ int sasgd_gradientTimestamp(sasgd_ctx* ctx, int32_t learner, int64_t* out);
 int sasgd_copyWeights(sasgd_ctx* ctx, int64_t version, float* host_out);
 int sasgd_copyGradient(sasgd_ctx* ctx, int32_t learner, float* host_out);
 int sasgd_copyMomentum(sasgd_ctx* ctx, float* host_out);
-/* Device address of a learner's gradient buffer (float32 [P]); valid for the context's lifetime. */
+/* Device address of a learner's gradient buffer (float32 [P]); valid for the context's lifetime.
+ * Fully connected weight gradients kept as factors (see flags) are expanded into the buffer by
+ * this call and by copyGradient (enqueued on the context's stream). */
 int sasgd_gradientPtr(sasgd_ctx* ctx, int32_t learner, float** out_dev);
 
 /* Accumulated device time of the two hot phases since the last reset, measured with HIP events

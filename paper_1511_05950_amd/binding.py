@@ -19,6 +19,7 @@ FP32, BF16 = 0, 1
 LR_PER_GRADIENT, LR_MEAN_STALENESS, LR_CONSTANT = 0, 1, 2
 LAYER_KINDS = {"conv": 0, "maxpool": 1, "avgpool": 2, "relu": 3, "fc": 4}
 LR_MODES = {"per_gradient": 0, "mean_staleness": 1, "constant": 2}
+FLAG_FLAT_FC_GRADIENT = 1
 COMPUTE = {"fp32": 0, "bf16": 1}
 
 EXPORTS = [
@@ -27,7 +28,7 @@ EXPORTS = [
     "sasgd_timestamp", "sasgd_numParams", "sasgd_gradientsPerUpdate", "sasgd_gradientTimestamp",
     "sasgd_copyWeights", "sasgd_copyGradient", "sasgd_copyMomentum", "sasgd_gradientPtr",
     "sasgd_setProfiling", "sasgd_phaseTime", "sasgd_last_error", "sasgd_version",
-    "sasgd_evaluate", "sasgd_setBaseRate", "sasgd_setPixelMean",
+    "sasgd_evaluate", "sasgd_setBaseRate", "sasgd_setPixelMean", "sasgd_factoredParams",
 ]
 
 
@@ -43,7 +44,7 @@ RELEASE_FN = ctypes.CFUNCTYPE(None, ctypes.c_void_p, ctypes.c_void_p)
 class SasgdConfig(ctypes.Structure):
     _fields_ = [
         ("lambda_", ctypes.c_int32), ("mu", ctypes.c_int32), ("n", ctypes.c_int32), ("ring_depth", ctypes.c_int32),
-        ("net", ctypes.c_int32), ("compute", ctypes.c_int32), ("lr_mode", ctypes.c_int32), ("reserved0", ctypes.c_int32),
+        ("net", ctypes.c_int32), ("compute", ctypes.c_int32), ("lr_mode", ctypes.c_int32), ("flags", ctypes.c_int32),
         ("num_params", ctypes.c_int64),
         ("alpha0", ctypes.c_float), ("momentum", ctypes.c_float), ("weight_decay", ctypes.c_float), ("reserved1", ctypes.c_float),
         ("stream", ctypes.c_void_p),
@@ -84,6 +85,7 @@ def load():
         lib.sasgd_timestamp.argtypes = [vp, P(i64)]
         lib.sasgd_numParams.argtypes = [vp, P(i64)]
         lib.sasgd_gradientsPerUpdate.argtypes = [vp, P(i32)]
+        lib.sasgd_factoredParams.argtypes = [vp, P(i64)]
         lib.sasgd_gradientTimestamp.argtypes = [vp, i32, P(i64)]
         lib.sasgd_copyWeights.argtypes = [vp, i64, vp]
         lib.sasgd_copyGradient.argtypes = [vp, i32, vp]
@@ -120,13 +122,14 @@ class Sasgd:
     """One context of the C library.  Methods mirror the C calls one to one."""
 
     def __init__(self, lam, mu, n, ring_depth, net=None, compute="fp32", lr_mode="per_gradient",
-                 num_params=0, alpha0=0.01, momentum=0.0, weight_decay=0.0, init_weights=None, stream=None):
+                 num_params=0, alpha0=0.01, momentum=0.0, weight_decay=0.0, init_weights=None, stream=None, flags=0):
         lib = load()
         cfg = SasgdConfig()
         cfg.lambda_, cfg.mu, cfg.n, cfg.ring_depth = lam, mu, n, ring_depth
         cfg.compute = COMPUTE[compute] if isinstance(compute, str) else compute
         cfg.lr_mode = LR_MODES[lr_mode] if isinstance(lr_mode, str) else lr_mode
         cfg.num_params = num_params
+        cfg.flags = flags
         cfg.alpha0, cfg.momentum, cfg.weight_decay = alpha0, momentum, weight_decay
         if stream is None:
             import torch
@@ -248,6 +251,11 @@ class Sasgd:
         c = ctypes.c_int32()
         self._check(load().sasgd_gradientsPerUpdate(self._h, ctypes.byref(c)))
         return c.value
+
+    def factoredParams(self):
+        n = ctypes.c_int64()
+        self._check(load().sasgd_factoredParams(self._h, ctypes.byref(n)))
+        return n.value
 
     def gradientTimestamp(self, learner):
         ts = ctypes.c_int64()

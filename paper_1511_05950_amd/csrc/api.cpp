@@ -267,6 +267,7 @@ int sasgd_calcGradient(sasgd_ctx* ctx, const int32_t* learners, int32_t count, f
     Learner& L = ctx->learners[(size_t)ids[k]];
     L.grad_timestamp = L.pulled_version;   // gradient timestamp = timestamp of the weights used (Section 2.1)
     L.grad_state = GRAD_COMPUTED;
+    L.fc_expanded = false;
     L.has_weights = false;                 // one mini-batch per push: nothing is accrued at the learner
     L.images = nullptr;
     L.labels = nullptr;
@@ -324,6 +325,7 @@ int sasgd_pushGradient(sasgd_ctx* ctx, int32_t learner, int32_t* out_staleness) 
   if (L.grad_state != GRAD_COMPUTED) return fail(ctx, SASGD_ESTATE, "pushGradient: no freshly computed gradient");
   if ((int)ctx->pending.size() >= kMaxLearners) return fail(ctx, SASGD_ESTATE, "pushGradient: pending queue full");
   Pending p;
+  p.factors_ws = L.workspace;   // fully connected factors, if the network keeps any, live in the learner's workspace
   p.grad = L.grad;
   p.timestamp = L.grad_timestamp;
   p.staleness = (int32_t)(ctx->timestamp - L.grad_timestamp);   // tau = i - j
@@ -340,6 +342,7 @@ int sasgd_pushGradientExternal(sasgd_ctx* ctx, const float* grad_dev, int64_t ti
   if (timestamp < 0 || timestamp > ctx->timestamp) return fail(ctx, SASGD_EINVAL, "pushGradientExternal: timestamp must lie in [0, i]");
   if ((int)ctx->pending.size() >= kMaxLearners) return fail(ctx, SASGD_ESTATE, "pushGradientExternal: pending queue full");
   Pending p;
+  p.factors_ws = nullptr;
   p.grad = grad_dev;
   p.timestamp = timestamp;
   p.staleness = (int32_t)(ctx->timestamp - timestamp);
@@ -410,8 +413,52 @@ int sasgd_applyUpdate(sasgd_ctx* ctx, int64_t* out_new_timestamp) {
     u.theta_out = ctx->ring_f32 + (size_t)slot_of(ctx, i + 1) * (size_t)ctx->P;
     u.shadow_out = nullptr;
   }
+  // Layers whose gradients are kept as factors get their own launch; the stretches of the flat vector between them
+  // go through the streaming kernel.
+  FactoredLayer fl[16];
+  const int nfl = ctx->net ? net_factored_layers(ctx->net, fl, 16) : 0;
   prof_begin(ctx, 1);
-  hipError_t e = launch_apply_update(u, ctx->stream);
+  hipError_t e = hipSuccess;
+  if (nfl == 0 || nfl > 16) {
+    e = launch_apply_update(u, ctx->stream);
+  } else {
+    auto flat_range = [&](int64_t begin, int64_t end) {
+      if (end <= begin) return hipSuccess;
+      UpdateLaunch r = u;
+      r.theta_in += begin;
+      r.theta_out += begin;
+      r.v += begin;
+      if (r.shadow_out) r.shadow_out += begin;
+      for (int l = 0; l < u.c; l++) r.grads[l] += begin;
+      r.P = end - begin;
+      return launch_apply_update(r, ctx->stream);
+    };
+    int64_t cursor = 0;
+    for (int k = 0; k < nfl && e == hipSuccess; k++) {
+      const FactoredLayer& F = fl[k];
+      e = flat_range(cursor, F.w_off);
+      if (e != hipSuccess) break;
+      FcUpdateLaunch fu;
+      fu.theta_in = u.theta_in + F.w_off;
+      fu.theta_out = u.theta_out + F.w_off;
+      fu.v = u.v + F.w_off;
+      fu.shadow_out = u.shadow_out ? u.shadow_out + F.w_off : nullptr;
+      fu.in = F.in; fu.out = F.out; fu.N = F.N; fu.NP = F.NP;
+      fu.c = u.c;
+      for (int l = 0; l < u.c; l++) {
+        const Pending& pd = ctx->pending[(size_t)l];
+        fu.grads[l] = pd.grad + F.w_off;
+        fu.coef[l] = u.coef[l];
+        fu.fx[l] = pd.factors_ws ? (const bf16_t*)pd.factors_ws + F.fx_off : nullptr;
+        fu.fdyT[l] = pd.factors_ws ? (const bf16_t*)pd.factors_ws + F.fdy_off : nullptr;
+      }
+      fu.momentum = u.momentum;
+      fu.decay = u.decay;
+      e = launch_apply_update_fc(fu, ctx->stream);
+      cursor = F.w_off + (int64_t)F.out * F.in + F.out;
+    }
+    if (e == hipSuccess) e = flat_range(cursor, ctx->P);
+  }
   prof_end(ctx);
   if (e == hipSuccess && new_slot_b16 && ctx->net)
     e = net_prepare_version(ctx->net, new_slot_b16, new_slot_b16 + Ppad, ctx->stream);
@@ -443,6 +490,17 @@ int sasgd_numParams(sasgd_ctx* ctx, int64_t* out) {
 int sasgd_gradientsPerUpdate(sasgd_ctx* ctx, int32_t* out_c) {
   if (!ctx || !out_c) return SASGD_EINVAL;
   *out_c = ctx->c;
+  return SASGD_OK;
+}
+
+int sasgd_factoredParams(sasgd_ctx* ctx, int64_t* out) {
+  if (!ctx || !out) return SASGD_EINVAL;
+  *out = 0;
+  if (ctx->net) {
+    FactoredLayer fl[16];
+    const int nfl = net_factored_layers(ctx->net, fl, 16);
+    for (int k = 0; k < nfl && k < 16; k++) *out += (int64_t)fl[k].in * fl[k].out;
+  }
   return SASGD_OK;
 }
 
@@ -479,12 +537,28 @@ int sasgd_copyWeights(sasgd_ctx* ctx, int64_t version, float* host_out) {
   return SASGD_OK;
 }
 
+// Writes the fully connected weight gradients that the learner holds as factors into its flat gradient buffer.
+static hipError_t expand_factored(sasgd_ctx* ctx, Learner& L) {
+  if (!ctx->net || L.fc_expanded || L.grad_timestamp < 0) return hipSuccess;
+  FactoredLayer fl[16];
+  const int nfl = net_factored_layers(ctx->net, fl, 16);
+  for (int k = 0; k < nfl && k < 16; k++) {
+    const FactoredLayer& F = fl[k];
+    hipError_t e = launch_fc_expand_factors((const bf16_t*)L.workspace + F.fx_off, (const bf16_t*)L.workspace + F.fdy_off,
+                                            L.grad + F.w_off, F.N, F.in, F.out, F.NP, ctx->stream);
+    if (e != hipSuccess) return e;
+  }
+  L.fc_expanded = true;
+  return hipSuccess;
+}
+
 int sasgd_copyGradient(sasgd_ctx* ctx, int32_t learner, float* host_out) {
   if (!ctx || !host_out || learner < 0 || learner >= ctx->cfg.lambda) return SASGD_EINVAL;
-  const Learner& L = ctx->learners[(size_t)learner];
+  Learner& L = ctx->learners[(size_t)learner];
   if (!L.grad) return fail(ctx, SASGD_EINVAL, "copyGradient: context has no network");
   if (L.grad_timestamp < 0) return fail(ctx, SASGD_ESTATE, "copyGradient: learner has not computed a gradient");
-  hipError_t e = hipMemcpyAsync(host_out, L.grad, (size_t)ctx->P * sizeof(float), hipMemcpyDeviceToHost, ctx->stream);
+  hipError_t e = expand_factored(ctx, L);
+  if (e == hipSuccess) e = hipMemcpyAsync(host_out, L.grad, (size_t)ctx->P * sizeof(float), hipMemcpyDeviceToHost, ctx->stream);
   if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
   if (e != hipSuccess) return fail_hip(ctx, e, "copyGradient");
   return SASGD_OK;
@@ -501,6 +575,8 @@ int sasgd_copyMomentum(sasgd_ctx* ctx, float* host_out) {
 int sasgd_gradientPtr(sasgd_ctx* ctx, int32_t learner, float** out_dev) {
   if (!ctx || !out_dev || learner < 0 || learner >= ctx->cfg.lambda) return SASGD_EINVAL;
   if (!ctx->learners[(size_t)learner].grad) return fail(ctx, SASGD_EINVAL, "gradientPtr: context has no network");
+  hipError_t e = expand_factored(ctx, ctx->learners[(size_t)learner]);
+  if (e != hipSuccess) return fail_hip(ctx, e, "gradientPtr");
   *out_dev = ctx->learners[(size_t)learner].grad;
   return SASGD_OK;
 }

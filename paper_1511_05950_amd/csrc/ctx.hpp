@@ -28,6 +28,23 @@ struct UpdateLaunch {
   float decay;             // (sum_l coef_l) * weight_decay
 };
 hipError_t launch_apply_update(const UpdateLaunch& u, hipStream_t stream);
+// Update of one fully connected layer (weights [out][in] followed by the bias [out]) whose gradients are kept as
+// factors.  All pointers address the first weight of the layer.
+struct FcUpdateLaunch {
+  const float* theta_in;
+  float* theta_out;
+  float* v;
+  bf16_t* shadow_out;      // optional
+  int in, out, N, NP;      // N images per mini-batch, dyT rows padded to NP
+  int32_t c;
+  const float* grads[kMaxLearners];     // written-out gradient of every pending gradient (bias part always used)
+  const bf16_t* fx[kMaxLearners];       // factor x [N][in], or nullptr: use the written-out weights gradient
+  const bf16_t* fdyT[kMaxLearners];     // factor dy transposed [out][NP]
+  float coef[kMaxLearners];
+  float momentum;
+  float decay;
+};
+hipError_t launch_apply_update_fc(const FcUpdateLaunch& u, hipStream_t stream);
 hipError_t launch_fp32_to_bf16(const float* src, bf16_t* dst, int64_t n, hipStream_t stream);
 hipError_t launch_bf16_to_fp32(const bf16_t* src, float* dst, int64_t n, hipStream_t stream);
 
@@ -52,6 +69,16 @@ hipError_t net_prepare_version(Net* net, const void* flat, void* packed, hipStre
 // out_rank_dev != nullptr: evaluation pass, forward and loss only, plus the rank of each image's true class.
 hipError_t net_calc_gradient(Net* net, const int* learners, const LearnerBind* binds, int count,
                              float* out_loss_dev, int32_t* out_rank_dev, hipStream_t stream);
+// Fully connected layers whose weight gradient calcGradient leaves as factors in the learner's workspace
+// (bf16 element offsets from the workspace base): weights at w_off [out][in], bias right behind them.
+struct FactoredLayer {
+  int64_t w_off;
+  int in, out, N, NP;
+  size_t fx_off, fdy_off;
+};
+int net_factored_layers(const Net* net, FactoredLayer* out, int max);
+// dW [out][in] fp32 from the factors (layers.hip); used by the getters that hand out a written-out gradient
+hipError_t launch_fc_expand_factors(const void* fx, const void* fdy, float* dw, int N, int in, int out, int NP, hipStream_t s);
 void net_set_pixel_mean(Net* net, const float* mean_dev);
 void net_input_shape(const Net* net, int* C, int* H, int* W);
 
@@ -67,9 +94,11 @@ struct Learner {
   GradState grad_state = GRAD_NONE;
   float* grad = nullptr;       // [P] fp32 (nullptr for NET_NONE)
   void* workspace = nullptr;
+  bool fc_expanded = false;    // the factored parts of the current gradient have been written out into `grad`
 };
 
 struct Pending {
+  const void* factors_ws;   // workspace holding the fully connected factors of this gradient, or nullptr (written out)
   const float* grad;
   int64_t timestamp;   // j
   int32_t staleness;   // tau = i - j at push time

@@ -529,4 +529,67 @@ hipError_t launch_label_rank(bool is_bf16, bool z_f32, const PtrTab& ws, const C
   return hipGetLastError();
 }
 
+// ------------------------------------------------------------------ fully connected weight gradient as factors
+// The weight gradient of a fully connected layer over a mini-batch of N images is the rank-N product
+// dW[o][i] = sum_n dy[n][o] x[n][i].  Instead of writing out * in values, keep the factors: a copy of x [N][in]
+// and dy transposed to [out][NP] (NP = N rounded up to 8, zero-filled), so that the update kernel reads the N values
+// of one output unit as contiguous 16-byte pieces.  The bias gradient db[o] = sum_n dy[n][o] is written out.
+__global__ __launch_bounds__(256) void fc_save_factors_kernel(PtrTab ws, PtrTab grads, size_t x_off, size_t dy_off, size_t fx_off,
+                                                              size_t fdy_off, int64_t b_off, int N, int in, int out, int NP) {
+  const bf16_t* x = (const bf16_t*)ws.p[blockIdx.z] + x_off;
+  const bf16_t* dy = (const bf16_t*)ws.p[blockIdx.z] + dy_off;
+  bf16_t* fx = (bf16_t*)ws.p[blockIdx.z] + fx_off;
+  bf16_t* fdy = (bf16_t*)ws.p[blockIdx.z] + fdy_off;
+  float* db = (float*)grads.p[blockIdx.z] + b_off;
+  const int xchunks = N * in / 8;
+  const int t = blockIdx.x * 256 + threadIdx.x;
+  if (t < xchunks) {
+    reinterpret_cast<uint4*>(fx)[t] = reinterpret_cast<const uint4*>(x)[t];
+  } else if (t - xchunks < out) {
+    const int o = t - xchunks;
+    float sum = 0.f;
+    for (int n = 0; n < NP; n++) {
+      const bf16_t d = n < N ? dy[(int64_t)n * out + o] : (bf16_t)0;
+      fdy[(int64_t)o * NP + n] = d;
+      sum += bf2f(d);
+    }
+    db[o] = sum;
+  }
+}
+
+// dW[o][i] = sum_n dy[n][o] x[n][i] from the saved factors, in the arithmetic the update kernel uses (fp32 FMA in
+// image order): the written-out gradient for the getters.  Four input units per thread.
+__global__ __launch_bounds__(256) void fc_expand_factors_kernel(const bf16_t* __restrict__ fx, const bf16_t* __restrict__ fdy,
+                                                                float* __restrict__ dw, int N, int in, int out, int NP) {
+  const int64_t total4 = (int64_t)out * in / 4;
+  for (int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x; t < total4; t += (int64_t)gridDim.x * 256) {
+    const int o = (int)(t / (in / 4)), i = (int)(t % (in / 4)) * 4;
+    float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+    for (int n = 0; n < N; n++) {
+      const float d = bf2f(fdy[(int64_t)o * NP + n]);
+      const uint2 xv = *reinterpret_cast<const uint2*>(fx + (int64_t)n * in + i);
+      a0 = fmaf(d, __uint_as_float(xv.x << 16), a0);
+      a1 = fmaf(d, __uint_as_float(xv.x & 0xffff0000u), a1);
+      a2 = fmaf(d, __uint_as_float(xv.y << 16), a2);
+      a3 = fmaf(d, __uint_as_float(xv.y & 0xffff0000u), a3);
+    }
+    *reinterpret_cast<float4*>(dw + (int64_t)o * in + i) = make_float4(a0, a1, a2, a3);
+  }
+}
+
+hipError_t launch_fc_save_factors(const PtrTab& ws, const PtrTab& grads, size_t x_off, size_t dy_off, size_t fx_off, size_t fdy_off,
+                                  int64_t b_off, int N, int in, int out, int NP, int count, hipStream_t s) {
+  const int work = N * in / 8 + out;
+  hipLaunchKernelGGL(fc_save_factors_kernel, dim3((unsigned)((work + 255) / 256), 1, (unsigned)count), dim3(256), 0, s, ws, grads, x_off,
+                     dy_off, fx_off, fdy_off, b_off, N, in, out, NP);
+  return hipGetLastError();
+}
+
+hipError_t launch_fc_expand_factors(const void* fx, const void* fdy, float* dw, int N, int in, int out, int NP, hipStream_t s) {
+  const int64_t total4 = (int64_t)out * in / 4;
+  const unsigned blocks = (unsigned)((total4 + 255) / 256 < 8192 ? (total4 + 255) / 256 : 8192);
+  hipLaunchKernelGGL(fc_expand_factors_kernel, dim3(blocks), dim3(256), 0, s, (const bf16_t*)fx, (const bf16_t*)fdy, dw, N, in, out, NP);
+  return hipGetLastError();
+}
+
 }  // namespace sasgd

@@ -32,6 +32,10 @@ struct Op {
   bool dgrad_bt = false;       // fc: B operand is the flat weight matrix read transposed
   int64_t pack_fwd = -1, pack_bwd = -1;   // element offsets in the packed-filter region of a version slot
   int Kp = 0, Kpt = 0;
+  // fully connected layer whose weight gradient is kept as the factors x [N][in] and dy^T [out][NP]
+  bool factored = false;
+  size_t fx_off = 0, fdy_off = 0;         // element offsets of the two factor copies in the workspace
+  int NP = 0;
 };
 
 struct Tensor {
@@ -223,6 +227,14 @@ int net_create(const sasgd_config& cfg, Net** out, int64_t* out_P, size_t* out_p
         op.vc = VConv{in, 1, L.units, 1, in, 1};
         op.gf = IGemm{0, op.w_off, N, L.units, 1, 1, in, 1, 1, 1, 0, in / chunk, in / chunk, in};
         op.gd = IGemm{0, op.w_off, N, in, 1, 1, L.units, 1, 1, 1, 0, L.units / chunk, L.units / chunk, in};
+        // rank-N weight gradient kept as factors: worth it while the N FMAs per weight and pending gradient stay far
+        // below what the update's streaming rate leaves room for
+        const int c_upd = cfg.lambda / cfg.n;
+        if (net->bf16 && !(cfg.flags & SASGD_FLAG_FLAT_FC_GRADIENT) && N <= 32 && (int64_t)c_upd * N <= 1024 && op.w_off % 4 == 0 &&
+            L.units % 4 == 0 && in % 8 == 0) {
+          op.factored = true;
+          op.NP = (N + 7) & ~7;
+        }
       }
       C = L.units; H = 1; W = 1;
       flat = true;
@@ -248,6 +260,11 @@ int net_create(const sasgd_config& cfg, Net** out, int64_t* out_P, size_t* out_p
     net->ops.back().out_f32 = true;
     net->scores_f32 = true;
     if (net->bf16) { new_tensor(net->tensors[(size_t)cur].elems); }   // room for the wider elements (tensor is last in the arena)
+  }
+  for (Op& op : net->ops) {
+    if (!op.factored) continue;
+    op.fx_off = net->tensors[(size_t)new_tensor((size_t)N * op.cs.C)].off;
+    op.fdy_off = net->tensors[(size_t)new_tensor((size_t)op.cs.K * op.NP)].off;
   }
   net->P = P;
   net->Ppad = ((size_t)P + 63) & ~(size_t)63;
@@ -349,6 +366,16 @@ static void set_splits(const Net* net, IGemm& g, int steps, int count) {
   g.splits = choose_splits(tiles, count, steps, (size_t)g.M * g.Ncols * 4, net->scratch_bytes);
 }
 
+int net_factored_layers(const Net* net, FactoredLayer* out, int max) {
+  int k = 0;
+  for (const Op& op : net->ops) {
+    if (!op.factored) continue;
+    if (k < max) out[k] = FactoredLayer{op.w_off, op.cs.C, op.cs.K, op.cs.N, op.NP, op.fx_off, op.fdy_off};
+    k++;
+  }
+  return k;
+}
+
 void net_set_pixel_mean(Net* net, const float* mean_dev) { net->pixel_mean = mean_dev; }
 void net_input_shape(const Net* net, int* C, int* H, int* W) { *C = net->inC; *H = net->inH; *W = net->inW; }
 
@@ -417,6 +444,15 @@ hipError_t net_calc_gradient(Net* net, const int* learners, const LearnerBind* b
             gd.a_off = dy;
             Epilogue ep{dx, tin.off, 0, 0, 0, tin.relu ? 1 : 0, 1};
             TRY(launch_igemm_f32(ws, wts, gd, op.vc, ep, op.w_off, true, count, stream));
+          }
+        } else if (op.mfma && op.factored) {
+          TRY(launch_fc_save_factors(ws, grads, tin.off, dy, op.fx_off, op.fdy_off, op.b_off, op.cs.N, op.cs.C, op.cs.K, op.NP, count, stream));
+          if (need_dx) {
+            IGemm gd = op.gd;
+            gd.a_off = dy;
+            set_splits(net, gd, (gd.Kchunks + 3) / 4, count);
+            Epilogue ep{dx, tin.off, 0, 0, 0, tin.relu ? 1 : 0, 0};
+            TRY(launch_igemm(ws, wts, gd, ep, op.dgrad_bt, count, stream));
           }
         } else if (op.mfma) {
           IGemm gw = op.gf;

@@ -173,6 +173,144 @@ hipError_t launch_apply_update(const UpdateLaunch& u, hipStream_t stream) {
   return hipSuccess;
 }
 
+// ------------------------------------------------------------------ update of a fully connected layer from factors
+// For a fully connected layer with a mini-batch of N images the weight gradient is dW[o][i] = sum_n dy[n][o] x[n][i].
+// A learner keeps x [N][in] and dy transposed [out][NP] (bf16) instead of writing dW; this kernel forms the product
+// while it streams theta and v: per gradient  p = sum_n dy x  (fp32 FMA in image order, the arithmetic of the
+// written-out gradient),  s += coef * p,  then the same update as apply_update_kernel.  HBM traffic per weight drops
+// by the 4 bytes of gradient; the N FMAs per weight are far below what the streaming rate leaves room for.
+// Gradients without factors (pushed from outside) are read as written-out vectors.  The layer's bias follows its
+// weights in the flat vector and is updated by one extra row of workgroups from the written-out bias gradients.
+struct FcFactors {
+  const bf16_t* x[kMaxLearners];     // [N][in] or nullptr: gradient l is a written-out vector
+  const bf16_t* dyT[kMaxLearners];   // [out][NP]
+};
+
+constexpr int kFcRows = 8;           // output units per workgroup
+
+template <bool SHADOW>
+__global__ __launch_bounds__(256) void apply_update_fc_kernel(const float* theta_in, float* theta_out, float* v, bf16_t* shadow, int in,
+                                                              int out, int N, int NP, int c, GradTable t, FcFactors f, float m,
+                                                              float decay) {
+  const int nrb = (out + kFcRows - 1) / kFcRows;
+  const int col = (blockIdx.x * 256 + threadIdx.x) * 4;
+  if ((int)blockIdx.y == nrb) {       // bias: elements out * in + col .. col + 3
+    if (col >= out) return;
+    const int64_t e = (int64_t)out * in + col;
+    float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int l = 0; l < c; l++) {
+      const float4 g = *reinterpret_cast<const float4*>(t.g[l] + e);
+      s.x = fmaf(t.coef[l], g.x, s.x); s.y = fmaf(t.coef[l], g.y, s.y);
+      s.z = fmaf(t.coef[l], g.z, s.z); s.w = fmaf(t.coef[l], g.w, s.w);
+    }
+    float4 a = *reinterpret_cast<const float4*>(theta_in + e), b = *reinterpret_cast<const float4*>(v + e);
+    b.x = fmaf(m, b.x, s.x) + decay * a.x; b.y = fmaf(m, b.y, s.y) + decay * a.y;
+    b.z = fmaf(m, b.z, s.z) + decay * a.z; b.w = fmaf(m, b.w, s.w) + decay * a.w;
+    a.x -= b.x; a.y -= b.y; a.z -= b.z; a.w -= b.w;
+    *reinterpret_cast<float4*>(v + e) = b;
+    *reinterpret_cast<float4*>(theta_out + e) = a;
+    if (SHADOW) {
+      uint2 o;
+      o.x = (uint32_t)f32_to_bf16_rne(a.x) | ((uint32_t)f32_to_bf16_rne(a.y) << 16);
+      o.y = (uint32_t)f32_to_bf16_rne(a.z) | ((uint32_t)f32_to_bf16_rne(a.w) << 16);
+      *reinterpret_cast<uint2*>(shadow + e) = o;
+    }
+    return;
+  }
+  if (col >= in) return;
+  const int o0 = blockIdx.y * kFcRows;
+  float4 th[kFcRows], vv[kFcRows], s[kFcRows];
+#pragma unroll
+  for (int r = 0; r < kFcRows; r++) {
+    s[r] = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (o0 + r < out) {
+      const int64_t e = (int64_t)(o0 + r) * in + col;
+      th[r] = ldg_nt(reinterpret_cast<const float4*>(theta_in + e));
+      vv[r] = ldg_nt(reinterpret_cast<const float4*>(v + e));
+    }
+  }
+  for (int l = 0; l < c; l++) {
+    const float cf = t.coef[l];
+    if (f.x[l]) {
+      float4 p[kFcRows];
+#pragma unroll
+      for (int r = 0; r < kFcRows; r++) p[r] = make_float4(0.f, 0.f, 0.f, 0.f);
+      for (int n0 = 0; n0 < NP; n0 += 8) {
+        uint2 xr[8];
+#pragma unroll
+        for (int k = 0; k < 8; k++)
+          xr[k] = n0 + k < N ? *reinterpret_cast<const uint2*>(f.x[l] + (int64_t)(n0 + k) * in + col) : make_uint2(0u, 0u);
+#pragma unroll
+        for (int r = 0; r < kFcRows; r++) {
+          const int o = min(o0 + r, out - 1);           // rows beyond the layer compute a value nobody stores
+          const uint4 d8 = *reinterpret_cast<const uint4*>(f.dyT[l] + (int64_t)o * NP + n0);   // same address for the whole workgroup
+          const uint32_t dw[4] = {d8.x, d8.y, d8.z, d8.w};
+#pragma unroll
+          for (int k = 0; k < 8; k++) {
+            const float d = __uint_as_float((k & 1) ? (dw[k >> 1] & 0xffff0000u) : (dw[k >> 1] << 16));
+            p[r].x = fmaf(d, __uint_as_float(xr[k].x << 16), p[r].x);
+            p[r].y = fmaf(d, __uint_as_float(xr[k].x & 0xffff0000u), p[r].y);
+            p[r].z = fmaf(d, __uint_as_float(xr[k].y << 16), p[r].z);
+            p[r].w = fmaf(d, __uint_as_float(xr[k].y & 0xffff0000u), p[r].w);
+          }
+        }
+      }
+#pragma unroll
+      for (int r = 0; r < kFcRows; r++) {
+        s[r].x = fmaf(cf, p[r].x, s[r].x); s[r].y = fmaf(cf, p[r].y, s[r].y);
+        s[r].z = fmaf(cf, p[r].z, s[r].z); s[r].w = fmaf(cf, p[r].w, s[r].w);
+      }
+    } else {
+#pragma unroll
+      for (int r = 0; r < kFcRows; r++) {
+        if (o0 + r < out) {
+          const float4 g = ldg_nt(reinterpret_cast<const float4*>(t.g[l] + (int64_t)(o0 + r) * in + col));
+          s[r].x = fmaf(cf, g.x, s[r].x); s[r].y = fmaf(cf, g.y, s[r].y);
+          s[r].z = fmaf(cf, g.z, s[r].z); s[r].w = fmaf(cf, g.w, s[r].w);
+        }
+      }
+    }
+  }
+#pragma unroll
+  for (int r = 0; r < kFcRows; r++) {
+    if (o0 + r >= out) continue;
+    const int64_t e = (int64_t)(o0 + r) * in + col;
+    float4 a = th[r], b = vv[r];
+    b.x = fmaf(m, b.x, s[r].x) + decay * a.x; b.y = fmaf(m, b.y, s[r].y) + decay * a.y;
+    b.z = fmaf(m, b.z, s[r].z) + decay * a.z; b.w = fmaf(m, b.w, s[r].w) + decay * a.w;
+    a.x -= b.x; a.y -= b.y; a.z -= b.z; a.w -= b.w;
+    stg_nt(reinterpret_cast<float4*>(v + e), b);
+    stg_nt(reinterpret_cast<float4*>(theta_out + e), a);
+    if (SHADOW) {
+      uint2 o;
+      o.x = (uint32_t)f32_to_bf16_rne(a.x) | ((uint32_t)f32_to_bf16_rne(a.y) << 16);
+      o.y = (uint32_t)f32_to_bf16_rne(a.z) | ((uint32_t)f32_to_bf16_rne(a.w) << 16);
+      *reinterpret_cast<uint2*>(shadow + e) = o;
+    }
+  }
+}
+
+hipError_t launch_apply_update_fc(const FcUpdateLaunch& u, hipStream_t stream) {
+  if (u.in < 4 || u.out < 4 || (u.in & 3) || (u.out & 3) || u.c < 1 || u.c > kMaxLearners) return hipErrorInvalidValue;
+  GradTable t;
+  FcFactors f;
+  for (int l = 0; l < kMaxLearners; l++) {
+    t.g[l] = l < u.c ? u.grads[l] : nullptr;
+    t.coef[l] = l < u.c ? u.coef[l] : 0.f;
+    f.x[l] = l < u.c ? u.fx[l] : nullptr;
+    f.dyT[l] = l < u.c ? u.fdyT[l] : nullptr;
+  }
+  const int widest = u.in > u.out ? u.in : u.out;
+  dim3 grid((unsigned)((widest + 1023) / 1024), (unsigned)((u.out + kFcRows - 1) / kFcRows + 1));
+  if (u.shadow_out)
+    hipLaunchKernelGGL((apply_update_fc_kernel<true>), grid, dim3(256), 0, stream, u.theta_in, u.theta_out, u.v, u.shadow_out, u.in, u.out,
+                       u.N, u.NP, u.c, t, f, u.momentum, u.decay);
+  else
+    hipLaunchKernelGGL((apply_update_fc_kernel<false>), grid, dim3(256), 0, stream, u.theta_in, u.theta_out, u.v, u.shadow_out, u.in, u.out,
+                       u.N, u.NP, u.c, t, f, u.momentum, u.decay);
+  return hipGetLastError();
+}
+
 __global__ void fp32_to_bf16_kernel(const float* __restrict__ src, bf16_t* __restrict__ dst, int64_t n) {
   int64_t stride = (int64_t)gridDim.x * blockDim.x;
   for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) dst[i] = f32_to_bf16_rne(src[i]);

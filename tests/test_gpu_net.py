@@ -330,3 +330,77 @@ def test_bad_labels_poison_the_loss_not_memory():
     ctx.calcGradient([0], loss)
     assert torch.isnan(loss).all()
     ctx.destroy()
+
+
+# ---------------------------------------------------------------------------------------------------------------
+# Fully connected weight gradients kept as rank-mu factors (bf16 compute): the product is formed inside applyUpdate.
+FC_NET = {"name": "fcnet", "input": (3, 10, 10), "classes": 8,
+          "layers": [("conv", 8, 3, 1, 1), ("relu",), ("maxpool", 3, 2), ("fc", 72), ("relu",), ("fc", 24), ("relu",), ("fc", 8)]}
+
+
+def _fc_run(flags, K=5):
+    from paper_1511_05950_amd import binding, driver
+    net, lam, n, mu = FC_NET, 6, 2, 5                      # c = 3 gradients per update, mu not a multiple of 8
+    c = lam // n
+    X = wl.images(net, K * c * mu, 70)
+    Y = wl.labels(net, K * c * mu, 71)
+    w0 = wl.init_weights(net, 72, std=0.1)
+    Xd, Yd = torch.from_numpy(X).cuda(), torch.from_numpy(Y).cuda()
+    sl = lambda i, l: slice((i * c + l) * mu, (i * c + l + 1) * mu)
+    sched = wl.uniform_schedule(K, c, 0, 2, 73)
+    ctx = binding.Sasgd(lam, mu, n, 3, net=net, compute="bf16", alpha0=0.05, momentum=0.9, weight_decay=1e-3, init_weights=w0, flags=flags)
+    grads = []
+    hook = lambda i, l, learner: grads.append(ctx.copyGradient(learner)) if i == 0 else None
+    log = driver.run_softsync(ctx, sched, lambda i, l: (Xd[sl(i, l)], Yd[sl(i, l)]), lam, on_gradient=hook)
+    out = dict(w=ctx.copyWeights(), v=ctx.copyMomentum(), grads=grads, log=log, factored=ctx.factoredParams(), w0=w0,
+               X=X, Y=Y, sched=sched, sl=sl, net=net, lam=lam, n=n)
+    ctx.destroy()
+    return out
+
+
+def test_factored_fc_gradient_matches_written_out_gradient_and_oracle():
+    from paper_1511_05950_amd import binding
+    fa = _fc_run(0)
+    fl = _fc_run(binding.FLAG_FLAT_FC_GRADIENT)
+    assert fa["factored"] == 72 * 200 + 24 * 72 + 8 * 24 and fl["factored"] == 0
+    assert fa["log"] == fl["log"]
+    # the first update's gradients are computed on identical weights: the expanded product equals the MFMA result
+    for ga, gb in zip(fa["grads"], fl["grads"]):
+        assert rel(ga, gb) < 1e-5
+    # after K updates with momentum and decay the two runs differ by rounding only
+    assert rel(fa["w"] - fa["w0"], fl["w"] - fl["w0"]) < 2e-3
+    assert rel(fa["v"], fl["v"]) < 5e-3
+    # and both follow the oracle (reduced-precision mode) within the bf16 bound
+    net = fa["net"]
+    ref = protocol.run(cnn.make_callback(net, round_bf16=True), fa["w0"], lambda i, l: (fa["X"][fa["sl"](i, l)], fa["Y"][fa["sl"](i, l)]),
+                       fa["sched"], fa["lam"], fa["n"], 0.05, 0.9, 1e-3)
+    assert fa["log"] == ref["log"]
+    assert rel(fa["w"] - fa["w0"], ref["theta"] - fa["w0"]) < 2e-2
+
+
+def test_factored_and_external_gradients_share_one_update():
+    # one window of c = 2: a learner's gradient (factors) and a gradient pushed from outside (written out)
+    from paper_1511_05950_amd import binding
+    net, mu = FC_NET, 4
+    X = wl.images(net, mu, 74)
+    Y = wl.labels(net, mu, 75)
+    w0 = wl.init_weights(net, 76, std=0.1)
+    P = wl.num_params(net)
+    gext = (np.random.default_rng(77).standard_normal(P) * 1e-2).astype(np.float32)
+    Xd, Yd, Gd = torch.from_numpy(X).cuda(), torch.from_numpy(Y).cuda(), torch.from_numpy(gext).cuda()
+    ctx = binding.Sasgd(2, mu, 1, 2, net=net, compute="bf16", alpha0=0.1, momentum=0.5, weight_decay=1e-2, init_weights=w0)
+    assert ctx.factoredParams() > 0
+    ctx.getMinibatch(0, Xd, Yd)
+    ctx.pullWeights(0, 0)
+    ctx.calcGradient([0])
+    g0 = ctx.copyGradient(0)
+    assert ctx.pushGradient(0) == 0
+    assert ctx.pushGradientExternal(Gd, 0) == 0
+    ctx.sumGradients()
+    ctx.applyUpdate()
+    w1, v1 = ctx.copyWeights(), ctx.copyMomentum()
+    ctx.destroy()
+    coef = 0.1 / 2
+    v_ref = coef * g0.astype(np.float64) + coef * gext.astype(np.float64) + 2 * coef * 1e-2 * w0.astype(np.float64)
+    assert rel(v1, v_ref) < 1e-5
+    assert rel(w1 - w0, -v_ref) < 1e-5
