@@ -77,11 +77,102 @@ __global__ __launch_bounds__(256) void pack_filters_kernel(const bf16_t* __restr
   }
 }
 
+// Layers with a multiple of 32 input and 16 output channels and no re-layout of the first layer: the repack is a
+// transposition ([n][c][tap] -> [n][tap][c] and [c][tap'][n]), done through LDS so that both the reads of the flat
+// filter and the writes of the fragments are contiguous.
+//   forward block  (32 output channels, 16 input channels): reads 32 runs of 16 T elements, writes T fragment blocks
+//   backward block (32 input channels, 16 output channels): reads 16 runs of 32 T elements, writes T fragment blocks
+// Fragment blocks of the zero padding (k beyond the filter) are never written: they keep the zeros the ring was
+// created with.
+struct PackFastJob {
+  int64_t w_off, fwd_off, bwd_off;
+  int C, K, T, KB16, KB16t;          // T = taps; fragment k-blocks per row of the two copies
+  int first_block, fwd_blocks;       // workgroups [first_block, next job's first_block): forward ones first
+};
+struct PackFastTable {
+  PackFastJob job[kMaxPackJobs];
+  int count;
+};
+constexpr int kPackMaxTaps = 25;
+
+__global__ __launch_bounds__(256) void pack_filters_lds_kernel(const bf16_t* __restrict__ flat, bf16_t* __restrict__ packed, PackFastTable t) {
+  __shared__ __attribute__((aligned(16))) bf16_t tile[32 * 16 * kPackMaxTaps];
+  int li = 0;
+  while (li + 1 < t.count && (int)blockIdx.x >= t.job[li + 1].first_block) li++;
+  const PackFastJob& jb = t.job[li];
+  const int b = blockIdx.x - jb.first_block;
+  const int T = jb.T, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int row = lane & 31, h = lane >> 5;
+  const bf16_t* W = flat + jb.w_off;
+  if (b < jb.fwd_blocks) {
+    const int groups = jb.C / 16, rb = b / groups, cg = b - rb * groups;
+    const int run = 16 * T;                                  // contiguous elements of one output channel
+    for (int ch = tid; ch < 64 * T; ch += 256) {             // 16-byte pieces: 2 T per run
+      const int r = ch / (2 * T), rem = (ch - r * 2 * T) * 8, n = 32 * rb + r;
+      uint4 q = make_uint4(0u, 0u, 0u, 0u);
+      if (n < jb.K) q = *reinterpret_cast<const uint4*>(W + ((int64_t)n * jb.C + 16 * cg) * T + rem);
+      *reinterpret_cast<uint4*>(tile + r * run + rem) = q;
+    }
+    __syncthreads();
+    for (int tap = wave; tap < T; tap += 4) {
+      union { bf16_t e[8]; uint4 q; } o;
+#pragma unroll
+      for (int j = 0; j < 8; j++) o.e[j] = tile[row * run + (8 * h + j) * T + tap];
+      const int kb = tap * groups + cg;
+      *reinterpret_cast<uint4*>(packed + jb.fwd_off + ((int64_t)rb * jb.KB16 + kb) * 512 + lane * 8) = o.q;
+    }
+  } else {
+    const int bb = b - jb.fwd_blocks;
+    const int groups = jb.K / 16, cb = bb / groups, ng = bb - cb * groups;
+    const int run = 32 * T;                                  // contiguous elements of 32 input channels of one filter
+    for (int ch = tid; ch < 64 * T; ch += 256) {             // 16-byte pieces: 4 T per run (the 32 channels all exist)
+      const int nn = ch / (4 * T), rem = (ch - nn * 4 * T) * 8;
+      *reinterpret_cast<uint4*>(tile + nn * run + rem) =
+          *reinterpret_cast<const uint4*>(W + ((int64_t)(16 * ng + nn) * jb.C + 32 * cb) * T + rem);
+    }
+    __syncthreads();
+    for (int tap = wave; tap < T; tap += 4) {                // tap' of the flipped filter
+      union { bf16_t e[8]; uint4 q; } o;
+#pragma unroll
+      for (int j = 0; j < 8; j++) o.e[j] = tile[(8 * h + j) * run + row * T + (T - 1 - tap)];
+      const int kb = tap * groups + ng;
+      *reinterpret_cast<uint4*>(packed + jb.bwd_off + ((int64_t)cb * jb.KB16t + kb) * 512 + lane * 8) = o.q;
+    }
+  }
+}
+
 hipError_t launch_pack_filters(const void* flat, void* packed, const PackTable& t, hipStream_t s) {
   if (t.count == 0 || t.total == 0) return hipSuccess;
-  const int64_t chunks = t.total / 8;
-  int blocks = (int)((chunks + 255) / 256 < 8192 ? (chunks + 255) / 256 : 8192);
-  hipLaunchKernelGGL(pack_filters_kernel, dim3(blocks), dim3(256), 0, s, (const bf16_t*)flat, (bf16_t*)packed, t);
+  PackTable slow;
+  PackFastTable fast;
+  slow.count = 0; slow.total = 0;
+  fast.count = 0;
+  int blocks_fast = 0;
+  for (int k = 0; k < t.count; k++) {
+    const PackJob& jb = t.job[k];
+    const VConv& v = jb.v;
+    const int T = v.ks * v.ks;
+    if (v.s2d == 1 && v.C == v.Creal && v.ks == v.ksr && v.C % 32 == 0 && v.K % 16 == 0 && T <= kPackMaxTaps && jb.Kpt > 0 && jb.w_off % 8 == 0) {
+      PackFastJob& f = fast.job[fast.count++];
+      f.w_off = jb.w_off; f.fwd_off = jb.fwd_off; f.bwd_off = jb.bwd_off;
+      f.C = v.C; f.K = v.K; f.T = T; f.KB16 = jb.Kp / 16; f.KB16t = jb.Kpt / 16;
+      f.first_block = blocks_fast;
+      f.fwd_blocks = ((v.K + 31) / 32) * (v.C / 16);
+      blocks_fast += f.fwd_blocks + ((v.C + 31) / 32) * (v.K / 16);
+    } else {
+      PackJob& o = slow.job[slow.count++];
+      o = jb;
+      o.start = slow.total;
+      slow.total += (int64_t)((v.K + 31) & ~31) * jb.Kp + (jb.Kpt > 0 ? (int64_t)((v.C + 31) & ~31) * jb.Kpt : 0);
+    }
+  }
+  if (slow.count > 0) {
+    const int64_t chunks = slow.total / 8;
+    int blocks = (int)((chunks + 255) / 256 < 8192 ? (chunks + 255) / 256 : 8192);
+    hipLaunchKernelGGL(pack_filters_kernel, dim3(blocks), dim3(256), 0, s, (const bf16_t*)flat, (bf16_t*)packed, slow);
+  }
+  if (fast.count > 0)
+    hipLaunchKernelGGL(pack_filters_lds_kernel, dim3((unsigned)blocks_fast), dim3(256), 0, s, (const bf16_t*)flat, (bf16_t*)packed, fast);
   return hipGetLastError();
 }
 
