@@ -157,6 +157,32 @@ def test_config2_200_updates():
     assert rel(v, ref["v"]) < 1e-3
 
 
+@pytest.mark.parametrize("mode", ["per_gradient", "mean_staleness"])
+def test_config3_first_updates(mode):
+    """BASELINE config 3 as bench.py runs it (CIFAR-shaped, bf16 compute, lambda = 18 learners of mu = 128 in one batched
+    call, 1-softsync: c = 18 gradients averaged per update, staleness in {0, 1, 2}), its first two updates, in both
+    readings of its learning rate (per gradient, and one rate per update from the mean staleness)."""
+    from paper_1511_05950_amd import binding, driver
+    cfgd = wl.config(3)
+    net, lam, mu, n, c = cfgd["net"], cfgd["lam"], cfgd["mu"], cfgd["n"], cfgd["c"]
+    K = 2
+    sched = cfgd["schedule"]()[:K]
+    X, Y, w0 = wl.images(net, K * c * mu, 7), wl.labels(net, K * c * mu, 8), cfgd["weights"]()
+    Xd, Yd = torch.from_numpy(X).cuda(), torch.from_numpy(Y).cuda()
+    sl = lambda i, l: slice((i * c + l) * mu, (i * c + l + 1) * mu)
+    ctx = binding.Sasgd(lam, mu, n, 3, net="cifar3", compute="bf16", lr_mode=mode, alpha0=cfgd["alpha0"], momentum=cfgd["momentum"],
+                        weight_decay=cfgd["weight_decay"], init_weights=w0)
+    log = driver.run_softsync(ctx, sched, lambda i, l: (Xd[sl(i, l)], Yd[sl(i, l)]), lam)
+    w, v = ctx.copyWeights(), ctx.copyMomentum()
+    ctx.destroy()
+    ref = protocol.run(cnn.make_callback(net, round_bf16=True), w0, lambda i, l: (X[sl(i, l)], Y[sl(i, l)]), sched, lam, n,
+                       cfgd["alpha0"], cfgd["momentum"], cfgd["weight_decay"], mode)
+    assert log == ref["log"]
+    assert [t for (_, _, _, _, t) in log[:c]] == [0] * c      # every first-update gradient reads theta_0
+    assert rel(w - w0, ref["theta"] - w0) < 2e-2
+    assert rel(v, ref["v"]) < 2e-2
+
+
 def test_batched_driver_matches_plain_driver():
     # merging calcGradient calls across updates must not change versions, staleness or (up to summation order) weights
     from paper_1511_05950_amd import binding, driver
