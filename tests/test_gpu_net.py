@@ -420,6 +420,11 @@ def test_factored_and_external_gradients_share_one_update():
     ctx.pullWeights(0, 0)
     ctx.calcGradient([0])
     g0 = ctx.copyGradient(0)
+    # an evaluation pass of the same learner on other images before the push must not disturb the saved factors
+    X2 = torch.from_numpy(wl.images(net, mu, 78)).cuda()
+    ctx.getMinibatch(0, X2, Yd)
+    ctx.pullWeights(0, 0)
+    ctx.evaluate([0], None, torch.zeros(mu, device="cuda", dtype=torch.int32))
     assert ctx.pushGradient(0) == 0
     assert ctx.pushGradientExternal(Gd, 0) == 0
     ctx.sumGradients()
