@@ -1000,32 +1000,52 @@ __global__ __launch_bounds__(256) void igemm_wgrad_kernel(PtrTab ws, PtrTab grad
 // One workgroup per output channel n: the row of partial sums is added in split order into LDS (coalesced reads),
 // then written to the flat gradient in ITS order (coalesced writes), the im2col column of each filter element
 // being looked up on the way.
-__global__ __launch_bounds__(256) void wgrad_finish_kernel(PtrTab ws, PtrTab grads, IGemm g, VConv v, int64_t w_off, int64_t b_off) {
-  extern __shared__ float row[];                 // kcols + 1 sums
+__global__ __launch_bounds__(256) void wgrad_finish_kernel(PtrTab ws, PtrTab grads, IGemm g, VConv v, int64_t w_off, int64_t b_off,
+                                                           int cgroup) {
+  extern __shared__ float row[];                 // sums of this workgroup's columns
   const int z = blockIdx.z, n = blockIdx.x;
   const int kcols = g.Kchunks * 8, ldk = kcols + 8;
   const float* part = reinterpret_cast<const float*>((const char*)ws.p[z] + g.scratch_off) + (int64_t)n * ldk;
   const int64_t split_stride = (int64_t)g.Ncols * ldk;
-  for (int k = threadIdx.x; k <= kcols; k += 256) {
+  float* dw = (float*)grads.p[z] + w_off + (int64_t)n * v.Creal * v.ksr * v.ksr;
+  if (blockIdx.y == 0 && threadIdx.x == 0) {     // bias gradient: the extra im2col column
+    float acc = 0.f;
+    for (int sp = 0; sp < g.splits; sp++) acc += part[sp * split_stride + kcols];
+    ((float*)grads.p[z] + b_off)[n] = acc;
+  }
+  if (v.s2d == 1) {
+    // channels [c_lo, c_hi) of this filter, all taps: columns tap * C + c are read tap by tap (contiguous runs), the
+    // run [c_lo * T, c_hi * T) of the flat gradient is written in its own order
+    const int T = v.ks * v.ks;
+    const int c_lo = blockIdx.y * cgroup, c_hi = min(v.Creal, c_lo + cgroup), cw = c_hi - c_lo;
+    if (cw <= 0) return;
+    for (int idx = threadIdx.x; idx < T * cw; idx += 256) {
+      const int tap = idx / cw, cc = idx - tap * cw;
+      const int k = tap * g.C + c_lo + cc;
+      float acc = 0.f;
+      for (int sp = 0; sp < g.splits; sp++) acc += part[sp * split_stride + k];
+      row[idx] = acc;
+    }
+    __syncthreads();
+    for (int j = threadIdx.x; j < T * cw; j += 256) {
+      const int cc = j / T, tap = j - cc * T;
+      dw[(int64_t)c_lo * T + j] = row[tap * cw + cc];
+    }
+    return;
+  }
+  // first layer seen through a space-to-depth input: whole row, general column lookup
+  for (int k = threadIdx.x; k < kcols; k += 256) {
     float acc = 0.f;
     for (int sp = 0; sp < g.splits; sp++) acc += part[sp * split_stride + k];
     row[k] = acc;
   }
   __syncthreads();
-  float* dw = (float*)grads.p[z] + w_off + (int64_t)n * v.Creal * v.ksr * v.ksr;
-  if (threadIdx.x == 0) ((float*)grads.p[z] + b_off)[n] = row[kcols];
   const int per_n = v.Creal * v.ksr * v.ksr;
   for (int j = threadIdx.x; j < per_n; j += 256) {
     const int kw = j % v.ksr, t = j / v.ksr;
     const int kh = t % v.ksr, c = t / v.ksr;
-    int tap, cp;
-    if (v.s2d == 1) {
-      tap = kh * v.ks + kw;
-      cp = c;
-    } else {
-      tap = (kh / v.s2d) * v.ks + kw / v.s2d;
-      cp = ((kh % v.s2d) * v.s2d + kw % v.s2d) * v.Creal + c;
-    }
+    const int tap = (kh / v.s2d) * v.ks + kw / v.s2d;
+    const int cp = ((kh % v.s2d) * v.s2d + kw % v.s2d) * v.Creal + c;
     dw[j] = row[tap * g.C + cp];
   }
 }
@@ -1052,9 +1072,21 @@ hipError_t launch_igemm_wgrad(const PtrTab& ws, const PtrTab& grads, const IGemm
     SASGD_WGRAD(128, 128, 64, 64);
   }
 #undef SASGD_WGRAD
-  if (g.splits > 1)
-    hipLaunchKernelGGL(wgrad_finish_kernel, dim3((unsigned)g.Ncols, 1, (unsigned)count), dim3(256), (size_t)cols * sizeof(float), s, ws,
-                       grads, g, v, w_off, b_off);
+  if (g.splits > 1) {
+    // enough workgroups to keep the chip busy: the channels of a filter are divided among several of them
+    int groups = 1, cgroup = v.Creal;
+    size_t lds = (size_t)cols * sizeof(float);
+    if (v.s2d == 1) {
+      groups = (int)((1536 + (int64_t)g.Ncols * count - 1) / ((int64_t)g.Ncols * count));
+      if (groups > v.Creal / 8) groups = v.Creal / 8;
+      if (groups < 1) groups = 1;
+      cgroup = (v.Creal + groups - 1) / groups;
+      groups = (v.Creal + cgroup - 1) / cgroup;
+      lds = (size_t)cgroup * v.ks * v.ks * sizeof(float);
+    }
+    hipLaunchKernelGGL(wgrad_finish_kernel, dim3((unsigned)g.Ncols, (unsigned)groups, (unsigned)count), dim3(256), lds, s, ws, grads, g, v,
+                       w_off, b_off, cgroup);
+  }
   return hipGetLastError();
 }
 
