@@ -186,7 +186,7 @@ struct FcFactors {
   const bf16_t* dyT[kMaxLearners];   // [out][NP]
 };
 
-constexpr int kFcRows = 8;           // output units per workgroup
+constexpr int kFcRows = 4;           // output units per workgroup (2, 8 and 16 measured slower at config 4)
 
 template <bool SHADOW>
 __global__ __launch_bounds__(256) void apply_update_fc_kernel(const float* theta_in, float* theta_out, float* v, bf16_t* shadow, int in,
