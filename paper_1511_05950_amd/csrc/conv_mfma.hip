@@ -759,7 +759,7 @@ hipError_t launch_igemm(const PtrTab& ws, const CPtrTab& wts, const IGemm& g, co
 // two conditional wraps (possible when 32 / OW + 1 <= OH); otherwise it is decoded from the row index every step.
 template <int BMG, int BNG, int WMG, int WNG, bool INCR>
 __global__ __launch_bounds__(256) void igemm_wgrad_kernel(PtrTab ws, PtrTab grads, IGemm g, VConv v, size_t dy_off, int64_t w_off,
-                                                          int64_t b_off) {
+                                                          int64_t b_off, int partial) {
   constexpr int WAVES_NG = BNG / WNG;                  // four wavefronts: (BMG / WMG) x (BNG / WNG)
   constexpr int TM = WMG / 32, TN = WNG / 32;
   constexpr int LDT_A = BMG + 32 - (BMG == 32 ? 32 : 0);
@@ -939,7 +939,7 @@ __global__ __launch_bounds__(256) void igemm_wgrad_kernel(PtrTab ws, PtrTab grad
   if (ms < msteps) step(0, false, false);
 
   const int kcols = g.Kchunks * 8;
-  if (g.splits > 1) {   // fp32 partial [split][n][kcols + 8]; wgrad_finish_kernel adds and scatters
+  if (partial) {   // fp32 partial [split][n][kcols + 8]; wgrad_finish_kernel adds and writes the flat gradient in its order
     const int ldk = kcols + 8;
     float* part = reinterpret_cast<float*>((char*)ws.p[z] + g.scratch_off) + (int64_t)sp * g.Ncols * ldk;
 #pragma unroll
@@ -1054,12 +1054,19 @@ hipError_t launch_igemm_wgrad(const PtrTab& ws, const PtrTab& grads, const IGemm
                               int64_t b_off, int count, hipStream_t s) {
   if (g.C % 8 || g.Ncols % 8 || g.splits < 1) return hipErrorInvalidValue;
   const int cols = g.Kchunks * 8 + 1;          // im2col columns plus the bias column
-  if (g.splits > 1 && (size_t)cols * sizeof(float) > 60 * 1024) return hipErrorInvalidValue;   // finish kernel keeps one row in LDS
+  const bool row_fits = v.s2d == 1 || (size_t)cols * sizeof(float) <= 60 * 1024;   // space-to-depth layers: the second pass keeps a whole row in LDS
+  if (g.splits > 1 && !row_fits) return hipErrorInvalidValue;
   const bool incr = BK / g.OW + 1 <= g.OH;      // one wrap of oh per step at most
+  // A convolution's tile holds one tap of many channels, the flat gradient wants all taps of one channel together:
+  // written straight from the tile every 4-byte element lands alone and every cache line is completed by as many
+  // workgroups as the window has taps (measured: 65-125 us per AlexNet layer at 18 learners).  So convolutions
+  // always go through the partial buffer and the second pass, which reads and writes whole lines (28-51 us).
+  const bool conv = v.ks > 1 || v.s2d > 1;
+  const int partial = (g.splits > 1 || (conv && row_fits)) ? 1 : 0;
 #define SASGD_WGRAD(BMG, BNG, WMG, WNG)                                                                                          \
   do {                                                                                                                           \
-    if (incr) hipLaunchKernelGGL((igemm_wgrad_kernel<BMG, BNG, WMG, WNG, true>), grid, dim3(256), 0, s, ws, grads, g, v, dy_off, w_off, b_off); \
-    else hipLaunchKernelGGL((igemm_wgrad_kernel<BMG, BNG, WMG, WNG, false>), grid, dim3(256), 0, s, ws, grads, g, v, dy_off, w_off, b_off);    \
+    if (incr) hipLaunchKernelGGL((igemm_wgrad_kernel<BMG, BNG, WMG, WNG, true>), grid, dim3(256), 0, s, ws, grads, g, v, dy_off, w_off, b_off, partial); \
+    else hipLaunchKernelGGL((igemm_wgrad_kernel<BMG, BNG, WMG, WNG, false>), grid, dim3(256), 0, s, ws, grads, g, v, dy_off, w_off, b_off, partial);    \
   } while (0)
   if (g.Ncols <= 32) {
     dim3 grid(1, (unsigned)((cols + 127) / 128), (unsigned)(count * g.splits));
@@ -1072,7 +1079,7 @@ hipError_t launch_igemm_wgrad(const PtrTab& ws, const PtrTab& grads, const IGemm
     SASGD_WGRAD(128, 128, 64, 64);
   }
 #undef SASGD_WGRAD
-  if (g.splits > 1) {
+  if (partial) {
     // enough workgroups to keep the chip busy: the channels of a filter are divided among several of them
     int groups = 1, cgroup = v.Creal;
     size_t lds = (size_t)cols * sizeof(float);
@@ -1081,6 +1088,8 @@ hipError_t launch_igemm_wgrad(const PtrTab& ws, const PtrTab& grads, const IGemm
       if (groups > v.Creal / 8) groups = v.Creal / 8;
       if (groups < 1) groups = 1;
       cgroup = (v.Creal + groups - 1) / groups;
+      const int cap = 15360 / (v.ks * v.ks);       // 60 KiB of sums per workgroup
+      if (cgroup > cap) cgroup = cap < 1 ? 1 : cap;
       groups = (v.Creal + cgroup - 1) / cgroup;
       lds = (size_t)cgroup * v.ks * v.ks * sizeof(float);
     }
