@@ -618,6 +618,62 @@ __global__ __launch_bounds__(NT, (WM * WN > 64 * 64 ? 2 : 1)) void igemm_frag_ke
   bf16_t* out = (bf16_t*)ws.p[z] + ep.out_off;
   const bf16_t* mask = (const bf16_t*)ws.p[z] + ep.mask_off;
   const bf16_t* bias = (const bf16_t*)wts.p[z] + ep.bias_off;
+  if (!ep.out_f32) {
+    // bf16 output: a lane holds single elements of 16 different rows, which written straight out are 2-byte stores.
+    // Each wavefront turns its 32-row blocks around in its own piece of LDS (the tiles there are no longer needed) and
+    // writes 16 bytes per lane, 8 lanes per row; the ReLU mask of the input gradient is read the same way.
+    constexpr int LDE = WN + 8;                          // row stride of the staging piece (elements)
+    static_assert(4 * 32 * LDE <= 2 * A_ELEMS || NT != 256, "staging piece fits the tile buffers");
+    __syncthreads();                                     // every wavefront has finished reading the last tile
+    bf16_t* stage = lds + wave * (32 * LDE);
+    constexpr int CPRW = WN / 8;                         // 16-byte chunks per row of the wavefront's tile
+    constexpr int RPI = 64 / CPRW;                       // rows covered by one 64-lane pass
+    const int rrow = lane / CPRW, rchunk = lane % CPRW;
+#pragma unroll
+    for (int i = 0; i < TM; i++) {
+#pragma unroll
+      for (int j = 0; j < TN; j++) {
+        const int n = n0 + wn0 + 32 * j + (lane & 31);
+        const float bv = (ep.has_bias && n < g.Ncols) ? bf2f(bias[n]) : 0.f;
+#pragma unroll
+        for (int r = 0; r < 16; r++) {
+          float v = acc[i][j][r] + bv;
+          if (ep.relu) v = fmaxf(v, 0.f);
+          stage[(8 * (r >> 2) + 4 * (lane >> 5) + (r & 3)) * LDE + 32 * j + (lane & 31)] = f2bf(v);
+        }
+      }
+      // LDS operations of one wavefront complete in order, so its reads below see its writes above; the compiler is
+      // told not to move LDS accesses across the two phases
+      __builtin_amdgcn_wave_barrier();
+      asm volatile("" ::: "memory");
+#pragma unroll
+      for (int it = 0; it < 32 / RPI; it++) {
+        const int row = rrow + RPI * it;
+        const int m = m0 + wm0 + 32 * i + row, n = n0 + wn0 + rchunk * 8;
+        uint4 q = *reinterpret_cast<const uint4*>(stage + row * LDE + rchunk * 8);
+        if (m < g.M && n < g.Ncols) {
+          const int64_t o = (int64_t)m * g.Ncols + n;
+          if (ep.use_mask) {
+            const uint4 mk = *reinterpret_cast<const uint4*>(mask + o);
+            const uint32_t mw[4] = {mk.x, mk.y, mk.z, mk.w};
+            uint32_t qw[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+            for (int w = 0; w < 4; w++) {                // keep a 16-bit half where the forward value is positive
+              const uint32_t lo = mw[w] & 0xffffu, hi = mw[w] >> 16;
+              const uint32_t keep = (((lo & 0x8000u) == 0 && (lo & 0x7fffu) != 0) ? 0x0000ffffu : 0u) |
+                                    (((hi & 0x8000u) == 0 && (hi & 0x7fffu) != 0) ? 0xffff0000u : 0u);
+              qw[w] &= keep;
+            }
+            q = make_uint4(qw[0], qw[1], qw[2], qw[3]);
+          }
+          *reinterpret_cast<uint4*>(out + o) = q;
+        }
+      }
+      __builtin_amdgcn_wave_barrier();
+      asm volatile("" ::: "memory");
+    }
+    return;
+  }
 #pragma unroll
   for (int j = 0; j < TN; j++) {
     const int n = n0 + wn0 + 32 * j + (lane & 31);
@@ -633,8 +689,7 @@ __global__ __launch_bounds__(NT, (WM * WN > 64 * 64 ? 2 : 1)) void igemm_frag_ke
         if (ep.relu) v = fmaxf(v, 0.f);
         const int64_t o = (int64_t)m * g.Ncols + n;
         if (ep.use_mask && !(bf2f(mask[o]) > 0.f)) v = 0.f;
-        if (ep.out_f32) reinterpret_cast<float*>(out)[o] = v;
-        else out[o] = f2bf(v);
+        reinterpret_cast<float*>(out)[o] = v;
       }
   }
 }
