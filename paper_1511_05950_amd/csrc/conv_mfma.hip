@@ -1088,36 +1088,29 @@ __global__ __launch_bounds__(256) void wgrad_finish_kernel(PtrTab ws, PtrTab gra
     }
     return;
   }
-  // first layer seen through a space-to-depth input: whole row, general column lookup
-  for (int k = threadIdx.x; k < kcols; k += 256) {
-    float acc = 0.f;
-    for (int sp = 0; sp < g.splits; sp++) acc += part[sp * split_stride + k];
-    row[k] = acc;
-  }
-  __syncthreads();
-  const int per_n = v.Creal * v.ksr * v.ksr;
-  for (int j = threadIdx.x; j < per_n; j += 256) {
-    const int kw = j % v.ksr, t = j / v.ksr;
-    const int kh = t % v.ksr, c = t / v.ksr;
-    const int tap = (kh / v.s2d) * v.ks + kw / v.s2d;
-    const int cp = ((kh % v.s2d) * v.s2d + kw % v.s2d) * v.Creal + c;
-    dw[j] = row[tap * g.C + cp];
-  }
+  // first layer seen through a space-to-depth input (a small filter): one thread per im2col column, blockIdx.y
+  // selects a run of 256 columns; the column's place in the flat filter is looked up and written on its own
+  const int k = blockIdx.y * 256 + threadIdx.x;
+  if (k >= kcols) return;
+  const int tap = k / g.C, cp = k - tap * g.C;
+  const int64_t dst = filter_src(v, 0, tap, cp);          // position inside one filter, or -1 for padding
+  if (dst < 0) return;
+  float acc = 0.f;
+  for (int sp = 0; sp < g.splits; sp++) acc += part[sp * split_stride + k];
+  dw[dst] = acc;
 }
 
 hipError_t launch_igemm_wgrad(const PtrTab& ws, const PtrTab& grads, const IGemm& g, const VConv& v, size_t dy_off, int64_t w_off,
                               int64_t b_off, int count, hipStream_t s) {
   if (g.C % 8 || g.Ncols % 8 || g.splits < 1) return hipErrorInvalidValue;
   const int cols = g.Kchunks * 8 + 1;          // im2col columns plus the bias column
-  const bool row_fits = v.s2d == 1 || (size_t)cols * sizeof(float) <= 60 * 1024;   // space-to-depth layers: the second pass keeps a whole row in LDS
-  if (g.splits > 1 && !row_fits) return hipErrorInvalidValue;
   const bool incr = BK / g.OW + 1 <= g.OH;      // one wrap of oh per step at most
   // A convolution's tile holds one tap of many channels, the flat gradient wants all taps of one channel together:
   // written straight from the tile every 4-byte element lands alone and every cache line is completed by as many
   // workgroups as the window has taps (measured: 65-125 us per AlexNet layer at 18 learners).  So convolutions
   // always go through the partial buffer and the second pass, which reads and writes whole lines (28-51 us).
   const bool conv = v.ks > 1 || v.s2d > 1;
-  const int partial = (g.splits > 1 || (conv && row_fits)) ? 1 : 0;
+  const int partial = (g.splits > 1 || conv) ? 1 : 0;
 #define SASGD_WGRAD(BMG, BNG, WMG, WNG)                                                                                          \
   do {                                                                                                                           \
     if (incr) hipLaunchKernelGGL((igemm_wgrad_kernel<BMG, BNG, WMG, WNG, true>), grid, dim3(256), 0, s, ws, grads, g, v, dy_off, w_off, b_off, partial); \
@@ -1136,8 +1129,8 @@ hipError_t launch_igemm_wgrad(const PtrTab& ws, const PtrTab& grads, const IGemm
 #undef SASGD_WGRAD
   if (partial) {
     // enough workgroups to keep the chip busy: the channels of a filter are divided among several of them
-    int groups = 1, cgroup = v.Creal;
-    size_t lds = (size_t)cols * sizeof(float);
+    int groups = (cols + 254) / 256, cgroup = v.Creal;   // space-to-depth first layer: runs of 256 columns, no LDS
+    size_t lds = 0;
     if (v.s2d == 1) {
       groups = (int)((1536 + (int64_t)g.Ncols * count - 1) / ((int64_t)g.Ncols * count));
       if (groups > v.Creal / 8) groups = v.Creal / 8;

@@ -460,7 +460,6 @@ hipError_t net_calc_gradient(Net* net, const int* learners, const LearnerBind* b
             const int64_t tiles = (int64_t)((gw.Ncols + 127) / 128) * ((gw.Kchunks * 8 + 1 + 127) / 128);
             gw.scratch_off = net->scratch_off;
             gw.splits = choose_splits(tiles, count, (gw.M + 31) / 32, (size_t)gw.Ncols * (gw.Kchunks * 8 + 8) * 4, net->scratch_bytes);
-            if (op.vc.s2d > 1 && (size_t)(gw.Kchunks * 8 + 1) * 4 > 60 * 1024) gw.splits = 1;   // that second pass keeps a whole filter row in LDS
           }
           TRY(launch_igemm_wgrad(ws, grads, gw, op.vc, dy, op.w_off, op.b_off, count, stream));
           if (need_dx) {
