@@ -354,6 +354,94 @@ __global__ __launch_bounds__(256) void pool_bwd_vec8_kernel(PtrTab ws, size_t dy
   }
 }
 
+// 3 x 3 windows at stride 2 (every pooling layer of the two reference networks): one lane owns 8 channels of a 2 x 2
+// block of the input, rows 2a, 2a+1 and columns 2b, 2b+1.  Only the four windows (a-1 | a, b-1 | b) reach into the
+// block, so they are read once for the four results instead of once per covered element (nine reads per block).
+template <bool MAX>
+__global__ __launch_bounds__(256) void pool_bwd_3x3s2_kernel(PtrTab ws, size_t dy_off, size_t dx_off, size_t arg_byte_off, PoolShape sh,
+                                                             int use_mask, size_t mask_off) {
+  const bf16_t* dy = (const bf16_t*)ws.p[blockIdx.z] + dy_off;
+  bf16_t* dx = (bf16_t*)ws.p[blockIdx.z] + dx_off;
+  const bf16_t* mask = (const bf16_t*)ws.p[blockIdx.z] + mask_off;
+  const uint8_t* arg = (const uint8_t*)ws.p[blockIdx.z] + arg_byte_off;
+  const int C8 = sh.C / 8, HB = (sh.H + 1) / 2, WB = (sh.W + 1) / 2;
+  const uint32_t total = (uint32_t)sh.N * HB * WB * C8;
+  for (uint32_t i = blockIdx.x * 256 + threadIdx.x; i < total; i += gridDim.x * 256) {
+    uint32_t r = i;
+    const int c8 = (int)(r % (uint32_t)C8);
+    r /= (uint32_t)C8;
+    const int b = (int)(r % (uint32_t)WB);
+    r /= (uint32_t)WB;
+    const int a = (int)(r % (uint32_t)HB);
+    const int n = (int)(r / (uint32_t)HB);
+    float acc[4][8];                                    // [2 * dh + dw][channel]
+#pragma unroll
+    for (int q = 0; q < 4; q++)
+#pragma unroll
+      for (int e = 0; e < 8; e++) acc[q][e] = 0.f;
+#pragma unroll
+    for (int wh = 0; wh < 2; wh++) {
+      const int oh = a - 1 + wh;
+      if (oh < 0 || oh >= sh.OH) continue;
+#pragma unroll
+      for (int ww = 0; ww < 2; ww++) {
+        const int ow = b - 1 + ww;
+        if (ow < 0 || ow >= sh.OW) continue;
+        const int64_t o = ((((int64_t)n * sh.OH + oh) * sh.OW + ow) * C8 + c8) * 8;
+        bf8 d;
+        d.v = *reinterpret_cast<const uint4*>(dy + o);
+        uint2 ar = make_uint2(0u, 0u);
+        if (MAX) ar = *reinterpret_cast<const uint2*>(arg + o);
+        float inv = 1.f;
+        if (!MAX) {
+          const int ch = min(oh * 2 + 3, sh.H) - oh * 2, cw = min(ow * 2 + 3, sh.W) - ow * 2;
+          inv = 1.f / (float)(ch * cw);
+        }
+        // window (oh, ow) starts at row 2 oh, column 2 ow: block row dh sits at window row 2 (a - oh) + dh
+#pragma unroll
+        for (int dh = 0; dh < 2; dh++) {
+          const int wr = 2 * (a - oh) + dh;             // 2, 3 for the window above (only 2 is inside), 0, 1 for the own one
+          if (wr > 2) continue;
+#pragma unroll
+          for (int dw = 0; dw < 2; dw++) {
+            const int wc = 2 * (b - ow) + dw;
+            if (wc > 2) continue;
+            const uint32_t pos = (uint32_t)(wr * 3 + wc);
+#pragma unroll
+            for (int e = 0; e < 8; e++) {
+              if (MAX) {
+                const uint32_t ae = ((e < 4 ? ar.x : ar.y) >> (8 * (e & 3))) & 0xffu;
+                if (ae == pos) acc[2 * dh + dw][e] += d.get(e);
+              } else {
+                acc[2 * dh + dw][e] += d.get(e) * inv;
+              }
+            }
+          }
+        }
+      }
+    }
+#pragma unroll
+    for (int dh = 0; dh < 2; dh++) {
+      const int ih = 2 * a + dh;
+      if (ih >= sh.H) continue;
+#pragma unroll
+      for (int dw = 0; dw < 2; dw++) {
+        const int iw = 2 * b + dw;
+        if (iw >= sh.W) continue;
+        const int64_t xo = ((((int64_t)n * sh.H + ih) * sh.W + iw) * C8 + c8) * 8;
+        if (use_mask) {
+          bf8 mk;
+          mk.v = *reinterpret_cast<const uint4*>(mask + xo);
+#pragma unroll
+          for (int e = 0; e < 8; e++)
+            if (!(mk.get(e) > 0.f)) acc[2 * dh + dw][e] = 0.f;
+        }
+        *reinterpret_cast<uint4*>(dx + xo) = pack8(acc[2 * dh + dw]);
+      }
+    }
+  }
+}
+
 hipError_t launch_pool_fwd(bool is_bf16, bool is_max, const PtrTab& ws, size_t x_off, size_t y_off, size_t arg_byte_off,
                            const PoolShape& sh, bool relu, int count, hipStream_t s) {
   dim3 g = grid_for((int64_t)sh.N * sh.OH * sh.OW * sh.C, count);
@@ -379,6 +467,12 @@ hipError_t launch_pool_bwd(bool is_bf16, bool is_max, const PtrTab& ws, size_t d
   dim3 g = grid_for((int64_t)sh.N * sh.H * sh.W * sh.C, count);
   int um = use_mask ? 1 : 0;
   if (is_bf16 && sh.C % 8 == 0 && dy_off % 8 == 0 && dx_off % 8 == 0 && arg_byte_off % 8 == 0 && mask_off % 8 == 0) {
+    if (sh.ks == 3 && sh.stride == 2) {
+      dim3 gb = grid_for((int64_t)sh.N * ((sh.H + 1) / 2) * ((sh.W + 1) / 2) * (sh.C / 8), count, 16384);
+      if (is_max) hipLaunchKernelGGL((pool_bwd_3x3s2_kernel<true>), gb, dim3(256), 0, s, ws, dy_off, dx_off, arg_byte_off, sh, um, mask_off);
+      else hipLaunchKernelGGL((pool_bwd_3x3s2_kernel<false>), gb, dim3(256), 0, s, ws, dy_off, dx_off, arg_byte_off, sh, um, mask_off);
+      return hipGetLastError();
+    }
     dim3 gv = grid_for((int64_t)sh.N * sh.H * sh.W * (sh.C / 8), count, 16384);
     if (is_max) hipLaunchKernelGGL((pool_bwd_vec8_kernel<true>), gv, dim3(256), 0, s, ws, dy_off, dx_off, arg_byte_off, sh, um, mask_off);
     else hipLaunchKernelGGL((pool_bwd_vec8_kernel<false>), gv, dim3(256), 0, s, ws, dy_off, dx_off, arg_byte_off, sh, um, mask_off);
