@@ -415,11 +415,11 @@ int sasgd_applyUpdate(sasgd_ctx* ctx, int64_t* out_new_timestamp) {
   }
   // Layers whose gradients are kept as factors get their own launch; the stretches of the flat vector between them
   // go through the streaming kernel.
-  FactoredLayer fl[16];
-  const int nfl = ctx->net ? net_factored_layers(ctx->net, fl, 16) : 0;
+  FactoredLayer fl[kMaxFactoredLayers];
+  const int nfl = ctx->net ? net_factored_layers(ctx->net, fl, kMaxFactoredLayers) : 0;
   prof_begin(ctx, 1);
   hipError_t e = hipSuccess;
-  if (nfl == 0 || nfl > 16) {
+  if (nfl == 0) {
     e = launch_apply_update(u, ctx->stream);
   } else {
     auto flat_range = [&](int64_t begin, int64_t end) {
@@ -497,9 +497,9 @@ int sasgd_factoredParams(sasgd_ctx* ctx, int64_t* out) {
   if (!ctx || !out) return SASGD_EINVAL;
   *out = 0;
   if (ctx->net) {
-    FactoredLayer fl[16];
-    const int nfl = net_factored_layers(ctx->net, fl, 16);
-    for (int k = 0; k < nfl && k < 16; k++) *out += (int64_t)fl[k].in * fl[k].out;
+    FactoredLayer fl[kMaxFactoredLayers];
+    const int nfl = net_factored_layers(ctx->net, fl, kMaxFactoredLayers);
+    for (int k = 0; k < nfl; k++) *out += (int64_t)fl[k].in * fl[k].out;
   }
   return SASGD_OK;
 }
@@ -540,9 +540,9 @@ int sasgd_copyWeights(sasgd_ctx* ctx, int64_t version, float* host_out) {
 // Writes the fully connected weight gradients that the learner holds as factors into its flat gradient buffer.
 static hipError_t expand_factored(sasgd_ctx* ctx, Learner& L) {
   if (!ctx->net || L.fc_expanded || L.grad_timestamp < 0) return hipSuccess;
-  FactoredLayer fl[16];
-  const int nfl = net_factored_layers(ctx->net, fl, 16);
-  for (int k = 0; k < nfl && k < 16; k++) {
+  FactoredLayer fl[kMaxFactoredLayers];
+  const int nfl = net_factored_layers(ctx->net, fl, kMaxFactoredLayers);
+  for (int k = 0; k < nfl; k++) {
     const FactoredLayer& F = fl[k];
     hipError_t e = launch_fc_expand_factors((const bf16_t*)L.workspace + F.fx_off, (const bf16_t*)L.workspace + F.fdy_off,
                                             L.grad + F.w_off, F.N, F.in, F.out, F.NP, ctx->stream);

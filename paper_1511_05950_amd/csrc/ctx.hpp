@@ -71,6 +71,7 @@ hipError_t net_calc_gradient(Net* net, const int* learners, const LearnerBind* b
                              float* out_loss_dev, int32_t* out_rank_dev, hipStream_t stream);
 // Fully connected layers whose weight gradient calcGradient leaves as factors in the learner's workspace
 // (bf16 element offsets from the workspace base): weights at w_off [out][in], bias right behind them.
+constexpr int kMaxFactoredLayers = 16;   // further fully connected layers write their gradient out
 struct FactoredLayer {
   int64_t w_off;
   int in, out, N, NP;

@@ -122,6 +122,7 @@ int net_create(const sasgd_config& cfg, Net** out, int64_t* out_P, size_t* out_p
   // space-to-depth transformed (stride s, no padding).
   const int chunk = net->bf16 ? 8 : 4;
   const bool allow_mfma = getenv("SASGD_NO_MFMA") == nullptr;
+  int n_factored = 0;
   auto round_chunk = [&](int x) { return (x + chunk - 1) / chunk * chunk; };
   net->inpack = InPack{C, H, W, C, H, W, 1};
   bool first_mfma = false;
@@ -231,9 +232,10 @@ int net_create(const sasgd_config& cfg, Net** out, int64_t* out_P, size_t* out_p
         // below what the update's streaming rate leaves room for
         const int c_upd = cfg.lambda / cfg.n;
         if (net->bf16 && !(cfg.flags & SASGD_FLAG_FLAT_FC_GRADIENT) && N <= 32 && (int64_t)c_upd * N <= 1024 && op.w_off % 4 == 0 &&
-            L.units % 4 == 0 && in % 8 == 0) {
+            L.units % 4 == 0 && in % 8 == 0 && n_factored < kMaxFactoredLayers) {
           op.factored = true;
           op.NP = (N + 7) & ~7;
+          n_factored++;
         }
       }
       C = L.units; H = 1; W = 1;

@@ -435,3 +435,34 @@ def test_factored_and_external_gradients_share_one_update():
     v_ref = coef * g0.astype(np.float64) + coef * gext.astype(np.float64) + 2 * coef * 1e-2 * w0.astype(np.float64)
     assert rel(v1, v_ref) < 1e-5
     assert rel(w1 - w0, -v_ref) < 1e-5
+
+
+def test_more_fully_connected_layers_than_the_factor_table_holds():
+    # the layers past the table's size write their gradient out; the update must treat both kinds alike
+    from paper_1511_05950_amd import binding
+    layers = []
+    for _ in range(18):
+        layers += [("fc", 16), ("relu",)]
+    net = {"name": "deepfc", "input": (8, 1, 1), "classes": 8, "layers": layers + [("fc", 8)]}
+    mu = 4
+    X = wl.images(net, mu, 80)
+    Y = wl.labels(net, mu, 81)
+    w0 = wl.init_weights(net, 82, std=0.35)
+    Xd, Yd = torch.from_numpy(X).cuda(), torch.from_numpy(Y).cuda()
+    res = []
+    for flags in (0, binding.FLAG_FLAT_FC_GRADIENT):
+        ctx = binding.Sasgd(1, mu, 1, 2, net=net, compute="bf16", alpha0=0.1, momentum=0.5, weight_decay=1e-2, init_weights=w0, flags=flags)
+        fp = ctx.factoredParams()
+        ctx.getMinibatch(0, Xd, Yd)
+        ctx.pullWeights(0, 0)
+        ctx.calcGradient([0])
+        assert ctx.pushGradient(0) == 0
+        ctx.sumGradients()
+        ctx.applyUpdate()
+        res.append((fp, ctx.copyWeights(), ctx.copyGradient(0)))
+        ctx.destroy()
+    # the layer on the raw input is not a candidate; the next 16 fill the table, the last two are written out
+    assert res[0][0] == 16 * 16 * 16 and res[1][0] == 0
+    assert np.abs(res[1][2]).max() > 0
+    assert rel(res[0][2], res[1][2]) < 1e-5
+    assert rel(res[0][1] - w0, res[1][1] - w0) < 1e-5
