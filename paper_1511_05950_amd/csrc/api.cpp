@@ -401,6 +401,7 @@ int sasgd_applyUpdate(sasgd_ctx* ctx, int64_t* out_new_timestamp) {
   u.momentum = ctx->cfg.momentum;
   u.decay = abar * ctx->cfg.weight_decay;
   u.v = ctx->v;
+  u.reverse = (int)(i & 1);   // consecutive updates walk in opposite directions (last-level cache reuse)
   const size_t Ppad = ((size_t)ctx->P + 63) & ~(size_t)63;
   bf16_t* new_slot_b16 = nullptr;
   if (ctx->cfg.compute == SASGD_BF16) {

@@ -26,6 +26,7 @@ struct UpdateLaunch {
   float coef[kMaxLearners];
   float momentum;
   float decay;             // (sum_l coef_l) * weight_decay
+  int reverse;             // walk the vector from its end (same result; see apply_update_kernel)
 };
 hipError_t launch_apply_update(const UpdateLaunch& u, hipStream_t stream);
 // Update of one fully connected layer (weights [out][in] followed by the bias [out]) whose gradients are kept as
