@@ -13,6 +13,8 @@
 // The im2col matrix is never materialised: a tile loader gathers 16-byte chunks straight from the NHWC
 // tensor (zero outside the image).  Only stride-1 windows are handled here; a strided first layer is
 // turned into a stride-1 layer by a space-to-depth re-layout of the input (see pack_input).
+#include <algorithm>
+#include <type_traits>
 #include "dev_common.hpp"
 #include "kernels.hpp"
 
@@ -386,11 +388,95 @@ __global__ __launch_bounds__(256) void igemm_kernel(PtrTab ws, CPtrTab wts, IGem
   }
 }
 
+typedef int v4i_t __attribute__((ext_vector_type(4)));
+// Bias, ReLU, ReLU mask of the input gradient, conversion and store of one wavefront's WM x WN accumulator tile whose
+// origin is (mw, nw).  `lds` is the workgroup's tile memory, free once every wavefront has passed the barrier inside.
+template <int WM, int WN>
+__device__ __forceinline__ void frag_epilogue(floatx16 (&acc)[WM / 32][WN / 32], bf16_t* lds, void* ws_base, const void* wt_base,
+                                              const IGemm& g, const Epilogue& ep, int mw, int nw, int lane, int wave) {
+  constexpr int TM = WM / 32, TN = WN / 32;
+  bf16_t* out = (bf16_t*)ws_base + ep.out_off;
+  const bf16_t* mask = (const bf16_t*)ws_base + ep.mask_off;
+  const bf16_t* bias = (const bf16_t*)wt_base + ep.bias_off;
+  if (!ep.out_f32) {
+    // bf16 output: a lane holds single elements of 16 different rows, which written straight out are 2-byte stores.
+    // Each wavefront turns its 32-row blocks around in its own piece of LDS (the tiles there are no longer needed) and
+    // writes 16 bytes per lane, 8 lanes per row; the ReLU mask of the input gradient is read the same way.
+    constexpr int LDE = WN + 8;                          // row stride of the staging piece (elements)
+    __syncthreads();                                     // every wavefront has finished reading the last tile
+    bf16_t* stage = lds + wave * (32 * LDE);
+    constexpr int CPRW = WN / 8;                         // 16-byte chunks per row of the wavefront's tile
+    constexpr int RPI = 64 / CPRW;                       // rows covered by one 64-lane pass
+    const int rrow = lane / CPRW, rchunk = lane % CPRW;
+#pragma unroll
+    for (int i = 0; i < TM; i++) {
+#pragma unroll
+      for (int j = 0; j < TN; j++) {
+        const int n = nw + 32 * j + (lane & 31);
+        const float bv = (ep.has_bias && n < g.Ncols) ? bf2f(bias[n]) : 0.f;
+#pragma unroll
+        for (int r = 0; r < 16; r++) {
+          float v = acc[i][j][r] + bv;
+          if (ep.relu) v = fmaxf(v, 0.f);
+          stage[(8 * (r >> 2) + 4 * (lane >> 5) + (r & 3)) * LDE + 32 * j + (lane & 31)] = f2bf(v);
+        }
+      }
+      // LDS operations of one wavefront complete in order, so its reads below see its writes above; the compiler is
+      // told not to move LDS accesses across the two phases
+      __builtin_amdgcn_wave_barrier();
+      asm volatile("" ::: "memory");
+#pragma unroll
+      for (int it = 0; it < 32 / RPI; it++) {
+        const int row = rrow + RPI * it;
+        const int m = mw + 32 * i + row, n = nw + rchunk * 8;
+        uint4 q = *reinterpret_cast<const uint4*>(stage + row * LDE + rchunk * 8);
+        if (m < g.M && n < g.Ncols) {
+          const int64_t o = (int64_t)m * g.Ncols + n;
+          if (ep.use_mask) {
+            const uint4 mk = *reinterpret_cast<const uint4*>(mask + o);
+            const uint32_t mw[4] = {mk.x, mk.y, mk.z, mk.w};
+            uint32_t qw[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+            for (int w = 0; w < 4; w++) {                // keep a 16-bit half where the forward value is positive
+              const uint32_t lo = mw[w] & 0xffffu, hi = mw[w] >> 16;
+              const uint32_t keep = (((lo & 0x8000u) == 0 && (lo & 0x7fffu) != 0) ? 0x0000ffffu : 0u) |
+                                    (((hi & 0x8000u) == 0 && (hi & 0x7fffu) != 0) ? 0xffff0000u : 0u);
+              qw[w] &= keep;
+            }
+            q = make_uint4(qw[0], qw[1], qw[2], qw[3]);
+          }
+          *reinterpret_cast<uint4*>(out + o) = q;
+        }
+      }
+      __builtin_amdgcn_wave_barrier();
+      asm volatile("" ::: "memory");
+    }
+    return;
+  }
+#pragma unroll
+  for (int j = 0; j < TN; j++) {
+    const int n = nw + 32 * j + (lane & 31);
+    if (n >= g.Ncols) continue;
+    const float bv = ep.has_bias ? bf2f(bias[n]) : 0.f;
+#pragma unroll
+    for (int i = 0; i < TM; i++)
+#pragma unroll
+      for (int r = 0; r < 16; r++) {
+        const int m = mw + 32 * i + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+        if (m >= g.M) continue;
+        float v = acc[i][j][r] + bv;
+        if (ep.relu) v = fmaxf(v, 0.f);
+        const int64_t o = (int64_t)m * g.Ncols + n;
+        if (ep.use_mask && !(bf2f(mask[o]) > 0.f)) v = 0.f;
+        reinterpret_cast<float*>(out)[o] = v;
+      }
+  }
+}
+
 // ------------------------------------------------------------------ convolution forward / dgrad, B from fragments
 // Same tiling as igemm_kernel, but only the gathered im2col tile goes through LDS; the filter operand comes
 // from the fragment-packed copy, one coalesced 1 KiB read per MFMA operand, prefetched one step ahead.  This
 // halves the LDS traffic per MFMA, which is what bounds the LDS-only variant.
-typedef int v4i_t __attribute__((ext_vector_type(4)));
 constexpr uint32_t kOutOfRange = 0x80000000u;   // buffer offset beyond any tensor: the load returns zeros
 
 // NT = threads per workgroup = 64 x number of wave tiles.
@@ -615,83 +701,240 @@ __global__ __launch_bounds__(NT, (WM * WN > 64 * 64 ? 2 : 1)) void igemm_frag_ke
     }
     return;
   }
-  bf16_t* out = (bf16_t*)ws.p[z] + ep.out_off;
-  const bf16_t* mask = (const bf16_t*)ws.p[z] + ep.mask_off;
-  const bf16_t* bias = (const bf16_t*)wts.p[z] + ep.bias_off;
-  if (!ep.out_f32) {
-    // bf16 output: a lane holds single elements of 16 different rows, which written straight out are 2-byte stores.
-    // Each wavefront turns its 32-row blocks around in its own piece of LDS (the tiles there are no longer needed) and
-    // writes 16 bytes per lane, 8 lanes per row; the ReLU mask of the input gradient is read the same way.
-    constexpr int LDE = WN + 8;                          // row stride of the staging piece (elements)
-    static_assert(4 * 32 * LDE <= 2 * A_ELEMS || NT != 256, "staging piece fits the tile buffers");
-    __syncthreads();                                     // every wavefront has finished reading the last tile
-    bf16_t* stage = lds + wave * (32 * LDE);
-    constexpr int CPRW = WN / 8;                         // 16-byte chunks per row of the wavefront's tile
-    constexpr int RPI = 64 / CPRW;                       // rows covered by one 64-lane pass
-    const int rrow = lane / CPRW, rchunk = lane % CPRW;
-#pragma unroll
-    for (int i = 0; i < TM; i++) {
-#pragma unroll
-      for (int j = 0; j < TN; j++) {
-        const int n = n0 + wn0 + 32 * j + (lane & 31);
-        const float bv = (ep.has_bias && n < g.Ncols) ? bf2f(bias[n]) : 0.f;
-#pragma unroll
-        for (int r = 0; r < 16; r++) {
-          float v = acc[i][j][r] + bv;
-          if (ep.relu) v = fmaxf(v, 0.f);
-          stage[(8 * (r >> 2) + 4 * (lane >> 5) + (r & 3)) * LDE + 32 * j + (lane & 31)] = f2bf(v);
-        }
-      }
-      // LDS operations of one wavefront complete in order, so its reads below see its writes above; the compiler is
-      // told not to move LDS accesses across the two phases
-      __builtin_amdgcn_wave_barrier();
-      asm volatile("" ::: "memory");
-#pragma unroll
-      for (int it = 0; it < 32 / RPI; it++) {
-        const int row = rrow + RPI * it;
-        const int m = m0 + wm0 + 32 * i + row, n = n0 + wn0 + rchunk * 8;
-        uint4 q = *reinterpret_cast<const uint4*>(stage + row * LDE + rchunk * 8);
-        if (m < g.M && n < g.Ncols) {
-          const int64_t o = (int64_t)m * g.Ncols + n;
-          if (ep.use_mask) {
-            const uint4 mk = *reinterpret_cast<const uint4*>(mask + o);
-            const uint32_t mw[4] = {mk.x, mk.y, mk.z, mk.w};
-            uint32_t qw[4] = {q.x, q.y, q.z, q.w};
-#pragma unroll
-            for (int w = 0; w < 4; w++) {                // keep a 16-bit half where the forward value is positive
-              const uint32_t lo = mw[w] & 0xffffu, hi = mw[w] >> 16;
-              const uint32_t keep = (((lo & 0x8000u) == 0 && (lo & 0x7fffu) != 0) ? 0x0000ffffu : 0u) |
-                                    (((hi & 0x8000u) == 0 && (hi & 0x7fffu) != 0) ? 0xffff0000u : 0u);
-              qw[w] &= keep;
-            }
-            q = make_uint4(qw[0], qw[1], qw[2], qw[3]);
-          }
-          *reinterpret_cast<uint4*>(out + o) = q;
-        }
-      }
-      __builtin_amdgcn_wave_barrier();
-      asm volatile("" ::: "memory");
+  static_assert(4 * 32 * (WN + 8) <= 2 * A_ELEMS || NT != 256, "the epilogue's staging piece fits the tile buffers");
+  frag_epilogue<WM, WN>(acc, lds, ws.p[z], wts.p[z], g, ep, m0 + wm0, n0 + wn0, lane, wave);
+}
+
+// ------------------------------------------------------------------ convolution forward / dgrad, input patch in LDS
+// For windows larger than 1 x 1 the im2col tile of one tap is the tile of the neighbouring tap shifted by one
+// pixel, so gathering it tap by tap moves every input pixel ks*ks times from the L1 into LDS.  This kernel puts
+// the input patch under a tile of BM output positions into LDS once per 32 input channels (zero padding and the
+// halo rows included, 80 bytes per pixel) and reads the MFMA A operand of tap (kh, kw) from it at the address of the
+// output position's window origin plus a wavefront-uniform offset.  The ks*ks contraction steps of one channel
+// chunk run without a barrier; the filter operand comes from the fragment-packed copy as in igemm_frag_kernel
+// (k = tap * C + c, so the 32 channels of a chunk are two 16-k blocks at tap * C/16 + 2 * chunk).
+//   patch rows: the output rows gr = m / OW of the tile, gr_lo .. gr_hi, may belong to several images; image n owns
+//   a band of (its output rows in the tile) + ks - 1 input rows, so the row of (gr, kh) is
+//   (gr - gr_lo) + kh + (ks - 1)(n - n_lo);  patch columns: OW + ks - 1 = W + 2 pad.
+// The contraction may be split over channel chunks (g.splits <= C / 32).
+struct HaloArgs {
+  int PW;              // patch width in pixels
+  uint32_t mg_pw;      // multiplier for division by PW
+  int n_px_max;        // pixels the LDS patch has room for
+};
+
+template <int BM, int BN, int WM, int WN>
+__global__ __launch_bounds__(256, (WM * WN > 64 * 64 ? 2 : 1)) void conv_halo_kernel(PtrTab ws, CPtrTab wts, IGemm g, Epilogue ep, HaloArgs h) {
+  constexpr int NT = 256;
+  constexpr int WAVES_N = BN / WN;
+  constexpr int TM = WM / 32, TN = WN / 32;
+  constexpr int PST = 40;                      // elements per patch pixel: 32 channels + 8 of padding (conflict-free 16-byte reads)
+  constexpr int PLR = TM * TN > 4 ? 2 : 4;     // 16-byte pieces per thread and refill round (registers are scarce with the large tile)
+  extern __shared__ __attribute__((aligned(16))) bf16_t halo_lds[];
+  bf16_t* lds = halo_lds;
+  int* tab = reinterpret_cast<int*>(lds + h.n_px_max * PST);   // byte offset of every patch pixel in the tensor
+
+  const int z = blockIdx.z / g.splits, sp = blockIdx.z % g.splits;
+  const bf16_t* act = (const bf16_t*)ws.p[z] + g.a_off;
+  const bf16_t* Bf = (const bf16_t*)wts.p[z] + g.b_off;
+  const __amdgpu_buffer_rsrc_t rsrc_a = __builtin_amdgcn_make_buffer_rsrc((void*)act, 0, (int)g.a_bytes, 0x00020000);
+  const __amdgpu_buffer_rsrc_t rsrc_b = __builtin_amdgcn_make_buffer_rsrc((void*)Bf, 0, (int)g.b_bytes, 0x00020000);
+  const int m0 = blockIdx.x * BM, n0 = blockIdx.y * BN;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm0 = (wave / WAVES_N) * WM, wn0 = (wave % WAVES_N) * WN;
+  const int KB16 = g.ldb / 16;
+  const int NB = (g.Ncols + 31) / 32;
+
+  const int ks = g.ks, PW = h.PW;
+  const int m_last = min(m0 + BM, g.M) - 1;
+  const int gr_lo = (int)fastdiv((uint32_t)m0, g.OW, g.mg_ow), gr_hi = (int)fastdiv((uint32_t)m_last, g.OW, g.mg_ow);
+  const int n_lo = (int)fastdiv((uint32_t)gr_lo, g.OH, g.mg_oh), n_hi = (int)fastdiv((uint32_t)gr_hi, g.OH, g.mg_oh);
+  const int oh_lo = gr_lo - n_lo * g.OH;
+  const int NR = gr_hi - gr_lo + 1;
+  const int n_px = (NR + (ks - 1) * (n_hi - n_lo + 1)) * PW;   // <= h.n_px_max (checked by the launcher's bound)
+  const int n_items = n_px * 4;
+
+  for (int p = tid; p < n_px; p += NT) {
+    const int pr = (int)fastdiv((uint32_t)p, PW, h.mg_pw), pc = p - pr * PW;
+    int start = 0, rem = NR, n = n_lo, first = oh_lo, ih = -1, nn = -1;
+    while (rem > 0) {
+      const int rows = min(g.OH - first, rem), len = rows + ks - 1;
+      if (pr < start + len) { nn = n; ih = first - g.pad + (pr - start); break; }
+      start += len; rem -= rows; n++; first = 0;
     }
-    return;
+    const int iw = pc - g.pad;
+    const bool ok = nn >= 0 && (unsigned)ih < (unsigned)g.H && (unsigned)iw < (unsigned)g.W;
+    tab[p] = ok ? ((nn * g.H + ih) * g.W + iw) * g.C * 2 : (int)kOutOfRange;
   }
+
+  // window origin of this lane's rows in the patch (bytes); rows beyond M repeat the last one and are never stored
+  int abase[TM];
+#pragma unroll
+  for (int i = 0; i < TM; i++) {
+    const uint32_t m = (uint32_t)min(m0 + wm0 + 32 * i + (lane & 31), g.M - 1);
+    const uint32_t gr = fastdiv(m, g.OW, g.mg_ow), ow = m - gr * (uint32_t)g.OW;
+    const uint32_t n = fastdiv(gr, g.OH, g.mg_oh);
+    const int pr0 = ((int)gr - gr_lo) + (ks - 1) * ((int)n - n_lo);
+    abase[i] = ((pr0 * PW + (int)ow) * PST + 8 * (lane >> 5)) * 2;
+  }
+  __syncthreads();
+
+  v4i_t pre[PLR];
+  const int rounds = (n_items + NT * PLR - 1) / (NT * PLR);
+  auto patch_load = [&](int round, int cc) {
+#pragma unroll
+    for (int j = 0; j < PLR; j++) {
+      const int it = (round * PLR + j) * NT + tid;
+      const int p = min(it >> 2, n_px - 1);
+      pre[j] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_a, tab[p] + (it & 3) * 16, cc * 64, 0);
+    }
+  };
+  auto patch_store = [&](int round) {
+#pragma unroll
+    for (int j = 0; j < PLR; j++) {
+      const int it = (round * PLR + j) * NT + tid;
+      if (it < n_items) *reinterpret_cast<v4i_t*>(reinterpret_cast<char*>(lds) + (it >> 2) * (PST * 2) + (it & 3) * 16) = pre[j];
+    }
+  };
+
+  uint32_t boff[TN];
 #pragma unroll
   for (int j = 0; j < TN; j++) {
-    const int n = n0 + wn0 + 32 * j + (lane & 31);
-    if (n >= g.Ncols) continue;
-    const float bv = ep.has_bias ? bf2f(bias[n]) : 0.f;
+    const int nb = (n0 + wn0) / 32 + j;
+    boff[j] = nb < NB ? (uint32_t)(((int64_t)nb * KB16 * 512 + lane * 8) * 2) : kOutOfRange;
+  }
+  const int b_tap = __builtin_amdgcn_readfirstlane((g.C / 16) * 1024);   // bytes from one tap's k-blocks to the next tap's
+  auto load_b = [&](bf16x8 (&bt)[2][TN], int s_off) {
+#pragma unroll
+    for (int kk = 0; kk < 2; kk++)
+#pragma unroll
+      for (int j = 0; j < TN; j++) {
+        union { v4i_t u; bf16x8 v; } f;
+        f.u = __builtin_amdgcn_raw_buffer_load_b128(rsrc_b, (int)(boff[j] + kk * 1024), s_off, 0);
+        bt[kk][j] = f.v;
+      }
+  };
+  auto lds_a = [&](int i, int toff, int kk) {
+    return *reinterpret_cast<const bf16x8*>(reinterpret_cast<const char*>(lds) + abase[i] + toff + kk * 32);
+  };
+
+  floatx16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; i++)
+#pragma unroll
+    for (int j = 0; j < TN; j++)
+#pragma unroll
+      for (int r = 0; r < 16; r++) acc[i][j][r] = 0.f;
+
+  const int chunks = g.C >> 5;
+  const int per = (chunks + g.splits - 1) / g.splits;
+  const int cc_begin = __builtin_amdgcn_readfirstlane(sp * per);
+  const int cc_end = __builtin_amdgcn_readfirstlane(min(chunks, cc_begin + per));
+  const int T = ks * ks;
+  const int a_wrap = (PW - ks) * PST * 2;
+
+  // patch byte offset of the running tap (c_aoff); patch offset, kw and filter byte offset of the tap after it (n_*)
+  int c_aoff = 0, n_aoff = 0, n_kw = 0, n_boff = 0;
+  auto advance = [&]() {
+    c_aoff = n_aoff;
+    n_kw++; n_aoff += PST * 2; n_boff += b_tap;
+    const bool wrap = n_kw == ks;
+    n_kw = wrap ? 0 : n_kw;
+    n_aoff += wrap ? a_wrap : 0;
+  };
+  // One tap: the filter fragments of the next tap are requested, the second k-block's A fragments are read, the
+  // first k-block's MFMAs run, the next tap's first A fragments are read, the second k-block's MFMAs run.
+  auto step = [&](bf16x8 (&bcur)[2][TN], bf16x8 (&bnext)[2][TN], bf16x8 (&a0)[TM], bf16x8 (&a0n)[TM], bool has_next) {
+    if (has_next) load_b(bnext, n_boff);
+    bf16x8 a1[TM];
+#pragma unroll
+    for (int i = 0; i < TM; i++) a1[i] = lds_a(i, c_aoff, 1);
+    __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_setprio(1);
 #pragma unroll
     for (int i = 0; i < TM; i++)
 #pragma unroll
-      for (int r = 0; r < 16; r++) {
-        const int m = m0 + wm0 + 32 * i + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-        if (m >= g.M) continue;
-        float v = acc[i][j][r] + bv;
-        if (ep.relu) v = fmaxf(v, 0.f);
-        const int64_t o = (int64_t)m * g.Ncols + n;
-        if (ep.use_mask && !(bf2f(mask[o]) > 0.f)) v = 0.f;
-        reinterpret_cast<float*>(out)[o] = v;
-      }
+      for (int j = 0; j < TN; j++) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0[i], bcur[0][j], acc[i][j], 0, 0, 0);
+    __builtin_amdgcn_s_setprio(0);
+    if (has_next) {
+#pragma unroll
+      for (int i = 0; i < TM; i++) a0n[i] = lds_a(i, n_aoff, 0);
+    }
+    __builtin_amdgcn_s_setprio(1);
+#pragma unroll
+    for (int i = 0; i < TM; i++)
+#pragma unroll
+      for (int j = 0; j < TN; j++) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1[i], bcur[1][j], acc[i][j], 0, 0, 0);
+    __builtin_amdgcn_s_setprio(0);
+    advance();
+  };
+
+  bf16x8 b0[2][TN], b1[2][TN], fa[TM], fb[TM];
+  if (cc_begin < cc_end) {
+#pragma unroll 1
+    for (int r = 0; r < rounds; r++) {
+      patch_load(r, cc_begin);
+      patch_store(r);
+    }
+    load_b(b0, cc_begin * 2048);
   }
+  __syncthreads();
+  // Two copies of the chunk loop, for odd and even tap counts: with the last taps written out straight-line the
+  // accumulators keep their registers around the loop (a joined tail made the compiler hold a second set).
+  auto run = [&](auto odd) {
+#pragma unroll 1
+    for (int cc = cc_begin; cc < cc_end; cc++) {
+      n_aoff = 0; n_kw = 0; n_boff = cc * 2048;
+      advance();                                 // c_aoff = tap 0, n_* = tap 1
+#pragma unroll
+      for (int i = 0; i < TM; i++) fa[i] = lds_a(i, 0, 0);
+      const int pairs = (T - 1) >> 1;            // odd: all but the last tap; even: all but the last two
+#pragma unroll 1
+      for (int t = 0; t < pairs; t++) {
+        step(b0, b1, fa, fb, true);
+        step(b1, b0, fb, fa, true);
+      }
+      const bool more = cc + 1 < cc_end;
+      if (more) patch_load(0, cc + 1);           // the next chunk's pixels travel while the last taps run
+      if constexpr (decltype(odd)::value) {
+        step(b0, b1, fa, fb, false);
+      } else {
+        step(b0, b1, fa, fb, true);
+        step(b1, b0, fb, fa, false);
+      }
+      if (more) load_b(b0, (cc + 1) * 2048);
+      __syncthreads();                           // every wavefront has finished reading the patch
+      if (more) {
+        patch_store(0);
+#pragma unroll 1
+        for (int r = 1; r < rounds; r++) {
+          patch_load(r, cc + 1);
+          patch_store(r);
+        }
+      }
+      __syncthreads();
+    }
+  };
+  if (T & 1) run(std::true_type{});
+  else run(std::false_type{});
+
+  if (g.splits > 1) {
+    float* part = reinterpret_cast<float*>((char*)ws.p[z] + g.scratch_off) + (int64_t)sp * g.M * g.Ncols;
+#pragma unroll
+    for (int j = 0; j < TN; j++) {
+      const int n = n0 + wn0 + 32 * j + (lane & 31);
+      if (n >= g.Ncols) continue;
+#pragma unroll
+      for (int i = 0; i < TM; i++)
+#pragma unroll
+        for (int r = 0; r < 16; r++) {
+          const int m = m0 + wm0 + 32 * i + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+          if (m < g.M) part[(int64_t)m * g.Ncols + n] = acc[i][j][r];
+        }
+    }
+    return;
+  }
+  frag_epilogue<WM, WN>(acc, lds, ws.p[z], wts.p[z], g, ep, m0 + wm0, n0 + wn0, lane, wave);
 }
 
 // Sum of the split partials in split order, then bias / ReLU / mask / conversion.
@@ -773,8 +1016,40 @@ static void launch_frag_t(const PtrTab& ws, const CPtrTab& wts, const IGemm& g, 
 }
 
 // Convolution forward / input gradient with fragment-packed filters (g.b_off points at the fragment copy).
+// The patch-in-LDS kernel applies to windows larger than 1 x 1 over a multiple of 32 channels whose patch (plus the
+// pixel table, 84 bytes per pixel) fits 64 KiB of LDS; the contraction is split at most once per channel chunk.
+template <int BM, int BN, int WM, int WN>
+static bool launch_halo_t(const PtrTab& ws, const CPtrTab& wts, const IGemm& g_in, const Epilogue& ep, int count, hipStream_t s) {
+  if (g_in.ks < 2 || g_in.C % 32 || g_in.OW + g_in.ks - 1 != g_in.W + 2 * g_in.pad) return false;
+  IGemm g = g_in;
+  g.splits = std::min(g.splits, g.C / 32);
+  HaloArgs h;
+  h.PW = g.OW + g.ks - 1;
+  h.mg_pw = magic_u32(h.PW);
+  const int rows = (BM + g.OW - 2) / g.OW + 1;               // output rows a tile of BM positions can touch
+  const int images = (rows + g.OH - 2) / g.OH + 1;           // and images those rows can belong to
+  h.n_px_max = (rows + (g.ks - 1) * images) * h.PW;
+  const size_t stage = (size_t)4 * 32 * (WN + 8) * 2;        // the epilogue's staging piece
+  const size_t bytes = std::max((size_t)h.n_px_max * 84, stage);
+  if (bytes > 64 * 1024) return false;
+  dim3 grid((unsigned)((g.M + BM - 1) / BM), (unsigned)((g.Ncols + BN - 1) / BN), (unsigned)(count * g.splits));
+  hipLaunchKernelGGL((conv_halo_kernel<BM, BN, WM, WN>), grid, dim3(256), bytes, s, ws, wts, g, ep, h);
+  if (g.splits > 1) {
+    int64_t total = ((int64_t)g.M * g.Ncols) >> 2;
+    unsigned blocks = (unsigned)((total + 255) / 256 < 2048 ? (total + 255) / 256 : 2048);
+    hipLaunchKernelGGL(igemm_finish_kernel, dim3(blocks, 1, (unsigned)count), dim3(256), 0, s, ws, wts, g, ep);
+  }
+  return true;
+}
+
 hipError_t launch_igemm_frag(const PtrTab& ws, const CPtrTab& wts, const IGemm& g, const Epilogue& ep, int count, hipStream_t s) {
   if (g.C % 8 || g.ldb % 32 || g.splits < 1) return hipErrorInvalidValue;
+  static const bool no_halo = getenv("SASGD_NO_HALO") != nullptr;
+  if (!no_halo && g.Ncols > 64) {
+    const bool done = g.Ncols % 256 == 0 ? launch_halo_t<128, 256, 128, 64>(ws, wts, g, ep, count, s)
+                                         : launch_halo_t<128, 128, 64, 64>(ws, wts, g, ep, count, s);
+    if (done) return hipGetLastError();
+  }
   // Wave tile 128 x 64 (two wavefronts per SIMD, accumulators in ordinary registers) wins where the columns fill
   // whole 256-wide tiles: each B fragment then serves four MFMAs instead of two.  Measured slower: 256 x 128 blocks,
   // 192-wide tiles of three wavefronts for 384 columns, 96-wide tiles for 96 columns, and taking the filters

@@ -79,6 +79,10 @@ TINY = {
     # shapes the bf16 MFMA kernels take (channel counts multiples of 8), with ragged tile edges
     "mfma_pad3": wl.tiny_net(3, 13, 11, 8, conv=((16, 3, 1, 1), (24, 5, 1, 2)), pool="maxpool", fc_hidden=40),
     "mfma_s2d": wl.tiny_net(3, 29, 27, 16, conv=((8, 7, 2, 0), (72, 3, 1, 0)), pool="avgpool", fc_hidden=136),
+    # windows over multiples of 32 channels (input patch kept in LDS): tiles spanning several images, ragged last
+    # tile, 1 / 3 / 5 / 8 channel chunks, odd and even tap counts, both tile widths, forward and input gradient
+    "patch_3x3": wl.tiny_net(3, 9, 8, 8, conv=((32, 3, 1, 1), (96, 3, 1, 1), (128, 3, 1, 0), (96, 2, 1, 1)), pool="maxpool", fc_hidden=24),
+    "patch_5x5": wl.tiny_net(3, 10, 9, 8, conv=((64, 3, 1, 1), (256, 5, 1, 2), (160, 3, 1, 1), (256, 4, 1, 1)), pool="avgpool", fc_hidden=24),
     "mfma_s4": wl.tiny_net(3, 39, 39, 8, conv=((24, 11, 4, 0), (40, 3, 1, 1), (136, 3, 1, 1)), pool="maxpool", fc_hidden=264),
 }
 
