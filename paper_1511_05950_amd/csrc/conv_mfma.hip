@@ -721,18 +721,18 @@ struct HaloArgs {
   int PW;              // patch width in pixels
   uint32_t mg_pw;      // multiplier for division by PW
   int n_px_max;        // pixels the LDS patch has room for
+  int tab_off;         // bytes from the start of LDS to the pixel table (behind the patch, rounded up to whole refill rounds)
 };
 
 template <int BM, int BN, int WM, int WN>
-__global__ __launch_bounds__(256, (WM * WN > 64 * 64 ? 2 : 1)) void conv_halo_kernel(PtrTab ws, CPtrTab wts, IGemm g, Epilogue ep, HaloArgs h) {
-  constexpr int NT = 256;
+__global__ __launch_bounds__(64 * (BM / WM) * (BN / WN), (WM * WN > 64 * 64 ? 2 : 3)) void conv_halo_kernel(PtrTab ws, CPtrTab wts, IGemm g, Epilogue ep, HaloArgs h) {
+  constexpr int NT = 64 * (BM / WM) * (BN / WN);
   constexpr int WAVES_N = BN / WN;
   constexpr int TM = WM / 32, TN = WN / 32;
   constexpr int PST = 40;                      // elements per patch pixel: 32 channels + 8 of padding (conflict-free 16-byte reads)
-  constexpr int PLR = TM * TN > 4 ? 2 : 4;     // 16-byte pieces per thread and refill round (registers are scarce with the large tile)
   extern __shared__ __attribute__((aligned(16))) bf16_t halo_lds[];
   bf16_t* lds = halo_lds;
-  int* tab = reinterpret_cast<int*>(lds + h.n_px_max * PST);   // byte offset of every patch pixel in the tensor
+  int* tab = reinterpret_cast<int*>(reinterpret_cast<char*>(lds) + h.tab_off);   // byte offset of every patch pixel in the tensor
 
   const int z = blockIdx.z / g.splits, sp = blockIdx.z % g.splits;
   const bf16_t* act = (const bf16_t*)ws.p[z] + g.a_off;
@@ -752,7 +752,6 @@ __global__ __launch_bounds__(256, (WM * WN > 64 * 64 ? 2 : 1)) void conv_halo_ke
   const int oh_lo = gr_lo - n_lo * g.OH;
   const int NR = gr_hi - gr_lo + 1;
   const int n_px = (NR + (ks - 1) * (n_hi - n_lo + 1)) * PW;   // <= h.n_px_max (checked by the launcher's bound)
-  const int n_items = n_px * 4;
 
   for (int p = tid; p < n_px; p += NT) {
     const int pr = (int)fastdiv((uint32_t)p, PW, h.mg_pw), pc = p - pr * PW;
@@ -779,21 +778,21 @@ __global__ __launch_bounds__(256, (WM * WN > 64 * 64 ? 2 : 1)) void conv_halo_ke
   }
   __syncthreads();
 
-  v4i_t pre[PLR];
-  const int rounds = (n_items + NT * PLR - 1) / (NT * PLR);
-  auto patch_load = [&](int round, int cc) {
-#pragma unroll
-    for (int j = 0; j < PLR; j++) {
-      const int it = (round * PLR + j) * NT + tid;
-      const int p = min(it >> 2, n_px - 1);
-      pre[j] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_a, tab[p] + (it & 3) * 16, cc * 64, 0);
-    }
-  };
-  auto patch_store = [&](int round) {
-#pragma unroll
-    for (int j = 0; j < PLR; j++) {
-      const int it = (round * PLR + j) * NT + tid;
-      if (it < n_items) *reinterpret_cast<v4i_t*>(reinterpret_cast<char*>(lds) + (it >> 2) * (PST * 2) + (it & 3) * 16) = pre[j];
+  // Patch refill: LDS-direct loads, 64 consecutive 16-byte slots per wavefront and instruction.  Slot s holds piece
+  // s % 5 of pixel s / 5; the fifth piece of a pixel is its padding and, like the slots beyond the patch, is
+  // requested out of range (the hardware writes zeros).
+  const int n_slots = n_px * 5;
+  const int dma_rounds = (n_slots + NT - 1) / NT;
+  const int wave_slot = __builtin_amdgcn_readfirstlane(wave * 64);
+  auto refill = [&](int cc) {
+#pragma unroll 1
+    for (int r = 0; r < dma_rounds; r++) {
+      const int sl = r * NT + tid;
+      const int px = (int)(__umulhi((uint32_t)sl, 0xCCCCCCCDu) >> 2);   // sl / 5
+      const int sub = sl - 5 * px;
+      const int voff = (sub < 4 && sl < n_slots) ? tab[min(px, n_px - 1)] + sub * 16 : (int)kOutOfRange;
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_a, (__attribute__((address_space(3))) void*)(reinterpret_cast<char*>(lds) + (r * NT + wave_slot) * 16),
+                                               16, voff, cc * 64, 0, 0);
     }
   };
 
@@ -842,11 +841,14 @@ __global__ __launch_bounds__(256, (WM * WN > 64 * 64 ? 2 : 1)) void conv_halo_ke
     n_kw = wrap ? 0 : n_kw;
     n_aoff += wrap ? a_wrap : 0;
   };
-  // One tap: the filter fragments of the next tap are requested, the second k-block's A fragments are read, the
-  // first k-block's MFMAs run, the next tap's first A fragments are read, the second k-block's MFMAs run.
-  auto step = [&](bf16x8 (&bcur)[2][TN], bf16x8 (&bnext)[2][TN], bf16x8 (&a0)[TM], bf16x8 (&a0n)[TM], bool has_next) {
-    if (has_next) load_b(bnext, n_boff);
-    bf16x8 a1[TM];
+  // One tap.  The filter fragments travel two taps ahead through a ring of three register sets (the L2 round trip is
+  // longer than one tap's MFMAs): `bld` receives tap t + 2 while `bcur` (tap t) is consumed.  The second k-block's A
+  // fragments are read, the first k-block's MFMAs run, the next tap's first A fragments are read, the second
+  // k-block's MFMAs run.
+  bf16x8 a0[TM];
+  auto step = [&](bf16x8 (&bcur)[2][TN], bf16x8 (&bld)[2][TN], bool ld, bool has_next) {
+    if (ld) load_b(bld, n_boff + b_tap);
+    bf16x8 a1[TM], a0n[TM];
 #pragma unroll
     for (int i = 0; i < TM; i++) a1[i] = lds_a(i, c_aoff, 1);
     __builtin_amdgcn_sched_barrier(0);
@@ -866,56 +868,60 @@ __global__ __launch_bounds__(256, (WM * WN > 64 * 64 ? 2 : 1)) void conv_halo_ke
 #pragma unroll
       for (int j = 0; j < TN; j++) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1[i], bcur[1][j], acc[i][j], 0, 0, 0);
     __builtin_amdgcn_s_setprio(0);
+    if (has_next) {
+#pragma unroll
+      for (int i = 0; i < TM; i++) a0[i] = a0n[i];
+    }
     advance();
   };
 
-  bf16x8 b0[2][TN], b1[2][TN], fa[TM], fb[TM];
+  bf16x8 bq0[2][TN], bq1[2][TN], bq2[2][TN];
   if (cc_begin < cc_end) {
-#pragma unroll 1
-    for (int r = 0; r < rounds; r++) {
-      patch_load(r, cc_begin);
-      patch_store(r);
-    }
-    load_b(b0, cc_begin * 2048);
+    refill(cc_begin);
+    load_b(bq0, cc_begin * 2048);
+    load_b(bq1, cc_begin * 2048 + b_tap);
   }
+  __builtin_amdgcn_s_waitcnt(0);
   __syncthreads();
-  // Two copies of the chunk loop, for odd and even tap counts: with the last taps written out straight-line the
-  // accumulators keep their registers around the loop (a joined tail made the compiler hold a second set).
-  auto run = [&](auto odd) {
+  // ks * ks leaves the remainder 0 or 1 when divided by three, so after the full groups of three taps either three
+  // or four taps remain.  They are written out straight-line in two copies of the chunk loop: with a joined tail the
+  // compiler kept a second set of accumulators.
+  auto run = [&](auto four) {
+    const int groups = (T - 2) / 3;
 #pragma unroll 1
     for (int cc = cc_begin; cc < cc_end; cc++) {
       n_aoff = 0; n_kw = 0; n_boff = cc * 2048;
       advance();                                 // c_aoff = tap 0, n_* = tap 1
 #pragma unroll
-      for (int i = 0; i < TM; i++) fa[i] = lds_a(i, 0, 0);
-      const int pairs = (T - 1) >> 1;            // odd: all but the last tap; even: all but the last two
+      for (int i = 0; i < TM; i++) a0[i] = lds_a(i, 0, 0);
 #pragma unroll 1
-      for (int t = 0; t < pairs; t++) {
-        step(b0, b1, fa, fb, true);
-        step(b1, b0, fb, fa, true);
+      for (int t = 0; t < groups; t++) {
+        step(bq0, bq2, true, true);
+        step(bq1, bq0, true, true);
+        step(bq2, bq1, true, true);
+      }
+      if constexpr (decltype(four)::value) {
+        step(bq0, bq2, true, true);
+        step(bq1, bq0, true, true);
+        step(bq2, bq1, false, true);
+        step(bq0, bq2, false, false);
+      } else {
+        step(bq0, bq2, true, true);
+        step(bq1, bq0, false, true);
+        step(bq2, bq1, false, false);
       }
       const bool more = cc + 1 < cc_end;
-      if (more) patch_load(0, cc + 1);           // the next chunk's pixels travel while the last taps run
-      if constexpr (decltype(odd)::value) {
-        step(b0, b1, fa, fb, false);
-      } else {
-        step(b0, b1, fa, fb, true);
-        step(b1, b0, fb, fa, false);
-      }
-      if (more) load_b(b0, (cc + 1) * 2048);
-      __syncthreads();                           // every wavefront has finished reading the patch
       if (more) {
-        patch_store(0);
-#pragma unroll 1
-        for (int r = 1; r < rounds; r++) {
-          patch_load(r, cc + 1);
-          patch_store(r);
-        }
+        load_b(bq0, (cc + 1) * 2048);
+        load_b(bq1, (cc + 1) * 2048 + b_tap);
       }
+      __syncthreads();                           // every wavefront has finished reading the patch
+      if (more) refill(cc + 1);
+      __builtin_amdgcn_s_waitcnt(0);
       __syncthreads();
     }
   };
-  if (T & 1) run(std::true_type{});
+  if (T % 3 == 1) run(std::true_type{});
   else run(std::false_type{});
 
   if (g.splits > 1) {
@@ -1029,11 +1035,14 @@ static bool launch_halo_t(const PtrTab& ws, const CPtrTab& wts, const IGemm& g_i
   const int rows = (BM + g.OW - 2) / g.OW + 1;               // output rows a tile of BM positions can touch
   const int images = (rows + g.OH - 2) / g.OH + 1;           // and images those rows can belong to
   h.n_px_max = (rows + (g.ks - 1) * images) * h.PW;
-  const size_t stage = (size_t)4 * 32 * (WN + 8) * 2;        // the epilogue's staging piece
-  const size_t bytes = std::max((size_t)h.n_px_max * 84, stage);
+  constexpr int NT = 64 * (BM / WM) * (BN / WN);
+  const size_t stage = (size_t)(NT / 64) * 32 * (WN + 8) * 2;   // the epilogue's staging pieces
+  const size_t slot_round = (size_t)NT * 16;                 // bytes one refill instruction per thread covers
+  h.tab_off = (int)(((size_t)h.n_px_max * 80 + slot_round - 1) / slot_round * slot_round);
+  const size_t bytes = std::max((size_t)h.tab_off + (size_t)h.n_px_max * 4, stage);
   if (bytes > 64 * 1024) return false;
   dim3 grid((unsigned)((g.M + BM - 1) / BM), (unsigned)((g.Ncols + BN - 1) / BN), (unsigned)(count * g.splits));
-  hipLaunchKernelGGL((conv_halo_kernel<BM, BN, WM, WN>), grid, dim3(256), bytes, s, ws, wts, g, ep, h);
+  hipLaunchKernelGGL((conv_halo_kernel<BM, BN, WM, WN>), grid, dim3(NT), bytes, s, ws, wts, g, ep, h);
   if (g.splits > 1) {
     int64_t total = ((int64_t)g.M * g.Ncols) >> 2;
     unsigned blocks = (unsigned)((total + 255) / 256 < 2048 ? (total + 255) / 256 : 2048);
@@ -1044,8 +1053,18 @@ static bool launch_halo_t(const PtrTab& ws, const CPtrTab& wts, const IGemm& g_i
 
 hipError_t launch_igemm_frag(const PtrTab& ws, const CPtrTab& wts, const IGemm& g, const Epilogue& ep, int count, hipStream_t s) {
   if (g.C % 8 || g.ldb % 32 || g.splits < 1) return hipErrorInvalidValue;
-  static const bool no_halo = getenv("SASGD_NO_HALO") != nullptr;
-  if (!no_halo && g.Ncols > 64) {
+  // Narrow layers: 256-row tiles (64 x 32 per wavefront) once there are enough of them to fill the chip, else 128 rows.
+  // Measured on the CIFAR-shaped layers (18 learners x 128 images): 5x5 over 32 channels, 16x16 images, 39 us against
+  // 46 us with 128-row tiles and 68 us for the tap-by-tap gather; 8x8 images 27 us against 33 us and 43 us.
+  if (g.Ncols <= 32) {
+    const bool many = (int64_t)((g.M + 255) / 256) * count >= 1024;
+    const bool done = many ? launch_halo_t<256, 32, 64, 32>(ws, wts, g, ep, count, s) : launch_halo_t<128, 32, 32, 32>(ws, wts, g, ep, count, s);
+    if (done) return hipGetLastError();
+  } else if (g.Ncols <= 64) {
+    if (launch_halo_t<128, 64, 64, 32>(ws, wts, g, ep, count, s)) return hipGetLastError();
+  }
+  if (g.Ncols > 64) {
+    // (measured slower for the 128-wide layers: 128 x 64 wave tiles in blocks of two wavefronts, and 256 x 128 blocks)
     const bool done = g.Ncols % 256 == 0 ? launch_halo_t<128, 256, 128, 64>(ws, wts, g, ep, count, s)
                                          : launch_halo_t<128, 128, 64, 64>(ws, wts, g, ep, count, s);
     if (done) return hipGetLastError();
