@@ -230,8 +230,8 @@ def bench_net(args, cfg_id):
 
 
 def bench_calc(args, cfg_id):
-    """calcGradient alone (the learners' half of the path): all lambda learners of BASELINE config 3 or 4 on the
-    current weights in ONE batched call per step; no server update inside the timed region."""
+    """calcGradient alone (the learners' half of the path): all lambda learners of BASELINE config 3 or 4 in ONE
+    batched call per step; no server update inside the timed region."""
     import torch
     import workloads as wl
     from paper_1511_05950_amd import binding
@@ -242,13 +242,25 @@ def bench_calc(args, cfg_id):
     torch.cuda.set_device(dev)
     X = torch.randn((lam * mu,) + net["input"], device=dev, generator=torch.Generator(device=dev).manual_seed(cfg_id))
     Y = torch.randint(0, net["classes"], (lam * mu,), device=dev, dtype=torch.int32)
-    ctx = binding.Sasgd(lam, mu, lam, 1, net=net["name"], compute=cfg["compute"], init_weights=cfg["weights"]())
+    # 1-softsync (config 3): every learner pulls the version the last update made.  lambda-softsync (config 4): each
+    # learner holds a weight version of its own, as it does when gradients are applied one at a time; the versions
+    # are made here by lambda updates with a zero gradient (weight decay alone moves them).
+    distinct = cfg["n"] > 1
+    ctx = binding.Sasgd(lam, mu, lam, lam + 1 if distinct else 1, net=net["name"], compute=cfg["compute"], init_weights=cfg["weights"](),
+                        alpha0=cfg["alpha0"], momentum=cfg["momentum"], weight_decay=cfg["weight_decay"])
     learners = list(range(lam))
+    if distinct:
+        zero = torch.zeros(ctx.P, device=dev)
+        for _ in range(lam):
+            ctx.pushGradientExternal(zero, ctx.timestamp())
+            ctx.sumGradients()
+            ctx.applyUpdate()
+        del zero
 
     def step():
         for L in learners:
             ctx.getMinibatch(L, X[L * mu:(L + 1) * mu], Y[L * mu:(L + 1) * mu])
-            ctx.pullWeights(L, 0)
+            ctx.pullWeights(L, L if distinct else 0)
         ctx.calcGradient(learners)
 
     for _ in range(args.warmup):
@@ -272,7 +284,9 @@ def bench_calc(args, cfg_id):
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(dt / args.steps * 1e3, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "calcGradient only, shapes of BASELINE config %d: %s net, %d learners x mu=%d in one batched call, "
-                               "bf16 compute" % (cfg_id, net["name"], lam, mu), "num_params": P},
+                               "bf16 compute, %s" % (cfg_id, net["name"], lam, mu,
+                                                     "one weight version per learner" if distinct else "all learners on one weight version"),
+                   "num_params": P},
         "roofline": {"bound": "mfma", "kernel": "calcGradient (all launches of one batched call of %d learners)" % lam,
                      "achieved": round(ach, 2), "peak": 2500.0, "unit": "TFLOP/s", "frac": round(ach / 2500.0, 5),
                      "traffic": None, "avg_call_us": round(ms_g / n_g * 1e3, 1), "learners_per_call": lam},

@@ -717,10 +717,27 @@ __global__ __launch_bounds__(NT, (WM * WN > 64 * 64 ? 2 : 1)) void igemm_frag_ke
 //   a band of (its output rows in the tile) + ks - 1 input rows, so the row of (gr, kh) is
 //   (gr - gr_lo) + kh + (ks - 1)(n - n_lo);  patch columns: OW + ks - 1 = W + 2 pad.
 // The contraction may be split over channel chunks (g.splits <= C / 32).
+// Workgroups are handed to the eight XCDs round-robin in launch order, and each XCD has its own L2.  This turns the
+// launch-order index around so that every XCD works through one contiguous eighth of the (x, y, z) tile space: tiles
+// that share filter fragments and halo rows then share an L2 instead of being spread over all eight.
+struct TileIdx { int x, y, z; };
+__device__ __forceinline__ TileIdx xcd_tile(int on) {
+  uint32_t lin = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);
+  const uint32_t per = (gridDim.x * gridDim.y * gridDim.z) >> 3;
+  if (on && lin < per * 8u) lin = (lin & 7u) * per + (lin >> 3);   // the last (count mod 8) workgroups keep their place
+  TileIdx t;
+  const uint32_t q = lin / gridDim.x;
+  t.x = (int)(lin - q * gridDim.x);
+  t.z = (int)(q / gridDim.y);
+  t.y = (int)(q - (uint32_t)t.z * gridDim.y);
+  return t;
+}
+
 struct HaloArgs {
   int PW;              // patch width in pixels
   uint32_t mg_pw;      // multiplier for division by PW
   int n_px_max;        // pixels the LDS patch has room for
+  int xcd;             // 1: XCD-contiguous tile order (see xcd_tile)
   int tab_off;         // bytes from the start of LDS to the pixel table (behind the patch, rounded up to whole refill rounds)
 };
 
@@ -734,12 +751,13 @@ __global__ __launch_bounds__(64 * (BM / WM) * (BN / WN), (WM * WN > 64 * 64 ? 2 
   bf16_t* lds = halo_lds;
   int* tab = reinterpret_cast<int*>(reinterpret_cast<char*>(lds) + h.tab_off);   // byte offset of every patch pixel in the tensor
 
-  const int z = blockIdx.z / g.splits, sp = blockIdx.z % g.splits;
+  const TileIdx tile = xcd_tile(h.xcd);
+  const int z = tile.z / g.splits, sp = tile.z % g.splits;
   const bf16_t* act = (const bf16_t*)ws.p[z] + g.a_off;
   const bf16_t* Bf = (const bf16_t*)wts.p[z] + g.b_off;
   const __amdgpu_buffer_rsrc_t rsrc_a = __builtin_amdgcn_make_buffer_rsrc((void*)act, 0, (int)g.a_bytes, 0x00020000);
   const __amdgpu_buffer_rsrc_t rsrc_b = __builtin_amdgcn_make_buffer_rsrc((void*)Bf, 0, (int)g.b_bytes, 0x00020000);
-  const int m0 = blockIdx.x * BM, n0 = blockIdx.y * BN;
+  const int m0 = tile.x * BM, n0 = tile.y * BN;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm0 = (wave / WAVES_N) * WM, wn0 = (wave % WAVES_N) * WN;
   const int KB16 = g.ldb / 16;
@@ -1025,12 +1043,13 @@ static void launch_frag_t(const PtrTab& ws, const CPtrTab& wts, const IGemm& g, 
 // The patch-in-LDS kernel applies to windows larger than 1 x 1 over a multiple of 32 channels whose patch (plus the
 // pixel table, 84 bytes per pixel) fits 64 KiB of LDS; the contraction is split at most once per channel chunk.
 template <int BM, int BN, int WM, int WN>
-static bool launch_halo_t(const PtrTab& ws, const CPtrTab& wts, const IGemm& g_in, const Epilogue& ep, int count, hipStream_t s) {
+static bool launch_halo_t(const PtrTab& ws, const CPtrTab& wts, const IGemm& g_in, const Epilogue& ep, int count, bool xcd_order, hipStream_t s) {
   if (g_in.ks < 2 || g_in.C % 32 || g_in.OW + g_in.ks - 1 != g_in.W + 2 * g_in.pad) return false;
   IGemm g = g_in;
   g.splits = std::min(g.splits, g.C / 32);
   HaloArgs h;
   h.PW = g.OW + g.ks - 1;
+  h.xcd = xcd_order ? 1 : 0;
   h.mg_pw = magic_u32(h.PW);
   const int rows = (BM + g.OW - 2) / g.OW + 1;               // output rows a tile of BM positions can touch
   const int images = (rows + g.OH - 2) / g.OH + 1;           // and images those rows can belong to
@@ -1053,20 +1072,30 @@ static bool launch_halo_t(const PtrTab& ws, const CPtrTab& wts, const IGemm& g_i
 
 hipError_t launch_igemm_frag(const PtrTab& ws, const CPtrTab& wts, const IGemm& g, const Epilogue& ep, int count, hipStream_t s) {
   if (g.C % 8 || g.ldb % 32 || g.splits < 1) return hipErrorInvalidValue;
+  // own: most learners of this call read a weight version of their own (lambda-softsync) rather than a shared one
+  int same = 0;
+  for (int k = 1; k < count; k++) same += wts.p[k] == wts.p[0] ? 1 : 0;
+  const bool own = count > 1 && 2 * same < count;
   // Narrow layers: 256-row tiles (64 x 32 per wavefront) once there are enough of them to fill the chip, else 128 rows.
   // Measured on the CIFAR-shaped layers (18 learners x 128 images): 5x5 over 32 channels, 16x16 images, 39 us against
   // 46 us with 128-row tiles and 68 us for the tap-by-tap gather; 8x8 images 27 us against 33 us and 43 us.
   if (g.Ncols <= 32) {
     const bool many = (int64_t)((g.M + 255) / 256) * count >= 1024;
-    const bool done = many ? launch_halo_t<256, 32, 64, 32>(ws, wts, g, ep, count, s) : launch_halo_t<128, 32, 32, 32>(ws, wts, g, ep, count, s);
+    const bool done = many ? launch_halo_t<256, 32, 64, 32>(ws, wts, g, ep, count, own, s) : launch_halo_t<128, 32, 32, 32>(ws, wts, g, ep, count, own, s);
     if (done) return hipGetLastError();
   } else if (g.Ncols <= 64) {
-    if (launch_halo_t<128, 64, 64, 32>(ws, wts, g, ep, count, s)) return hipGetLastError();
+    if (launch_halo_t<128, 64, 64, 32>(ws, wts, g, ep, count, own, s)) return hipGetLastError();
   }
   if (g.Ncols > 64) {
     // (measured slower for the 128-wide layers: 128 x 64 wave tiles in blocks of two wavefronts, and 256 x 128 blocks)
-    const bool done = g.Ncols % 256 == 0 ? launch_halo_t<128, 256, 128, 64>(ws, wts, g, ep, count, s)
-                                         : launch_halo_t<128, 128, 64, 64>(ws, wts, g, ep, count, s);
+    // Learners on one weight version share their filter fragments in every L2 and 128-row tiles spread over all XCDs
+    // are fastest (conv3 forward, 18 learners: 89 us; 101 us with the XCD-contiguous order, 105 us with 256 rows).  With
+    // a version per learner the fragments are the larger part of a workgroup's traffic: 256-row tiles read them half as
+    // often and the XCD-contiguous order keeps a learner's tiles on one L2 (101 us against 120 us).  Also measured
+    // slower in both cases: 128 x 64 wave tiles in two-wavefront blocks, eight-wavefront 256 x 128 blocks, 256 x 256.
+    const bool done = g.Ncols % 256 == 0 ? launch_halo_t<128, 256, 128, 64>(ws, wts, g, ep, count, own, s)
+                      : own && g.Ncols > 128 ? launch_halo_t<256, 128, 128, 64>(ws, wts, g, ep, count, own, s)
+                                             : launch_halo_t<128, 128, 64, 64>(ws, wts, g, ep, count, own, s);
     if (done) return hipGetLastError();
   }
   // Wave tile 128 x 64 (two wavefronts per SIMD, accumulators in ordinary registers) wins where the columns fill

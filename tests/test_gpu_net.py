@@ -470,3 +470,34 @@ def test_more_fully_connected_layers_than_the_factor_table_holds():
     assert np.abs(res[1][2]).max() > 0
     assert rel(res[0][2], res[1][2]) < 1e-5
     assert rel(res[0][1] - w0, res[1][1] - w0) < 1e-5
+
+
+def test_learners_on_different_weight_versions_in_one_call():
+    # two learners of one batched call hold different versions: every kernel must read each learner's own filters
+    # (the convolution kernels also choose other tile shapes and another tile order in this case)
+    from paper_1511_05950_amd import binding
+    net, mu = TINY["patch_5x5"], 3
+    rng = np.random.default_rng(90)
+    P = wl.num_params(net)
+    theta0 = (rng.standard_normal(P) * 0.3).astype(np.float32)
+    X = wl.images(net, 2 * mu, 91)
+    Y = wl.labels(net, 2 * mu, 92)
+    Xd, Yd = torch.from_numpy(X).cuda(), torch.from_numpy(Y).cuda()
+    push = torch.from_numpy((rng.standard_normal(P) * 0.5).astype(np.float32)).cuda()
+    ctx = binding.Sasgd(2, mu, 2, 3, net=net, compute="bf16", alpha0=0.1, init_weights=theta0)
+    ctx.getMinibatch(0, Xd[:mu], Yd[:mu])
+    ctx.pullWeights(0, 0)
+    ctx.pushGradientExternal(push, 0)
+    ctx.sumGradients()
+    ctx.applyUpdate()
+    theta1 = ctx.copyWeights()
+    assert rel(theta1, theta0) > 1e-2
+    ctx.getMinibatch(1, Xd[mu:], Yd[mu:])
+    ctx.pullWeights(1, 0)
+    ctx.calcGradient([0, 1])
+    for L, th in ((0, theta0), (1, theta1)):
+        g = ctx.copyGradient(L)
+        _, rg = cnn.loss_and_gradient(net, th, X[L * mu:(L + 1) * mu], Y[L * mu:(L + 1) * mu], round_bf16=True)
+        worst, errs = layer_errors(net, g, rg)
+        assert worst < TOL["bf16"], (L, errs)
+    ctx.destroy()
