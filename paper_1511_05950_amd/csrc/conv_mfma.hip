@@ -1171,6 +1171,13 @@ static bool launch_halo_t(const PtrTab& ws, const CPtrTab& wts, const IGemm& g_i
   if (g_in.ks < 2 || g_in.C % 32 || g_in.OW + g_in.ks - 1 != g_in.W + 2 * g_in.pad) return false;
   IGemm g = g_in;
   g.splits = std::min(g.splits, g.C / 32);
+  {
+    // a two-way split that the tiles nearly fill the chip without is not worth its second pass (conv5 forward of the
+    // AlexNet shape at 18 learners, 396 tiles on 512 places: 92 us unsplit against 104 + 25 us)
+    const int64_t tiles = (int64_t)((g.M + BM - 1) / BM) * ((g.Ncols + BN - 1) / BN) * count;
+    const int64_t places = 256 * (WM * WN > 64 * 64 ? 2 : 3);
+    if (g.splits == 2 && tiles * 10 >= places * 6) g.splits = 1;
+  }
   HaloArgs h;
   h.PW = g.OW + g.ks - 1;
   h.xcd = xcd_order ? 1 : 0;
@@ -1234,13 +1241,18 @@ hipError_t launch_igemm_frag(const PtrTab& ws, const CPtrTab& wts, const IGemm& 
   return hipGetLastError();
 }
 
-hipError_t launch_igemm(const PtrTab& ws, const CPtrTab& wts, const IGemm& g, const Epilogue& ep, bool b_transposed, int count,
+hipError_t launch_igemm(const PtrTab& ws, const CPtrTab& wts, const IGemm& g_in, const Epilogue& ep, bool b_transposed, int count,
                         hipStream_t s) {
+  const IGemm& g = g_in;
   if (g.C % 8 || g.ldb % 8 || (b_transposed && g.Ncols % 8) || g.splits < 1) return hipErrorInvalidValue;
   if (!b_transposed && g.M <= 32 && g.ks == 1 && g.H == 1 && g.W == 1 && g.C % FCK == 0 && g.ldb == g.C && g.Ncols % 8 == 0 &&
       (int64_t)g.Ncols * g.ldb * 2 < ((int64_t)1 << 31) && !ep.use_mask) {
     // a fully connected layer on one learner's small mini-batch: the weight-streaming kernel (fc6 of the AlexNet shape,
     // 18 learners with a weight version each: 257 us = 5.3 TB/s against 290 us with the generic tile kernel)
+    // the split was chosen for 128-unit tiles; with 32 units per workgroup fewer copies (often none) fill the chip
+    IGemm g = g_in;
+    const int64_t blocks = (int64_t)((g.Ncols + 31) / 32) * count;
+    g.splits = (int)std::max<int64_t>(1, std::min<int64_t>(g.splits, (1024 + blocks - 1) / blocks));
     hipLaunchKernelGGL(fc_rows_kernel, dim3((unsigned)((g.Ncols + 31) / 32), 1, (unsigned)(count * g.splits)), dim3(256), 0, s, ws, wts, g, ep);
     if (g.splits > 1) {
       int64_t total = ((int64_t)g.M * g.Ncols) >> 2;
@@ -1283,10 +1295,11 @@ __global__ __launch_bounds__(256) void igemm_wgrad_kernel(PtrTab ws, PtrTab grad
   constexpr int A_ELEMS = BK * LDT_A, B_ELEMS = BK * LDT_B;
   __shared__ __attribute__((aligned(16))) bf16_t lds[2 * (A_ELEMS + B_ELEMS)];
 
-  const int z = blockIdx.z / g.splits, sp = blockIdx.z % g.splits;
+  const TileIdx tile = xcd_tile(1);   // a learner's tiles share dy and x: keep them on one XCD's L2 (AlexNet layers 3-9 % faster)
+  const int z = tile.z / g.splits, sp = tile.z % g.splits;
   const bf16_t* x = (const bf16_t*)ws.p[z] + g.a_off;
   const bf16_t* dy = (const bf16_t*)ws.p[z] + dy_off;
-  const int n0 = blockIdx.x * BMG, k0 = blockIdx.y * BNG;   // output-channel and im2col-column origins
+  const int n0 = tile.x * BMG, k0 = tile.y * BNG;           // output-channel and im2col-column origins
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm0 = (wave / WAVES_NG) * WMG, wn0 = (wave % WAVES_NG) * WNG;
 
