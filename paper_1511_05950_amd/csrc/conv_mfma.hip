@@ -972,7 +972,8 @@ __global__ __launch_bounds__(256) void igemm_finish_kernel(PtrTab ws, CPtrTab wt
   const uint32_t total4 = (uint32_t)(((int64_t)g.M * g.Ncols) >> 2);
   for (uint32_t o4 = blockIdx.x * 256 + threadIdx.x; o4 < total4; o4 += gridDim.x * 256) {
     float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-    for (int sp = 0; sp < g.splits; sp++) {
+#pragma unroll 4
+    for (int sp = 0; sp < g.splits; sp++) {   // loads of several splits in flight; the additions keep split order
       const float4 p = part[(size_t)sp * total4 + o4];
       v.x += p.x; v.y += p.y; v.z += p.z; v.w += p.w;
     }
@@ -1150,7 +1151,14 @@ static void launch_igemm_t(const PtrTab& ws, const CPtrTab& wts, const IGemm& g,
 }
 
 template <int BM, int BN, int WM, int WN>
-static void launch_frag_t(const PtrTab& ws, const CPtrTab& wts, const IGemm& g, const Epilogue& ep, int count, hipStream_t s) {
+static void launch_frag_t(const PtrTab& ws, const CPtrTab& wts, const IGemm& g_in, const Epilogue& ep, int count, hipStream_t s) {
+  IGemm g = g_in;
+  {
+    // a two-way split that the tiles nearly fill the chip without is not worth its second pass
+    const int64_t tiles = (int64_t)((g.M + BM - 1) / BM) * ((g.Ncols + BN - 1) / BN) * count;
+    const int64_t places = 256 * (WM * WN > 64 * 64 ? 2 : 3);
+    if (g.splits == 2 && tiles * 10 >= places * 6) g.splits = 1;
+  }
   dim3 grid((unsigned)((g.M + BM - 1) / BM), (unsigned)((g.Ncols + BN - 1) / BN), (unsigned)(count * g.splits));
   constexpr int NT = 64 * (BM / WM) * (BN / WN);
   const bool uni = g.CPT % 4 == 0 && g.ks * g.ks <= 32 && g.Kchunks % 4 == 0;
@@ -1552,6 +1560,7 @@ __global__ __launch_bounds__(256) void wgrad_finish_kernel(PtrTab ws, PtrTab gra
       const int tap = idx / cw, cc = idx - tap * cw;
       const int k = tap * g.C + c_lo + cc;
       float acc = 0.f;
+#pragma unroll 8
       for (int sp = 0; sp < g.splits; sp++) acc += part[sp * split_stride + k];
       row[idx] = acc;
     }
@@ -1570,6 +1579,7 @@ __global__ __launch_bounds__(256) void wgrad_finish_kernel(PtrTab ws, PtrTab gra
   const int64_t dst = filter_src(v, 0, tap, cp);          // position inside one filter, or -1 for padding
   if (dst < 0) return;
   float acc = 0.f;
+#pragma unroll 8
   for (int sp = 0; sp < g.splits; sp++) acc += part[sp * split_stride + k];
   dw[dst] = acc;
 }
