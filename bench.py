@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the staleness-aware n-softsync ASGD hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload server|cifar|alex|cifar-fp32-c4|cifar-fp32-c1|alex-calc|cifar-calc]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload server|cifar|alex|cifar-fp32-c4|cifar-fp32-c1|alex-calc|alex-calc-shared|cifar-calc]
 
 Default workload "server" is BASELINE config 1, the parameter-server microbenchmark: P = 60 M fp32
 parameters, lambda = 54 gradients resident in HBM, momentum 0.9, weight decay 5e-4.  One step consumes every
@@ -10,7 +10,8 @@ learner's gradient once in each of the two protocols the config names:
      1-softsync:  1 sumGradients+applyUpdate with c = 54              (232 B per parameter)
 The printed value is algorithmic HBM bytes (4 (c + 4) per parameter and update) over wall time of the step.
 The other workloads run the whole path (calcGradient + sumGradients + applyUpdate) on BASELINE configs 3, 4, 0, 2;
-"alex-calc" / "cifar-calc" time calcGradient alone with all lambda learners in one batched call.
+"alex-calc" / "cifar-calc" time calcGradient alone with all lambda learners in one batched call (alex-calc: every
+learner on a weight version of its own, as under lambda-softsync; alex-calc-shared: all on one version).
 Prints ONE JSON line.
 """
 import argparse
@@ -229,7 +230,7 @@ def bench_net(args, cfg_id):
     return out
 
 
-def bench_calc(args, cfg_id):
+def bench_calc(args, cfg_id, shared=False):
     """calcGradient alone (the learners' half of the path): all lambda learners of BASELINE config 3 or 4 in ONE
     batched call per step; no server update inside the timed region."""
     import torch
@@ -245,7 +246,7 @@ def bench_calc(args, cfg_id):
     # 1-softsync (config 3): every learner pulls the version the last update made.  lambda-softsync (config 4): each
     # learner holds a weight version of its own, as it does when gradients are applied one at a time; the versions
     # are made here by lambda updates with a zero gradient (weight decay alone moves them).
-    distinct = cfg["n"] > 1
+    distinct = cfg["n"] > 1 and not shared
     ctx = binding.Sasgd(lam, mu, lam, lam + 1 if distinct else 1, net=net["name"], compute=cfg["compute"], init_weights=cfg["weights"](),
                         alpha0=cfg["alpha0"], momentum=cfg["momentum"], weight_decay=cfg["weight_decay"])
     learners = list(range(lam))
@@ -316,6 +317,8 @@ def main():
         out = bench_net(args, {"cifar": 3, "alex": 4, "cifar-fp32-c4": 0, "cifar-fp32-c1": 2}[args.workload])
     elif args.workload in ("cifar-calc", "alex-calc"):
         out = bench_calc(args, {"cifar-calc": 3, "alex-calc": 4}[args.workload])
+    elif args.workload == "alex-calc-shared":      # all learners on one weight version (what 1-softsync would give)
+        out = bench_calc(args, 4, shared=True)
     else:
         raise SystemExit("unknown workload " + args.workload)
     print(json.dumps(out))
