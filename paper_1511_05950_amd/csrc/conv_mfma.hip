@@ -1342,8 +1342,8 @@ __global__ __launch_bounds__(256) void fc_rows_kernel(PtrTab ws, CPtrTab wts, IG
   }
 }
 
-int choose_splits(int64_t tiles, int count, int steps, size_t bytes_per_split, size_t scratch_bytes) {
-  const int64_t target = 600;   // workgroups wanted per launch; 256..1024 measured, flat between 400 and 768 at 6 and 18 learners
+int choose_splits(int64_t tiles, int count, int steps, size_t bytes_per_split, size_t scratch_bytes, int64_t target) {
+  // target = workgroups wanted per launch; 600 by default (256..1024 measured, flat between 400 and 768 at 6 and 18 learners)
   int64_t sp = (target + tiles * count - 1) / (tiles * count);
   if (sp > steps / 4) sp = steps / 4;                // keep at least four contraction steps per workgroup
   if (bytes_per_split > 0 && (int64_t)(scratch_bytes / bytes_per_split) < sp) sp = (int64_t)(scratch_bytes / bytes_per_split);

@@ -132,7 +132,7 @@ hipError_t launch_igemm(const PtrTab& ws, const CPtrTab& wts, const IGemm& g, co
 hipError_t launch_igemm_wgrad(const PtrTab& ws, const PtrTab& grads, const IGemm& g, const VConv& v, size_t dy_off, int64_t w_off,
                               int64_t b_off, int count, hipStream_t s);
 // Split choice: enough workgroups for the chip, bounded by the contraction length and the scratch size.
-int choose_splits(int64_t tiles, int count, int steps, size_t bytes_per_split, size_t scratch_bytes);
+int choose_splits(int64_t tiles, int count, int steps, size_t bytes_per_split, size_t scratch_bytes, int64_t target = 600);
 
 // y = conv(x, w) + b, optional ReLU.  w_off / b_off: element offsets into the learner's flat weight vector.
 // out_f32: y is stored as fp32 whatever T is (class scores).
