@@ -48,8 +48,10 @@ __global__ __launch_bounds__(256) void conv_fwd_simple_kernel(PtrTab ws, CPtrTab
   }
 }
 
-// Fully connected forward with a long contraction: one wavefront per output element, lanes stride over the
-// inputs (both operands contiguous), butterfly sum.  Same result order for every launch shape.
+// Fully connected forward with a long contraction: one wavefront per image and group of kFcKU output units, lanes
+// stride over the inputs (both operands contiguous; x is read once for the group), butterfly sums.  Every output is
+// the same chain of operations whatever the launch shape.
+constexpr int kFcKU = 8;
 template <typename T>
 __global__ __launch_bounds__(256) void fc_fwd_wave_kernel(PtrTab ws, CPtrTab wts, size_t x_off, size_t y_off, int64_t w_off,
                                                           int64_t b_off, int N, int C, int K, int relu, int out_f32) {
@@ -57,20 +59,56 @@ __global__ __launch_bounds__(256) void fc_fwd_wave_kernel(PtrTab ws, CPtrTab wts
   T* y = (T*)ws.p[blockIdx.z] + y_off;
   const T* w = (const T*)wts.p[blockIdx.z] + w_off;
   const T* b = (const T*)wts.p[blockIdx.z] + b_off;
-  const int o = blockIdx.x * 4 + (threadIdx.x >> 6);      // output element index n * K + k
+  const int groups = (K + kFcKU - 1) / kFcKU;
+  const int o = blockIdx.x * 4 + (threadIdx.x >> 6);      // (image, group of units)
   const int lane = threadIdx.x & 63;
-  if (o >= N * K) return;
-  const int n = o / K, k = o - n * K;
+  if (o >= N * groups) return;
+  const int n = o / groups, k0 = (o - n * groups) * kFcKU;
   const T* xp = x + (int64_t)n * C;
-  const T* wp = w + (int64_t)k * C;
-  float acc = 0.f;
-  for (int c = lane; c < C; c += 64) acc = fmaf(ldf(xp + c), ldf(wp + c), acc);
-  acc = wave_sum(acc) + ldf(b + k);
-  if (relu) acc = fmaxf(acc, 0.f);
-  if (lane == 0) {
-    if (out_f32) reinterpret_cast<float*>(y)[o] = acc;
-    else stf(y + o, acc);
+  const T* wp[kFcKU];
+#pragma unroll
+  for (int u = 0; u < kFcKU; u++) wp[u] = w + (int64_t)min(k0 + u, K - 1) * C;   // units beyond K repeat the last one and are not stored
+  float acc[kFcKU];
+#pragma unroll
+  for (int u = 0; u < kFcKU; u++) acc[u] = 0.f;
+  for (int c = lane; c < C; c += 64) {
+    const float xv = ldf(xp + c);
+#pragma unroll
+    for (int u = 0; u < kFcKU; u++) acc[u] = fmaf(xv, ldf(wp[u] + c), acc[u]);
   }
+#pragma unroll
+  for (int u = 0; u < kFcKU; u++) {
+    const int k = k0 + u;
+    float v = wave_sum(acc[u]);
+    if (k >= K) continue;
+    v += ldf(b + k);
+    if (relu) v = fmaxf(v, 0.f);
+    if (lane == 0) {
+      if (out_f32) reinterpret_cast<float*>(y)[(int64_t)n * K + k] = v;
+      else stf(y + (int64_t)n * K + k, v);
+    }
+  }
+}
+
+// Input gradient of a fully connected layer (1 x 1 window on a 1 x 1 image): dx[n][c] = sum_k dy[n][k] w[k][c], one
+// thread per element, neighbouring lanes on neighbouring c; 32-bit index arithmetic.
+template <typename T>
+__global__ __launch_bounds__(256) void fc_dgrad_simple_kernel(PtrTab ws, CPtrTab wts, size_t dy_off, size_t dx_off, int64_t w_off, int N, int C,
+                                                              int K, int use_mask, size_t mask_off) {
+  const T* dy = (const T*)ws.p[blockIdx.z] + dy_off;
+  T* dx = (T*)ws.p[blockIdx.z] + dx_off;
+  const T* mask = (const T*)ws.p[blockIdx.z] + mask_off;
+  const T* w = (const T*)wts.p[blockIdx.z] + w_off;
+  const uint32_t i = blockIdx.x * 256u + threadIdx.x;
+  if (i >= (uint32_t)N * (uint32_t)C) return;
+  const uint32_t n = i / (uint32_t)C, c = i - n * (uint32_t)C;
+  float acc = 0.f;
+  if (!use_mask || ldf(mask + i) > 0.f) {
+    const T* dp = dy + (size_t)n * K;
+#pragma unroll 4
+    for (int k = 0; k < K; k++) acc = fmaf(ldf(dp + k), ldf(w + (size_t)k * C + c), acc);
+  }
+  stf(dx + i, acc);
 }
 
 // ------------------------------------------------------------------ input gradient
@@ -157,25 +195,40 @@ __global__ __launch_bounds__(256) void conv_wgrad_simple_kernel(PtrTab ws, PtrTa
 }
 
 // Fully connected layer (1 x 1 window on a 1 x 1 input): dW[k][c] = sum_n dy[n][k] x[n][c].  One thread per input
-// unit c and one workgroup row per output unit k: neighbouring lanes read neighbouring x, dy[n][k] is a broadcast.
-// The thread of c = 0 also accumulates the bias gradient.
+// unit c, one-wavefront workgroups, one workgroup row per kFcWU output units: neighbouring lanes read neighbouring
+// x, dy[n][k] is a broadcast.  The thread of c = 0 also accumulates the bias gradients.
+constexpr int kFcWU = 4;     // output units per wavefront in fc_wgrad_simple_kernel: x is read once for them
 template <typename T>
-__global__ __launch_bounds__(256) void fc_wgrad_simple_kernel(PtrTab ws, PtrTab grads, size_t x_off, size_t dy_off, int64_t w_off,
-                                                              int64_t b_off, int N, int C, int K) {
+__global__ __launch_bounds__(64) void fc_wgrad_simple_kernel(PtrTab ws, PtrTab grads, size_t x_off, size_t dy_off, int64_t w_off,
+                                                             int64_t b_off, int N, int C, int K) {
   const T* x = (const T*)ws.p[blockIdx.z] + x_off;
   const T* dy = (const T*)ws.p[blockIdx.z] + dy_off;
   float* dw = (float*)grads.p[blockIdx.z] + w_off;
   float* db = (float*)grads.p[blockIdx.z] + b_off;
-  const int c = blockIdx.x * 256 + threadIdx.x, k = blockIdx.y;
+  const int c = blockIdx.x * 64 + threadIdx.x, k0 = blockIdx.y * kFcWU;
   if (c >= C) return;
-  float acc = 0.f, bsum = 0.f;
-  for (int n = 0; n < N; n++) {
-    const float d = ldf(dy + (int64_t)n * K + k);
-    acc = fmaf(d, ldf(x + (int64_t)n * C + c), acc);
-    bsum += d;
+  int ku[kFcWU];
+#pragma unroll
+  for (int u = 0; u < kFcWU; u++) ku[u] = min(k0 + u, K - 1);               // units beyond K repeat the last one and are not stored
+  float acc[kFcWU], bsum[kFcWU];
+#pragma unroll
+  for (int u = 0; u < kFcWU; u++) acc[u] = bsum[u] = 0.f;
+#pragma unroll 8
+  for (int n = 0; n < N; n++) {                                             // loads of several images in flight; sums stay in image order
+    const float xv = ldf(x + (int64_t)n * C + c);
+#pragma unroll
+    for (int u = 0; u < kFcWU; u++) {
+      const float d = ldf(dy + (int64_t)n * K + ku[u]);
+      acc[u] = fmaf(d, xv, acc[u]);
+      bsum[u] += d;
+    }
   }
-  dw[(int64_t)k * C + c] = acc;
-  if (c == 0) db[k] = bsum;
+#pragma unroll
+  for (int u = 0; u < kFcWU; u++) {
+    if (k0 + u >= K) continue;
+    dw[(int64_t)(k0 + u) * C + c] = acc[u];
+    if (c == 0) db[k0 + u] = bsum[u];
+  }
 }
 
 static inline dim3 grid1(int64_t total, int count) {
@@ -189,7 +242,7 @@ hipError_t launch_conv_fwd_simple(bool is_bf16, const PtrTab& ws, const CPtrTab&
                                   int64_t b_off, const ConvShape& sh, bool relu, bool out_f32, int count, hipStream_t s) {
   int r = relu ? 1 : 0, of = out_f32 ? 1 : 0;
   if (sh.ks == 1 && sh.H == 1 && sh.W == 1 && sh.C >= 256 && (int64_t)sh.N * sh.K < (1 << 22)) {
-    dim3 gw((unsigned)(((int64_t)sh.N * sh.K + 3) / 4), 1, (unsigned)count);
+    dim3 gw((unsigned)(((int64_t)sh.N * ((sh.K + kFcKU - 1) / kFcKU) + 3) / 4), 1, (unsigned)count);
     if (is_bf16) hipLaunchKernelGGL(fc_fwd_wave_kernel<bf16_t>, gw, dim3(256), 0, s, ws, wts, x_off, y_off, w_off, b_off, sh.N, sh.C, sh.K, r, of);
     else hipLaunchKernelGGL(fc_fwd_wave_kernel<float>, gw, dim3(256), 0, s, ws, wts, x_off, y_off, w_off, b_off, sh.N, sh.C, sh.K, r, of);
     return hipGetLastError();
@@ -202,8 +255,14 @@ hipError_t launch_conv_fwd_simple(bool is_bf16, const PtrTab& ws, const CPtrTab&
 
 hipError_t launch_conv_dgrad_simple(bool is_bf16, const PtrTab& ws, const CPtrTab& wts, size_t dy_off, size_t dx_off, int64_t w_off,
                                     const ConvShape& sh, bool use_mask, size_t mask_off, int count, hipStream_t s) {
-  dim3 g = grid1((int64_t)sh.N * sh.H * sh.W * sh.C, count);
   int um = use_mask ? 1 : 0;
+  if (sh.ks == 1 && sh.H == 1 && sh.W == 1 && sh.OH == 1 && sh.OW == 1 && sh.pad == 0 && sh.stride == 1 && (int64_t)sh.N * sh.C < ((int64_t)1 << 31)) {
+    dim3 gf((unsigned)(((int64_t)sh.N * sh.C + 255) / 256), 1, (unsigned)count);
+    if (is_bf16) hipLaunchKernelGGL(fc_dgrad_simple_kernel<bf16_t>, gf, dim3(256), 0, s, ws, wts, dy_off, dx_off, w_off, sh.N, sh.C, sh.K, um, mask_off);
+    else hipLaunchKernelGGL(fc_dgrad_simple_kernel<float>, gf, dim3(256), 0, s, ws, wts, dy_off, dx_off, w_off, sh.N, sh.C, sh.K, um, mask_off);
+    return hipGetLastError();
+  }
+  dim3 g = grid1((int64_t)sh.N * sh.H * sh.W * sh.C, count);
   if (is_bf16) hipLaunchKernelGGL(conv_dgrad_simple_kernel<bf16_t>, g, dim3(256), 0, s, ws, wts, dy_off, dx_off, w_off, sh, um, mask_off);
   else hipLaunchKernelGGL(conv_dgrad_simple_kernel<float>, g, dim3(256), 0, s, ws, wts, dy_off, dx_off, w_off, sh, um, mask_off);
   return hipGetLastError();
@@ -212,9 +271,9 @@ hipError_t launch_conv_dgrad_simple(bool is_bf16, const PtrTab& ws, const CPtrTa
 hipError_t launch_conv_wgrad_simple(bool is_bf16, const PtrTab& ws, const PtrTab& grads, size_t x_off, size_t dy_off, int64_t w_off,
                                     int64_t b_off, const ConvShape& sh, int count, hipStream_t s) {
   if (sh.ks == 1 && sh.H == 1 && sh.W == 1 && sh.pad == 0 && sh.K <= 65535) {
-    dim3 g((unsigned)((sh.C + 255) / 256), (unsigned)sh.K, (unsigned)count);
-    if (is_bf16) hipLaunchKernelGGL(fc_wgrad_simple_kernel<bf16_t>, g, dim3(256), 0, s, ws, grads, x_off, dy_off, w_off, b_off, sh.N, sh.C, sh.K);
-    else hipLaunchKernelGGL(fc_wgrad_simple_kernel<float>, g, dim3(256), 0, s, ws, grads, x_off, dy_off, w_off, b_off, sh.N, sh.C, sh.K);
+    dim3 g((unsigned)((sh.C + 63) / 64), (unsigned)((sh.K + kFcWU - 1) / kFcWU), (unsigned)count);
+    if (is_bf16) hipLaunchKernelGGL(fc_wgrad_simple_kernel<bf16_t>, g, dim3(64), 0, s, ws, grads, x_off, dy_off, w_off, b_off, sh.N, sh.C, sh.K);
+    else hipLaunchKernelGGL(fc_wgrad_simple_kernel<float>, g, dim3(64), 0, s, ws, grads, x_off, dy_off, w_off, b_off, sh.N, sh.C, sh.K);
     return hipGetLastError();
   }
   const int64_t elems = (int64_t)sh.K * sh.C * sh.ks * sh.ks + sh.K;
