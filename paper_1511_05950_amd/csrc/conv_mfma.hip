@@ -1525,7 +1525,7 @@ hipError_t launch_igemm(const PtrTab& ws, const CPtrTab& wts, const IGemm& g_in,
   const IGemm& g = g_in;
   if (g.C % 8 || g.ldb % 8 || (b_transposed && g.Ncols % 8) || g.splits < 1) return hipErrorInvalidValue;
   if (!b_transposed && g.M <= 32 && g.ks == 1 && g.H == 1 && g.W == 1 && g.C % FCK == 0 && g.ldb == g.C && g.Ncols % 8 == 0 &&
-      (int64_t)g.Ncols * g.ldb * 2 < ((int64_t)1 << 31) && !ep.use_mask) {
+      (int64_t)g.Ncols * g.ldb * 2 < ((int64_t)1 << 31) && (int64_t)g.M * g.C * 2 < ((int64_t)1 << 31) && !ep.use_mask) {
     // a fully connected layer on one learner's small mini-batch: the weight-streaming kernel (fc6 of the AlexNet shape,
     // 18 learners with a weight version each: 257 us = 5.3 TB/s against 290 us with the generic tile kernel)
     // the split was chosen for 128-unit tiles; with 32 units per workgroup fewer copies (often none) fill the chip
