@@ -83,6 +83,8 @@ TINY = {
     # tile, 1 / 3 / 5 / 8 channel chunks, odd and even tap counts, both tile widths, forward and input gradient
     "patch_3x3": wl.tiny_net(3, 9, 8, 8, conv=((32, 3, 1, 1), (96, 3, 1, 1), (128, 3, 1, 0), (96, 2, 1, 1)), pool="maxpool", fc_hidden=24),
     "patch_5x5": wl.tiny_net(3, 10, 9, 8, conv=((64, 3, 1, 1), (256, 5, 1, 2), (160, 3, 1, 1), (256, 4, 1, 1)), pool="avgpool", fc_hidden=24),
+    # 16 and 48 input channels with 5 x 5 and 4 x 4 windows: the patch kernel that walks the filters' 16-k blocks
+    "patch_c16": wl.tiny_net(3, 12, 11, 8, conv=((16, 3, 1, 1), (48, 5, 1, 2), (96, 4, 1, 1), (40, 5, 1, 2)), pool="maxpool", fc_hidden=24),
     "mfma_s4": wl.tiny_net(3, 39, 39, 8, conv=((24, 11, 4, 0), (40, 3, 1, 1), (136, 3, 1, 1)), pool="maxpool", fc_hidden=264),
 }
 
