@@ -503,3 +503,12 @@ def test_learners_on_different_weight_versions_in_one_call():
         worst, errs = layer_errors(net, g, rg)
         assert worst < TOL["bf16"], (L, errs)
     ctx.destroy()
+
+
+def test_patch_kernel_tiles_spanning_many_small_images():
+    # 3 x 3 feature maps: a 128-position tile covers 14 images, each with its own band of halo rows in the patch
+    net = wl.tiny_net(3, 5, 5, 6, conv=((32, 3, 1, 0), (64, 3, 1, 1), (96, 2, 1, 1)), pool="avgpool", fc_hidden=16)
+    for (g, rg, loss, rl) in one_gradient(net, 40, "bf16", seed=95, lam=2):
+        worst, errs = layer_errors(net, g, rg)
+        assert worst < TOL["bf16"], errs
+        assert abs(loss - rl) < 2e-2 * max(1.0, abs(rl))
