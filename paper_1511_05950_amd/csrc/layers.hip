@@ -298,6 +298,68 @@ __global__ __launch_bounds__(256) void pool_fwd_vec8_kernel(PtrTab ws, size_t x_
   }
 }
 
+// 3 x 3 windows (every pooling layer of the two reference networks): the nine 16-byte reads of a window are all
+// requested before the first is used (the general kernel above walks the window in a loop whose trip count the
+// compiler does not know, one dependent read after the other).  Same arithmetic and the same winner on ties.
+template <bool MAX>
+__global__ __launch_bounds__(256) void pool_fwd_3x3_kernel(PtrTab ws, size_t x_off, size_t y_off, size_t arg_byte_off, PoolShape sh, int relu) {
+  const bf16_t* x = (const bf16_t*)ws.p[blockIdx.z] + x_off;
+  bf16_t* y = (bf16_t*)ws.p[blockIdx.z] + y_off;
+  uint8_t* arg = (uint8_t*)ws.p[blockIdx.z] + arg_byte_off;
+  const int C8 = sh.C / 8;
+  const uint32_t total = (uint32_t)sh.N * sh.OH * sh.OW * C8;
+  for (uint32_t i = blockIdx.x * 256 + threadIdx.x; i < total; i += gridDim.x * 256) {
+    uint32_t r = i;
+    const int c8 = (int)(r % (uint32_t)C8);
+    r /= (uint32_t)C8;
+    const int ow = (int)(r % (uint32_t)sh.OW);
+    r /= (uint32_t)sh.OW;
+    const int oh = (int)(r % (uint32_t)sh.OH);
+    const int n = (int)(r / (uint32_t)sh.OH);
+    const int h0 = oh * sh.stride, w0 = ow * sh.stride;
+    const int nh = min(3, sh.H - h0), nw = min(3, sh.W - w0);          // rows and columns of the window inside the image
+    const bf16_t* base = x + (((int64_t)n * sh.H + h0) * sh.W + w0) * sh.C + c8 * 8;
+    bf8 v[9];
+#pragma unroll
+    for (int kh = 0; kh < 3; kh++)
+#pragma unroll
+      for (int kw = 0; kw < 3; kw++) {
+        const bool in = kh < nh && kw < nw;
+        v[kh * 3 + kw].v = *reinterpret_cast<const uint4*>(base + (in ? ((int64_t)kh * sh.W + kw) * sh.C : 0));   // outside: the first element again
+      }
+    float acc[8];
+    int best[8];
+#pragma unroll
+    for (int e = 0; e < 8; e++) { acc[e] = v[0].get(e); best[e] = 0; }
+#pragma unroll
+    for (int t = 1; t < 9; t++) {
+      const bool in = t / 3 < nh && t % 3 < nw;
+#pragma unroll
+      for (int e = 0; e < 8; e++) {
+        const float f = v[t].get(e);
+        if (MAX) {
+          if (in && f > acc[e]) { acc[e] = f; best[e] = t; }
+        } else {
+          if (in) acc[e] += f;
+        }
+      }
+    }
+    const float cnt = (float)(nh * nw);
+#pragma unroll
+    for (int e = 0; e < 8; e++) {
+      if (!MAX) acc[e] /= cnt;
+      if (relu) acc[e] = fmaxf(acc[e], 0.f);
+    }
+    *reinterpret_cast<uint4*>(y + (size_t)i * 8) = pack8(acc);
+    if (MAX) {
+      uint2 a;
+      a.x = (uint32_t)best[0] | ((uint32_t)best[1] << 8) | ((uint32_t)best[2] << 16) | ((uint32_t)best[3] << 24);
+      a.y = (uint32_t)best[4] | ((uint32_t)best[5] << 8) | ((uint32_t)best[6] << 16) | ((uint32_t)best[7] << 24);
+      *reinterpret_cast<uint2*>(arg + (size_t)i * 8) = a;
+    }
+  }
+}
+
 template <bool MAX>
 __global__ __launch_bounds__(256) void pool_bwd_vec8_kernel(PtrTab ws, size_t dy_off, size_t dx_off, size_t arg_byte_off, PoolShape sh,
                                                             int use_mask, size_t mask_off) {
@@ -448,6 +510,11 @@ hipError_t launch_pool_fwd(bool is_bf16, bool is_max, const PtrTab& ws, size_t x
   int r = relu ? 1 : 0;
   if (is_bf16 && sh.C % 8 == 0 && x_off % 8 == 0 && y_off % 8 == 0 && arg_byte_off % 8 == 0) {
     dim3 gv = grid_for((int64_t)sh.N * sh.OH * sh.OW * (sh.C / 8), count, 16384);
+    if (sh.ks == 3 && (int64_t)sh.N * sh.H * sh.W * sh.C < ((int64_t)1 << 31)) {
+      if (is_max) hipLaunchKernelGGL((pool_fwd_3x3_kernel<true>), gv, dim3(256), 0, s, ws, x_off, y_off, arg_byte_off, sh, r);
+      else hipLaunchKernelGGL((pool_fwd_3x3_kernel<false>), gv, dim3(256), 0, s, ws, x_off, y_off, arg_byte_off, sh, r);
+      return hipGetLastError();
+    }
     if (is_max) hipLaunchKernelGGL((pool_fwd_vec8_kernel<true>), gv, dim3(256), 0, s, ws, x_off, y_off, arg_byte_off, sh, r);
     else hipLaunchKernelGGL((pool_fwd_vec8_kernel<false>), gv, dim3(256), 0, s, ws, x_off, y_off, arg_byte_off, sh, r);
     return hipGetLastError();
