@@ -436,37 +436,66 @@ __global__ __launch_bounds__(256) void pool_bwd_3x3s2_kernel(PtrTab ws, size_t d
     r /= (uint32_t)WB;
     const int a = (int)(r % (uint32_t)HB);
     const int n = (int)(r / (uint32_t)HB);
+    // All reads are requested before the first is used: windows outside the output and block elements outside the
+    // input read a clamped (valid) address and are discarded by a predicate instead of a branch around the load.
+    bool w_ok[4];
+    uint4 dv[4];
+    uint2 av[4];
+    float inv[4];
+#pragma unroll
+    for (int wh = 0; wh < 2; wh++)
+#pragma unroll
+      for (int ww = 0; ww < 2; ww++) {
+        const int oh = a - 1 + wh, ow = b - 1 + ww;
+        const int q = 2 * wh + ww;
+        w_ok[q] = oh >= 0 && oh < sh.OH && ow >= 0 && ow < sh.OW;
+        const int ohc = min(max(oh, 0), sh.OH - 1), owc = min(max(ow, 0), sh.OW - 1);
+        const int64_t o = ((((int64_t)n * sh.OH + ohc) * sh.OW + owc) * C8 + c8) * 8;
+        dv[q] = *reinterpret_cast<const uint4*>(dy + o);
+        av[q] = make_uint2(0u, 0u);
+        if (MAX) av[q] = *reinterpret_cast<const uint2*>(arg + o);
+        inv[q] = 1.f;
+        if (!MAX) {
+          const int ch = min(ohc * 2 + 3, sh.H) - ohc * 2, cw = min(owc * 2 + 3, sh.W) - owc * 2;
+          inv[q] = 1.f / (float)(ch * cw);
+        }
+      }
+    bool x_ok[4];
+    int64_t xo[4];
+    uint4 mv[4];
+#pragma unroll
+    for (int dh = 0; dh < 2; dh++)
+#pragma unroll
+      for (int dw = 0; dw < 2; dw++) {
+        const int ih = 2 * a + dh, iw = 2 * b + dw;
+        const int q = 2 * dh + dw;
+        x_ok[q] = ih < sh.H && iw < sh.W;
+        xo[q] = ((((int64_t)n * sh.H + min(ih, sh.H - 1)) * sh.W + min(iw, sh.W - 1)) * C8 + c8) * 8;
+        mv[q] = make_uint4(0u, 0u, 0u, 0u);
+        if (use_mask) mv[q] = *reinterpret_cast<const uint4*>(mask + xo[q]);
+      }
     float acc[4][8];                                    // [2 * dh + dw][channel]
 #pragma unroll
     for (int q = 0; q < 4; q++)
 #pragma unroll
       for (int e = 0; e < 8; e++) acc[q][e] = 0.f;
 #pragma unroll
-    for (int wh = 0; wh < 2; wh++) {
-      const int oh = a - 1 + wh;
-      if (oh < 0 || oh >= sh.OH) continue;
+    for (int wh = 0; wh < 2; wh++)
 #pragma unroll
       for (int ww = 0; ww < 2; ww++) {
-        const int ow = b - 1 + ww;
-        if (ow < 0 || ow >= sh.OW) continue;
-        const int64_t o = ((((int64_t)n * sh.OH + oh) * sh.OW + ow) * C8 + c8) * 8;
+        const int wq = 2 * wh + ww;
         bf8 d;
-        d.v = *reinterpret_cast<const uint4*>(dy + o);
-        uint2 ar = make_uint2(0u, 0u);
-        if (MAX) ar = *reinterpret_cast<const uint2*>(arg + o);
-        float inv = 1.f;
-        if (!MAX) {
-          const int ch = min(oh * 2 + 3, sh.H) - oh * 2, cw = min(ow * 2 + 3, sh.W) - ow * 2;
-          inv = 1.f / (float)(ch * cw);
-        }
-        // window (oh, ow) starts at row 2 oh, column 2 ow: block row dh sits at window row 2 (a - oh) + dh
+        d.v = w_ok[wq] ? dv[wq] : make_uint4(0u, 0u, 0u, 0u);
+        const uint2 ar = av[wq];
+        // window (oh, ow) = (a - 1 + wh, b - 1 + ww) starts at row 2 oh, column 2 ow: block row dh sits at window row
+        // 2 (a - oh) + dh, i.e. 2, 3 for the window above (only 2 is inside), 0, 1 for the own one
 #pragma unroll
         for (int dh = 0; dh < 2; dh++) {
-          const int wr = 2 * (a - oh) + dh;             // 2, 3 for the window above (only 2 is inside), 0, 1 for the own one
+          const int wr = 2 * (1 - wh) + dh;
           if (wr > 2) continue;
 #pragma unroll
           for (int dw = 0; dw < 2; dw++) {
-            const int wc = 2 * (b - ow) + dw;
+            const int wc = 2 * (1 - ww) + dw;
             if (wc > 2) continue;
             const uint32_t pos = (uint32_t)(wr * 3 + wc);
 #pragma unroll
@@ -475,31 +504,23 @@ __global__ __launch_bounds__(256) void pool_bwd_3x3s2_kernel(PtrTab ws, size_t d
                 const uint32_t ae = ((e < 4 ? ar.x : ar.y) >> (8 * (e & 3))) & 0xffu;
                 if (ae == pos) acc[2 * dh + dw][e] += d.get(e);
               } else {
-                acc[2 * dh + dw][e] += d.get(e) * inv;
+                acc[2 * dh + dw][e] += d.get(e) * inv[wq];
               }
             }
           }
         }
       }
-    }
 #pragma unroll
-    for (int dh = 0; dh < 2; dh++) {
-      const int ih = 2 * a + dh;
-      if (ih >= sh.H) continue;
+    for (int q = 0; q < 4; q++) {
+      if (!x_ok[q]) continue;
+      if (use_mask) {
+        bf8 mk;
+        mk.v = mv[q];
 #pragma unroll
-      for (int dw = 0; dw < 2; dw++) {
-        const int iw = 2 * b + dw;
-        if (iw >= sh.W) continue;
-        const int64_t xo = ((((int64_t)n * sh.H + ih) * sh.W + iw) * C8 + c8) * 8;
-        if (use_mask) {
-          bf8 mk;
-          mk.v = *reinterpret_cast<const uint4*>(mask + xo);
-#pragma unroll
-          for (int e = 0; e < 8; e++)
-            if (!(mk.get(e) > 0.f)) acc[2 * dh + dw][e] = 0.f;
-        }
-        *reinterpret_cast<uint4*>(dx + xo) = pack8(acc[2 * dh + dw]);
+        for (int e = 0; e < 8; e++)
+          if (!(mk.get(e) > 0.f)) acc[q][e] = 0.f;
       }
+      *reinterpret_cast<uint4*>(dx + xo[q]) = pack8(acc[q]);
     }
   }
 }
