@@ -512,3 +512,20 @@ def test_patch_kernel_tiles_spanning_many_small_images():
         worst, errs = layer_errors(net, g, rg)
         assert worst < TOL["bf16"], errs
         assert abs(loss - rl) < 2e-2 * max(1.0, abs(rl))
+
+
+@pytest.mark.parametrize("compute", ["fp32", "bf16"])
+def test_largest_learner_count_in_one_call(compute):
+    """64 learners, the most one context takes, with a mini-batch each in ONE calcGradient call: every learner's
+    gradient and loss against the oracle (the pointer tables of a launch are full); 65 learners are refused."""
+    from paper_1511_05950_amd import binding
+    net = TINY["mfma_pad3"]
+    # weights of scale 0.1: at the other tests' 0.3 one of these 64 two-image batches is classified with a loss of 3e-12
+    # and its gradient (norm 3e-9) has no meaningful relative error
+    for (g, rg, loss, rl) in one_gradient(net, 2, compute, seed=164, scale=0.1, lam=64):
+        worst, errs = layer_errors(net, g, rg)
+        assert worst < TOL[compute], (compute, errs)
+        assert abs(loss - rl) < (1e-5 if compute == "fp32" else 2e-2) * max(1.0, abs(rl))
+    theta = np.zeros(wl.num_params(net), dtype=np.float32)
+    with pytest.raises(binding.SasgdError):
+        binding.Sasgd(65, 2, 65, 2, net=net, compute=compute, init_weights=theta)
