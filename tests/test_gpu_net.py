@@ -529,3 +529,15 @@ def test_largest_learner_count_in_one_call(compute):
     theta = np.zeros(wl.num_params(net), dtype=np.float32)
     with pytest.raises(binding.SasgdError):
         binding.Sasgd(65, 2, 65, 2, net=net, compute=compute, init_weights=theta)
+
+
+@pytest.mark.parametrize("compute", ["fp32", "bf16"])
+@pytest.mark.parametrize("name", ["max_clipped", "mfma_pad3", "patch_3x3", "mfma_s4"])
+def test_single_image_minibatch(name, compute):
+    """mu = 1: the smallest mini-batch (the mean over the mini-batch is the gradient of the one image; every GEMM has
+    fewer rows than a tile)."""
+    net = TINY[name]
+    for (g, rg, loss, rl) in one_gradient(net, 1, compute, seed=7 + sum(map(ord, name)), scale=0.1, lam=3):
+        worst, errs = layer_errors(net, g, rg)
+        assert worst < TOL[compute], (name, compute, errs)
+        assert abs(loss - rl) < (1e-5 if compute == "fp32" else 2e-2) * max(1.0, abs(rl))
