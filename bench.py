@@ -27,7 +27,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of the update kernel at P = 60e6, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
 # script scaled by a plain 240 MB copy in the same run (summary: profiles/apply_update_config1.txt)
 TRAFFIC_C1 = 1.2000e9
-TRAFFIC_C54 = 13.920e9
+TRAFFIC_C54 = 14.402e9      # the two-pass form writes and re-reads its sums: + 2 x 240 MB
 
 
 def cpu_baseline_server(cfg, budget_s=12.0):
@@ -126,7 +126,7 @@ def bench_server(args):
         "roofline": {"bound": "hbm", "kernel": "apply_update_kernel (c=1)", "achieved": round(achA, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achA / HBM_PEAK_GBS, 4), "traffic": TRAFFIC_C1,
                      "avg_launch_us": round(kA * 1e6, 2), "bytes_per_launch": P * 20},
-        "roofline_c54": {"bound": "hbm", "kernel": "apply_update_kernel (c=54)", "achieved": round(achB, 1),
+        "roofline_c54": {"bound": "hbm", "kernel": "sum_gradients_kernel + apply_update_kernel per stretch of 2 Mi parameters (c=54, 58 launches)", "achieved": round(achB, 1),
                          "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achB / HBM_PEAK_GBS, 4), "traffic": TRAFFIC_C54,
                          "avg_launch_us": round(kB * 1e6, 2), "bytes_per_launch": P * 4 * (lam + 4)},
     }

@@ -15,7 +15,8 @@
  *  - All device work is enqueued on the hipStream_t given at creation (passed as void*).
  *    Calls return without waiting for the device, except the copy* getters, which block.
  *  - The context owns the weight ring, momentum, per-learner gradient buffers and
- *    workspaces; all are allocated in sasgd_create and freed in sasgd_destroy; no other
+ *    workspaces (and, when floor(lambda / n) >= 25, an 8 MiB buffer of partial sums for the
+ *    update of long windows); all are allocated in sasgd_create and freed in sasgd_destroy; no other
  *    call allocates device memory.  The caller owns mini-batch buffers and externally
  *    pushed gradients and keeps them alive until the work that reads them has completed
  *    on the stream.

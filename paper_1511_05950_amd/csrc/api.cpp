@@ -154,6 +154,10 @@ int sasgd_create(const sasgd_config* cfg, const float* init_weights, sasgd_ctx**
     }
     ctx->v = (float*)ctx_alloc(ctx, P * sizeof(float));
     if (!ctx->ring_f32 || !ctx->v) { rc = fail(ctx, SASGD_ENOMEM, "weight ring / momentum"); break; }
+    if (cfg->lambda / cfg->n >= kTwoPassMinC) {
+      ctx->sum_buf = (float*)ctx_alloc(ctx, (size_t)kSumStretch * sizeof(float));
+      if (!ctx->sum_buf) { rc = fail(ctx, SASGD_ENOMEM, "buffer of the two-pass update"); break; }
+    }
 
     hipError_t e = hipMemcpyAsync(ctx->ring_f32, init_weights, P * sizeof(float),
                                   is_device_pointer(init_weights) ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice,
@@ -401,6 +405,7 @@ int sasgd_applyUpdate(sasgd_ctx* ctx, int64_t* out_new_timestamp) {
   u.momentum = ctx->cfg.momentum;
   u.decay = abar * ctx->cfg.weight_decay;
   u.v = ctx->v;
+  u.sum_buf = ctx->sum_buf;
   u.reverse = (int)(i & 1);   // consecutive updates walk in opposite directions (last-level cache reuse)
   const size_t Ppad = ((size_t)ctx->P + 63) & ~(size_t)63;
   bf16_t* new_slot_b16 = nullptr;

@@ -27,7 +27,11 @@ struct UpdateLaunch {
   float momentum;
   float decay;             // (sum_l coef_l) * weight_decay
   int reverse;             // walk the vector from its end (same result; see apply_update_kernel)
+  float* sum_buf;          // kSumStretch floats for the two-pass form of long windows, or nullptr: always one pass
 };
+// Windows of at least kTwoPassMinC gradients are applied in two passes per stretch of kSumStretch parameters.
+constexpr int kTwoPassMinC = 25;
+constexpr int64_t kSumStretch = (int64_t)1 << 21;   // 8 MiB of sums: 512 workgroups of 4 096 parameters
 hipError_t launch_apply_update(const UpdateLaunch& u, hipStream_t stream);
 // Update of one fully connected layer (weights [out][in] followed by the bias [out]) whose gradients are kept as
 // factors.  All pointers address the first weight of the layer.
@@ -121,6 +125,7 @@ struct sasgd_ctx {
   sasgd::bf16_t* ring_b16 = nullptr; // BF16 compute: [R][P + pack] shadow copies
   size_t slot_elems_b16 = 0;         // elements per bf16 slot (P rounded up + packed filters)
   float* v = nullptr;                // momentum [P]
+  float* sum_buf = nullptr;          // [kSumStretch] partial result of long windows (c >= kTwoPassMinC), else nullptr
   std::vector<sasgd::Learner> learners;
   std::vector<sasgd::Pending> pending;
   bool window_closed = false;

@@ -9,7 +9,17 @@
 // copy of theta_{i+1}): 4 (c + 4) bytes per parameter, nothing else touches HBM.  The kernel is
 // bandwidth bound; each lane moves 16-byte vectors, gradients are read with non-temporal loads
 // because they are never read again.
+//
+// Long windows (c >= kTwoPassMinC) take the same arithmetic in two launches per stretch of kSumStretch parameters:
+// sum_gradients_kernel writes s for the stretch to a small buffer, apply_update_kernel then runs on the stretch with
+// that buffer as its one "gradient" of coefficient 1 (fma(1, s, 0) = s: the result is bit-identical).  A pass that
+// only reads streams c gradients at the rate of a pure read (7.07 TB/s measured); in the single pass the two written
+// streams are interleaved with the 54 read ones all the time and the whole runs at copy speed (5.7 TB/s).  The
+// buffer is 8 MiB and is read back right after it was written, so it stays in the L2s.  P = 60 M, c = 54:
+// 2.43 -> 2.15 ms; the two forms cross at c of about 24.
 #include "ctx.hpp"
+
+#include <algorithm>
 
 namespace sasgd {
 
@@ -50,7 +60,8 @@ __device__ __forceinline__ void stg_nt(float4* p, float4 v) {
 // the 256 MB last-level cache still holds (P = 60 M, c = 1: 204 -> 175 us per update).  NT bit 0 / bit 1: theta
 // and v are read / written with non-temporal hints, which lose that reuse (gradients always are: nobody reads
 // them again).
-template <int ILP, int U, bool EARLY, bool SHADOW, int NT>
+// GPLAIN: the gradients are read with ordinary loads (the second pass of a long window reads the sums just written).
+template <int ILP, int U, bool EARLY, bool SHADOW, int NT, bool GPLAIN = false>
 __global__ __launch_bounds__(256) void apply_update_kernel(const float4* theta_in, float4* theta_out, float4* v,
                                                            uint2* __restrict__ shadow, int64_t n4, int c,
                                                            GradTable t, float m, float decay, int reverse) {
@@ -74,7 +85,7 @@ __global__ __launch_bounds__(256) void apply_update_kernel(const float4* theta_i
 #pragma unroll
       for (int e = 0; e < ILP; e++) {
         const int64_t i = base + e * 256;
-        if (i < n4) g[u][e] = ldg_nt(reinterpret_cast<const float4*>(t.g[l + u]) + i);
+        if (i < n4) g[u][e] = GPLAIN ? reinterpret_cast<const float4*>(t.g[l + u])[i] : ldg_nt(reinterpret_cast<const float4*>(t.g[l + u]) + i);
       }
 #pragma unroll
     for (int u = 0; u < U; u++) {           // arrival order l, l+1, ... within every element
@@ -127,6 +138,57 @@ __global__ __launch_bounds__(256) void apply_update_kernel(const float4* theta_i
   }
 }
 
+// First pass of a long window: s = sum_l coef_l g_l for one stretch, the FMA chain of apply_update_kernel, written
+// with ordinary stores.
+template <int ILP, int U>
+__global__ __launch_bounds__(256) void sum_gradients_kernel(float4* __restrict__ out, int64_t n4, int c, GradTable t) {
+  const int64_t base = (int64_t)blockIdx.x * (256 * ILP) + threadIdx.x;
+  float4 s[ILP];
+#pragma unroll
+  for (int e = 0; e < ILP; e++) s[e] = make_float4(0.f, 0.f, 0.f, 0.f);
+  int l = 0;
+  for (; l + U <= c; l += U) {
+    float4 g[U][ILP];
+#pragma unroll
+    for (int u = 0; u < U; u++)
+#pragma unroll
+      for (int e = 0; e < ILP; e++) {
+        const int64_t i = base + e * 256;
+        if (i < n4) g[u][e] = ldg_nt(reinterpret_cast<const float4*>(t.g[l + u]) + i);
+      }
+#pragma unroll
+    for (int u = 0; u < U; u++) {           // arrival order l, l+1, ... within every element
+      const float cf = t.coef[l + u];
+#pragma unroll
+      for (int e = 0; e < ILP; e++) {
+        s[e].x = fmaf(cf, g[u][e].x, s[e].x);
+        s[e].y = fmaf(cf, g[u][e].y, s[e].y);
+        s[e].z = fmaf(cf, g[u][e].z, s[e].z);
+        s[e].w = fmaf(cf, g[u][e].w, s[e].w);
+      }
+    }
+  }
+  for (; l < c; l++) {
+    const float cf = t.coef[l];
+#pragma unroll
+    for (int e = 0; e < ILP; e++) {
+      const int64_t i = base + e * 256;
+      if (i < n4) {
+        float4 g = ldg_nt(reinterpret_cast<const float4*>(t.g[l]) + i);
+        s[e].x = fmaf(cf, g.x, s[e].x);
+        s[e].y = fmaf(cf, g.y, s[e].y);
+        s[e].z = fmaf(cf, g.z, s[e].z);
+        s[e].w = fmaf(cf, g.w, s[e].w);
+      }
+    }
+  }
+#pragma unroll
+  for (int e = 0; e < ILP; e++) {
+    const int64_t i = base + e * 256;
+    if (i < n4) out[i] = s[e];
+  }
+}
+
 // Scalar tail (P not a multiple of 4): at most 3 elements.
 __global__ void apply_update_tail_kernel(const float* theta_in, float* theta_out, float* v, bf16_t* shadow,
                                          int64_t begin, int64_t P, int c, GradTable t, float m, float decay) {
@@ -155,8 +217,8 @@ static void launch_shape_nt(const UpdateLaunch& u, const GradTable& t, int64_t n
 }
 // theta and v take ordinary loads and stores for windows of up to kKeepMaxC gradients, so that the next update
 // finds their tail in the last-level cache; behind longer gradient sweeps nothing of them survives and the
-// streaming hints are the faster choice (P = 60 M, c = 54, after other updates: 2.45 against 2.61 ms).
-constexpr int kKeepMaxC = 24;
+// streaming hints are the faster choice (P = 60 M, c = 54, after other updates: 2.45 against 2.61 ms in one pass).
+constexpr int kKeepMaxC = kTwoPassMinC - 1;
 template <int ILP, int U, bool EARLY>
 static void launch_shape(const UpdateLaunch& u, const GradTable& t, int64_t n4, hipStream_t stream) {
   if (u.c <= kKeepMaxC) launch_shape_nt<ILP, U, EARLY, 0>(u, t, n4, stream);
@@ -172,7 +234,32 @@ hipError_t launch_apply_update(const UpdateLaunch& u, hipStream_t stream) {
     t.coef[l] = l < u.c ? u.coef[l] : 0.f;
   }
   const int64_t n4 = u.P / 4;
-  if (n4 > 0) {
+  if (n4 > 0 && u.c >= kTwoPassMinC && u.sum_buf) {
+    // stretches of 512 workgroups (two per compute unit; 256-1024 measured within 4 %, other counts slower)
+    constexpr int64_t stretch4 = kSumStretch / 4;
+    float4* sums = reinterpret_cast<float4*>(u.sum_buf);
+    GradTable tb;
+    for (int l = 0; l < kMaxLearners; l++) { tb.g[l] = nullptr; tb.coef[l] = 0.f; }
+    tb.g[0] = u.sum_buf;
+    tb.coef[0] = 1.0f;
+    for (int64_t off = 0; off < n4; off += stretch4) {
+      const int64_t len = std::min(stretch4, n4 - off);
+      const int blocks = (int)((len + 256 * 4 - 1) / (256 * 4));
+      GradTable ta = t;
+      for (int l = 0; l < u.c; l++) ta.g[l] = t.g[l] + off * 4;
+      hipLaunchKernelGGL((sum_gradients_kernel<4, 3>), dim3(blocks), dim3(256), 0, stream, sums, len, u.c, ta);
+      const float4* tin = reinterpret_cast<const float4*>(u.theta_in) + off;
+      float4* tout = reinterpret_cast<float4*>(u.theta_out) + off;
+      float4* vv = reinterpret_cast<float4*>(u.v) + off;
+      uint2* sh = u.shadow_out ? reinterpret_cast<uint2*>(u.shadow_out) + off : nullptr;
+      if (sh)
+        hipLaunchKernelGGL((apply_update_kernel<4, 1, true, true, 3, true>), dim3(blocks), dim3(256), 0, stream, tin, tout, vv, sh, len, 1, tb, u.momentum, u.decay, 0);
+      else
+        hipLaunchKernelGGL((apply_update_kernel<4, 1, true, false, 3, true>), dim3(blocks), dim3(256), 0, stream, tin, tout, vv, sh, len, 1, tb, u.momentum, u.decay, 0);
+    }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  } else if (n4 > 0) {
     if (u.c == 1) launch_shape<4, 1, true>(u, t, n4, stream);
     else if (u.c == 2 || u.c == 4) launch_shape<4, 2, true>(u, t, n4, stream);
     else launch_shape<4, 3, false>(u, t, n4, stream);

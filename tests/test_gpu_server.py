@@ -81,6 +81,18 @@ def test_update_without_momentum_is_the_softsync_rule():
     assert relerr(w, th) < 1e-6
 
 
+@pytest.mark.parametrize("compute", ["fp32", "bf16"])
+def test_long_window_in_two_passes_over_several_stretches(compute):
+    """Windows of 25 and more gradients are applied stretch by stretch (sums first, then the update): a vector of
+    three stretches with a ragged last one and a scalar tail, c = 30; and c = 24, the longest single-pass window, on
+    the same size."""
+    P = 2 * (1 << 21) + 900_003
+    w, mom, th, v = run_server_case(P, 30, 1, K=3, alpha0=0.01, m=0.9, wd=5e-4, lr_mode="per_gradient", seed=77, compute=compute)
+    assert relerr(w, th) < 1e-5 and relerr(mom, v) < 1e-5
+    w, mom, th, v = run_server_case(P, 24, 1, K=2, alpha0=0.01, m=0.9, wd=5e-4, lr_mode="per_gradient", seed=78, compute=compute)
+    assert relerr(w, th) < 1e-5 and relerr(mom, v) < 1e-5
+
+
 def test_update_bf16_shadow_matches_master():
     from paper_1511_05950_amd import binding
     P = 70_001
