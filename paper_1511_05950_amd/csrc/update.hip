@@ -15,7 +15,8 @@
 // that buffer as its one "gradient" of coefficient 1 (fma(1, s, 0) = s: the result is bit-identical).  A pass that
 // only reads streams c gradients at the rate of a pure read (7.07 TB/s measured); in the single pass the two written
 // streams are interleaved with the 54 read ones all the time and the whole runs at copy speed (5.7 TB/s).  The
-// buffer is 8 MiB and is read back right after it was written, so it stays in the L2s.  P = 60 M, c = 54:
+// buffer is 8 MiB and is read back right after it was written (it passes the L2s' memory interface both ways, 8 bytes
+// per parameter of counted traffic, and fits the memory-side cache many times over).  P = 60 M, c = 54:
 // 2.43 -> 2.15 ms; the two forms cross at c of about 24.
 #include "ctx.hpp"
 
