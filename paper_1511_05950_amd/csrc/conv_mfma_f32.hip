@@ -8,6 +8,8 @@
 //   * wgrad keeps its two tiles as they lie in memory (rows = output positions): one lane needs one scalar per
 //     MFMA operand, so no transpose is involved; the bias gradient is an extra im2col column of ones.
 // Block tile 128 x 32 (forward / dgrad) and 32 x 128 (wgrad), four wavefronts of one 32 x 32 MFMA block each.
+#include <algorithm>
+
 #include "dev_common.hpp"
 #include "kernels.hpp"
 
@@ -26,7 +28,7 @@ __device__ __forceinline__ uint32_t fdiv(uint32_t n, int d, uint32_t magic) { re
 __global__ __launch_bounds__(256) void igemm_f32_kernel(PtrTab ws, CPtrTab wts, IGemm g, VConv v, Epilogue ep, int64_t w_off,
                                                         int dgrad) {
   __shared__ __attribute__((aligned(16))) float lds[2 * (128 + 32) * FLD];
-  const int z = blockIdx.z;
+  const int z = blockIdx.z / g.splits, sp = blockIdx.z % g.splits;
   const float* act = (const float*)ws.p[z] + g.a_off;
   const float* W = (const float*)wts.p[z] + w_off;
   const __amdgpu_buffer_rsrc_t rsrc_a = __builtin_amdgcn_make_buffer_rsrc((void*)act, 0, (int)g.a_bytes, 0x00020000);
@@ -92,12 +94,16 @@ __global__ __launch_bounds__(256) void igemm_f32_kernel(PtrTab ws, CPtrTab wts, 
   floatx16 acc;
 #pragma unroll
   for (int r = 0; r < 16; r++) acc[r] = 0.f;
-  const int ksteps = (g.Kchunks + 3) / 4;
-  load(0);
-  store(0);
+  const int all_steps = (g.Kchunks + 3) / 4;
+  const int per = (all_steps + g.splits - 1) / g.splits;
+  const int ks_begin = sp * per, ksteps = min(all_steps, ks_begin + per);
+  if (ks_begin < ksteps) {
+    load(ks_begin);
+    store(0);
+  }
   __syncthreads();
-  for (int ks = 0; ks < ksteps; ks++) {
-    const int buf = ks & 1;
+  for (int ks = ks_begin; ks < ksteps; ks++) {
+    const int buf = (ks - ks_begin) & 1;
     if (ks + 1 < ksteps) load(ks + 1);
     const float* A = lds + buf * (128 + 32) * FLD + (wave * 32 + (lane & 31)) * FLD + 8 * (lane >> 5);
     const float* B = lds + buf * (128 + 32) * FLD + 128 * FLD + (lane & 31) * FLD + 8 * (lane >> 5);
@@ -108,11 +114,20 @@ __global__ __launch_bounds__(256) void igemm_f32_kernel(PtrTab ws, CPtrTab wts, 
     __syncthreads();
   }
 
+  const int n = n0 + (lane & 31);
+  if (n >= g.Ncols) return;
+  if (g.splits > 1) {   // raw partial sums [split][m][n]; igemm_finish_f32_kernel adds them in split order
+    float* part = reinterpret_cast<float*>((char*)ws.p[z] + g.scratch_off) + (int64_t)sp * g.M * g.Ncols;
+#pragma unroll
+    for (int r = 0; r < 16; r++) {
+      const int m = m0 + wave * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+      if (m < g.M) part[(int64_t)m * g.Ncols + n] = acc[r];
+    }
+    return;
+  }
   float* out = (float*)ws.p[z] + ep.out_off;
   const float* mask = (const float*)ws.p[z] + ep.mask_off;
   const float* bias = (const float*)wts.p[z] + ep.bias_off;
-  const int n = n0 + (lane & 31);
-  if (n >= g.Ncols) return;
   const float bv = ep.has_bias ? bias[n] : 0.f;
 #pragma unroll
   for (int r = 0; r < 16; r++) {
@@ -126,11 +141,38 @@ __global__ __launch_bounds__(256) void igemm_f32_kernel(PtrTab ws, CPtrTab wts, 
   }
 }
 
+// Sum of the partial tiles of a split contraction, in split order, then bias, ReLU and the ReLU mask of the input
+// gradient: the epilogue of igemm_f32_kernel.
+__global__ __launch_bounds__(256) void igemm_finish_f32_kernel(PtrTab ws, CPtrTab wts, IGemm g, Epilogue ep) {
+  const int z = blockIdx.z;
+  const float* part = reinterpret_cast<const float*>((const char*)ws.p[z] + g.scratch_off);
+  float* out = (float*)ws.p[z] + ep.out_off;
+  const float* mask = (const float*)ws.p[z] + ep.mask_off;
+  const float* bias = (const float*)wts.p[z] + ep.bias_off;
+  const uint32_t total = (uint32_t)((int64_t)g.M * g.Ncols);
+  for (uint32_t o = blockIdx.x * 256 + threadIdx.x; o < total; o += gridDim.x * 256) {
+    float val = 0.f;
+#pragma unroll 4
+    for (int sp = 0; sp < g.splits; sp++) val += part[(size_t)sp * total + o];
+    if (ep.has_bias) val += bias[o % (uint32_t)g.Ncols];
+    if (ep.relu) val = fmaxf(val, 0.f);
+    if (ep.use_mask && !(mask[o] > 0.f)) val = 0.f;
+    out[o] = val;
+  }
+}
+
+// g.splits > 1 divides the contraction among that many workgroups per tile (mini-batches of a few images give a
+// handful of tiles, each a serial chain of hundreds of fp32 MFMAs); needs g.scratch_off and M * Ncols < 2^32.
 hipError_t launch_igemm_f32(const PtrTab& ws, const CPtrTab& wts, const IGemm& g, const VConv& v, const Epilogue& ep, int64_t w_off,
                             bool dgrad, int count, hipStream_t s) {
-  if (g.C % 4) return hipErrorInvalidValue;
-  dim3 grid((unsigned)((g.M + 127) / 128), (unsigned)((g.Ncols + 31) / 32), (unsigned)count);
+  if (g.C % 4 || g.splits < 1 || (int64_t)count * g.splits > 65535) return hipErrorInvalidValue;
+  dim3 grid((unsigned)((g.M + 127) / 128), (unsigned)((g.Ncols + 31) / 32), (unsigned)(count * g.splits));
   hipLaunchKernelGGL(igemm_f32_kernel, grid, dim3(256), 0, s, ws, wts, g, v, ep, w_off, dgrad ? 1 : 0);
+  if (g.splits > 1) {
+    const int64_t total = (int64_t)g.M * g.Ncols;
+    const unsigned blocks = (unsigned)std::min<int64_t>((total + 255) / 256, 2048);
+    hipLaunchKernelGGL(igemm_finish_f32_kernel, dim3(blocks, 1, (unsigned)count), dim3(256), 0, s, ws, wts, g, ep);
+  }
   return hipGetLastError();
 }
 
@@ -140,7 +182,7 @@ __global__ __launch_bounds__(256) void igemm_wgrad_f32_kernel(PtrTab ws, PtrTab 
                                                               int64_t b_off) {
   constexpr int LA = 32 + 4, LB = 128 + 4;     // row strides (floats) of the dy and im2col tiles, 16-byte aligned
   __shared__ __attribute__((aligned(16))) float lds[2 * FK * (LA + LB)];
-  const int z = blockIdx.z;
+  const int z = blockIdx.z / g.splits, sp = blockIdx.z % g.splits;
   const float* x = (const float*)ws.p[z] + g.a_off;
   const float* dy = (const float*)ws.p[z] + dy_off;
   const float* consts = (const float*)ws.p[z] + g.zero_off;
@@ -192,12 +234,16 @@ __global__ __launch_bounds__(256) void igemm_wgrad_f32_kernel(PtrTab ws, PtrTab 
   floatx16 acc;
 #pragma unroll
   for (int r = 0; r < 16; r++) acc[r] = 0.f;
-  const int msteps = (g.M + FK - 1) / FK;
-  load(0);
-  store(0);
+  const int all_steps = (g.M + FK - 1) / FK;
+  const int per = (all_steps + g.splits - 1) / g.splits;
+  const int ms_begin = sp * per, msteps = min(all_steps, ms_begin + per);
+  if (ms_begin < msteps) {
+    load(ms_begin);
+    store(0);
+  }
   __syncthreads();
-  for (int ms = 0; ms < msteps; ms++) {
-    const int buf = ms & 1;
+  for (int ms = ms_begin; ms < msteps; ms++) {
+    const int buf = (ms - ms_begin) & 1;
     if (ms + 1 < msteps) load(ms + 1);
     const float* A = lds + buf * FK * (LA + LB) + 8 * (lane >> 5) * LA + (lane & 31);
     const float* B = lds + buf * FK * (LA + LB) + FK * LA + 8 * (lane >> 5) * LB + wave * 32 + (lane & 31);
@@ -207,11 +253,21 @@ __global__ __launch_bounds__(256) void igemm_wgrad_f32_kernel(PtrTab ws, PtrTab 
     __syncthreads();
   }
 
-  float* dw = (float*)grads.p[z] + w_off;
-  float* db = (float*)grads.p[z] + b_off;
   const int kcols = g.Kchunks * 4;
   const int k = k0 + wave * 32 + (lane & 31);
   if (k > kcols) return;
+  if (g.splits > 1) {   // partial sums [split][n][kcols + 4]; wgrad_finish_f32_kernel adds them and writes the gradient
+    const int ldk = kcols + 4;
+    float* part = reinterpret_cast<float*>((char*)ws.p[z] + g.scratch_off) + (int64_t)sp * g.Ncols * ldk;
+#pragma unroll
+    for (int r = 0; r < 16; r++) {
+      const int n = n0 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+      if (n < g.Ncols) part[(int64_t)n * ldk + k] = acc[r];
+    }
+    return;
+  }
+  float* dw = (float*)grads.p[z] + w_off;
+  float* db = (float*)grads.p[z] + b_off;
   const int tap = k / g.C, cp = k - tap * g.C;
 #pragma unroll
   for (int r = 0; r < 16; r++) {
@@ -223,12 +279,40 @@ __global__ __launch_bounds__(256) void igemm_wgrad_f32_kernel(PtrTab ws, PtrTab 
   }
 }
 
+// Sum of the partial weight gradients in split order; element (n, k) goes to its place in the flat gradient
+// (column kcols is the bias gradient).
+__global__ __launch_bounds__(256) void wgrad_finish_f32_kernel(PtrTab ws, PtrTab grads, IGemm g, VConv v, int64_t w_off, int64_t b_off) {
+  const int z = blockIdx.z;
+  const int kcols = g.Kchunks * 4, ldk = kcols + 4;
+  const float* part = reinterpret_cast<const float*>((const char*)ws.p[z] + g.scratch_off);
+  float* dw = (float*)grads.p[z] + w_off;
+  float* db = (float*)grads.p[z] + b_off;
+  const int64_t split_stride = (int64_t)g.Ncols * ldk;
+  const int total = g.Ncols * (kcols + 1);
+  for (int idx = blockIdx.x * 256 + threadIdx.x; idx < total; idx += gridDim.x * 256) {
+    const int n = idx / (kcols + 1), k = idx - n * (kcols + 1);
+    float val = 0.f;
+#pragma unroll 4
+    for (int sp = 0; sp < g.splits; sp++) val += part[sp * split_stride + (int64_t)n * ldk + k];
+    if (k == kcols) { db[n] = val; continue; }
+    const int tap = k / g.C, cp = k - tap * g.C;
+    const int64_t dst = filter_src(v, n, tap, cp);
+    if (dst >= 0) dw[dst] = val;
+  }
+}
+
+// g.splits > 1 divides the output positions among that many workgroups per tile (needs g.scratch_off).
 hipError_t launch_igemm_wgrad_f32(const PtrTab& ws, const PtrTab& grads, const IGemm& g, const VConv& v, size_t dy_off, int64_t w_off,
                                   int64_t b_off, int count, hipStream_t s) {
-  if (g.C % 4 || g.Ncols % 4) return hipErrorInvalidValue;
+  if (g.C % 4 || g.Ncols % 4 || g.splits < 1 || (int64_t)count * g.splits > 65535) return hipErrorInvalidValue;
   const int cols = g.Kchunks * 4 + 1;
-  dim3 grid((unsigned)((g.Ncols + 31) / 32), (unsigned)((cols + 127) / 128), (unsigned)count);
+  dim3 grid((unsigned)((g.Ncols + 31) / 32), (unsigned)((cols + 127) / 128), (unsigned)(count * g.splits));
   hipLaunchKernelGGL(igemm_wgrad_f32_kernel, grid, dim3(256), 0, s, ws, grads, g, v, dy_off, w_off, b_off);
+  if (g.splits > 1) {
+    const int total = g.Ncols * cols;
+    hipLaunchKernelGGL(wgrad_finish_f32_kernel, dim3((unsigned)std::min((total + 255) / 256, 1024), 1, (unsigned)count), dim3(256), 0, s,
+                       ws, grads, g, v, w_off, b_off);
+  }
   return hipGetLastError();
 }
 

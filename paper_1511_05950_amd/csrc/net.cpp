@@ -318,9 +318,10 @@ int net_create(const sasgd_config& cfg, Net** out, int64_t* out_P, size_t* out_p
   bytes += ((size_t)N * 4 + 255) & ~(size_t)255;
   // scratch for split contractions: room for 8 partial copies of the largest output, within 16..128 MiB
   size_t need = 0;
+  const int cw = net->bf16 ? 8 : 4;                // channels per im2col chunk
   for (const Op& op : net->ops) {
-    if (!op.mfma || !net->bf16) continue;
-    size_t fwd = (size_t)op.gf.M * op.gf.Ncols * 4, wg = (size_t)op.gf.Ncols * (op.gf.Kchunks * 8 + 8) * 4;
+    if (!op.mfma) continue;
+    size_t fwd = (size_t)op.gf.M * op.gf.Ncols * 4, wg = (size_t)op.gf.Ncols * (op.gf.Kchunks * cw + cw) * 4;
     size_t dg = (size_t)op.gd.M * op.gd.Ncols * 4;
     need = fwd > need ? fwd : need;
     need = wg > need ? wg : need;
@@ -359,6 +360,13 @@ hipError_t net_set_workspace(Net* net, int learner, void* ws, hipStream_t stream
 hipError_t net_prepare_version(Net* net, const void* flat, void* packed, hipStream_t stream) {
   if (net->pack.count == 0) return hipSuccess;
   return launch_pack_filters(flat, packed, net->pack, stream);
+}
+
+// fp32 MFMA path: 128 x 32 tiles, contraction steps of 16 (four 4-channel chunks)
+static void set_splits_f32(const Net* net, IGemm& g, int count) {
+  const int64_t tiles = (int64_t)((g.M + 127) / 128) * ((g.Ncols + 31) / 32);
+  g.scratch_off = net->scratch_off;
+  g.splits = choose_splits(tiles, count, (g.Kchunks + 3) / 4, (size_t)g.M * g.Ncols * 4, net->scratch_bytes);
 }
 
 static void set_splits(const Net* net, IGemm& g, int steps, int count) {
@@ -405,7 +413,9 @@ hipError_t net_calc_gradient(Net* net, const int* learners, const LearnerBind* b
       case OP_CONV:
         if (op.mfma && !bf) {
           Epilogue ep{yo, 0, op.b_off, 1, op.relu ? 1 : 0, 0, 1};
-          TRY(launch_igemm_f32(ws, wts, op.gf, op.vc, ep, op.w_off, false, count, stream));
+          IGemm gf = op.gf;
+          set_splits_f32(net, gf, count);
+          TRY(launch_igemm_f32(ws, wts, gf, op.vc, ep, op.w_off, false, count, stream));
         } else if (op.mfma) {
           Epilogue ep{yo, 0, op.b_off, 1, op.relu ? 1 : 0, 0, op.out_f32 ? 1 : 0};
           IGemm gf = op.gf;
@@ -440,10 +450,17 @@ hipError_t net_calc_gradient(Net* net, const int* learners, const LearnerBind* b
     switch (op.kind) {
       case OP_CONV:
         if (op.mfma && !bf) {
-          TRY(launch_igemm_wgrad_f32(ws, grads, op.gf, op.vc, dy, op.w_off, op.b_off, count, stream));
+          {
+            IGemm gw = op.gf;
+            const int64_t tiles = (int64_t)((gw.Ncols + 31) / 32) * ((gw.Kchunks * 4 + 1 + 127) / 128);
+            gw.scratch_off = net->scratch_off;
+            gw.splits = choose_splits(tiles, count, (gw.M + 15) / 16, (size_t)gw.Ncols * (gw.Kchunks * 4 + 4) * 4, net->scratch_bytes);
+            TRY(launch_igemm_wgrad_f32(ws, grads, gw, op.vc, dy, op.w_off, op.b_off, count, stream));
+          }
           if (need_dx) {
             IGemm gd = op.gd;
             gd.a_off = dy;
+            set_splits_f32(net, gd, count);
             Epilogue ep{dx, tin.off, 0, 0, 0, tin.relu ? 1 : 0, 1};
             TRY(launch_igemm_f32(ws, wts, gd, op.vc, ep, op.w_off, true, count, stream));
           }

@@ -93,7 +93,12 @@ TINY = {
 @pytest.mark.parametrize("name", sorted(TINY))
 def test_tiny_net_gradient(name, compute):
     net = TINY[name]
-    for (g, rg, loss, rl) in one_gradient(net, 3, compute, seed=sum(map(ord, name))):
+    # patch_5x5 feeds 140 000 values through ReLUs; with the seed of the other nets one learner has two of them at
+    # 6e-9 and 2e-8 of the sum of their terms' magnitudes (fp64, PyTorch on the CPU), below what fp32 sums resolve:
+    # the sign of such a value depends on the summation order, and one flipped ReLU moves the early layers' gradients
+    # by 1e-3.  With the next seed the closest value is 5e-7 away.
+    seed = sum(map(ord, name)) + (1 if name == "patch_5x5" else 0)
+    for (g, rg, loss, rl) in one_gradient(net, 3, compute, seed=seed):
         worst, errs = layer_errors(net, g, rg)
         assert worst < TOL[compute], (name, compute, errs)
         assert abs(loss - rl) < (1e-5 if compute == "fp32" else 2e-2) * max(1.0, abs(rl))
