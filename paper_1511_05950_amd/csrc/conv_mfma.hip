@@ -1696,9 +1696,6 @@ __global__ __launch_bounds__(256) void igemm_wgrad_kernel(PtrTab ws, PtrTab grad
   // requested, then the MFMAs run on buffer `buf`: a global load has a whole step to arrive.  Two steps per loop
   // iteration make `buf` a constant.
   auto step = [&](int buf, bool has1, bool has2) {
-    if (has1) store_lds(buf ^ 1);
-    if (has2) load_regs();
-    __builtin_amdgcn_sched_barrier(0);
     const bf16_t* A = lds + buf * (A_ELEMS + B_ELEMS);
     const bf16_t* B = A + A_ELEMS;
 #pragma unroll
@@ -1726,6 +1723,10 @@ __global__ __launch_bounds__(256) void igemm_wgrad_kernel(PtrTab ws, PtrTab grad
 #pragma unroll
         for (int j = 0; j < TN; j++) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
     }
+    // the wait for the next tiles' global loads falls behind this step's MFMAs instead of in front of its LDS reads
+    __builtin_amdgcn_sched_barrier(0);
+    if (has1) store_lds(buf ^ 1);
+    if (has2) load_regs();
     __syncthreads();
   };
 
