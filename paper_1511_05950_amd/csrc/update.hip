@@ -235,7 +235,7 @@ hipError_t launch_apply_update(const UpdateLaunch& u, hipStream_t stream) {
     t.coef[l] = l < u.c ? u.coef[l] : 0.f;
   }
   const int64_t n4 = u.P / 4;
-  if (n4 > 0 && u.c >= kTwoPassMinC && u.sum_buf) {
+  if (u.P >= kSumStretch && u.c >= kTwoPassMinC && u.sum_buf) {   // shorter vectors: one launch, nothing to separate
     // stretches of 512 workgroups (two per compute unit; 256-1024 measured within 4 %, other counts slower)
     constexpr int64_t stretch4 = kSumStretch / 4;
     float4* sums = reinterpret_cast<float4*>(u.sum_buf);
