@@ -156,7 +156,9 @@ int sasgd_applyUpdate(sasgd_ctx* ctx, int64_t* out_new_timestamp);
 
 /* evaluate: forward pass only over the bound mini-batches of the listed learners, each on its
  * bound weight version (the test / validation error curves of Section 4.3).  Nothing is
- * consumed: bindings, gradients and the protocol state stay as they are.
+ * consumed: bindings, gradients and the protocol state stay as they are, except that a binding an
+ * evaluation has used no longer holds its version in the ring (applyUpdate may overwrite it; a later
+ * calcGradient on that binding then fails with ERANGE until the learner pulls again).
  * out_loss_dev: optional device float[count], mean loss per listed learner.
  * out_rank_dev: device int32[count * mu]; entry k*mu + s is the number of classes that precede
  * the true class of image s of learners[k] when the class scores are sorted in descending

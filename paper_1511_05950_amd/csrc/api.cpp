@@ -63,7 +63,7 @@ inline bool version_in_ring(const sasgd_ctx* ctx, int64_t version) {
 // Device address of the weights a learner reads for `version`.
 const void* version_ptr(const sasgd_ctx* ctx, int64_t version) {
   if (ctx->cfg.compute == SASGD_BF16) return ctx->ring_b16 + (size_t)slot_of(ctx, version) * ctx->slot_elems_b16;
-  return ctx->ring_f32 + (size_t)slot_of(ctx, version) * (size_t)ctx->P;
+  return ctx->ring_f32 + (size_t)slot_of(ctx, version) * ctx->slot_elems_f32;
 }
 
 void prof_begin(sasgd_ctx* ctx, int which) {
@@ -89,6 +89,23 @@ void prof_collect(sasgd_ctx* ctx) {
     (void)hipEventDestroy(ev.b);
   }
   ctx->events.clear();
+}
+
+// coef_l = alpha(tau_l) / c with alpha(tau) = alpha0 / tau for tau > 0 (Section 2.4) and alpha0 at tau = 0; the two
+// other rate modes replace alpha(tau_l) by alpha0 / mean(tau) or by alpha0.
+void window_coefficients(int lr_mode, float a0, int c, const int32_t* tau, float* coef) {
+  if (lr_mode == SASGD_LR_MEAN_STALENESS) {
+    int64_t sum = 0;
+    for (int l = 0; l < c; l++) sum += tau[l];
+    const float mean = (float)((double)sum / (double)c);
+    const float a = a0 / std::max(mean, 1.0f);
+    for (int l = 0; l < c; l++) coef[l] = a / (float)c;
+  } else {
+    for (int l = 0; l < c; l++) {
+      const float a = lr_mode == SASGD_LR_CONSTANT ? a0 : a0 / (float)std::max(tau[l], 1);
+      coef[l] = a / (float)c;
+    }
+  }
 }
 
 }  // namespace
@@ -150,7 +167,8 @@ int sasgd_create(const sasgd_config* cfg, const float* init_weights, sasgd_ctx**
       ctx->ring_b16 = (bf16_t*)ctx_alloc(ctx, R * ctx->slot_elems_b16 * sizeof(bf16_t));
       if (!ctx->ring_b16) { rc = fail(ctx, SASGD_ENOMEM, "weight ring (bf16)"); break; }
     } else {
-      ctx->ring_f32 = (float*)ctx_alloc(ctx, R * P * sizeof(float));
+      ctx->slot_elems_f32 = Ppad;       // every slot starts 256-byte aligned (the kernels move 16 bytes per lane)
+      ctx->ring_f32 = (float*)ctx_alloc(ctx, R * Ppad * sizeof(float));
     }
     ctx->v = (float*)ctx_alloc(ctx, P * sizeof(float));
     if (!ctx->ring_f32 || !ctx->v) { rc = fail(ctx, SASGD_ENOMEM, "weight ring / momentum"); break; }
@@ -236,6 +254,7 @@ int sasgd_pullWeights(sasgd_ctx* ctx, int32_t learner, int32_t staleness_request
   if (!version_in_ring(ctx, j)) return fail(ctx, SASGD_ERANGE, "pullWeights: version has left the ring");
   Learner& L = ctx->learners[(size_t)learner];
   L.has_weights = true;
+  L.evaluated = false;
   L.pulled_version = j;
   if (out_timestamp) *out_timestamp = j;
   return SASGD_OK;
@@ -303,6 +322,9 @@ int sasgd_evaluate(sasgd_ctx* ctx, const int32_t* learners, int32_t count, float
   }
   hipError_t e = net_calc_gradient(ctx->net, ids, binds, count, out_loss_dev, out_rank_dev, ctx->stream);
   if (e != hipSuccess) return fail_hip(ctx, e, "evaluate");
+  // The bindings stay, but a binding that an evaluation has used no longer keeps its version in the ring: a training
+  // loop evaluates and moves on, and must not be stopped by applyUpdate's eviction check many updates later.
+  for (int k = 0; k < count; k++) ctx->learners[(size_t)ids[k]].evaluated = true;
   return SASGD_OK;
 }
 
@@ -362,21 +384,9 @@ int sasgd_sumGradients(sasgd_ctx* ctx, int32_t* out_pending) {
   if (ctx->window_closed) return fail(ctx, SASGD_ESTATE, "sumGradients: window already closed; call applyUpdate");
   const int c = ctx->c;
   if ((int)ctx->pending.size() < c) return fail(ctx, SASGD_ENOTREADY, "sumGradients: fewer than c gradients pending");
-  // coef_l = alpha(tau_l) / c with alpha(tau) = alpha0 / tau for tau > 0 (Section 2.4) and alpha0 at tau = 0
-  const float a0 = ctx->cfg.alpha0;
-  if (ctx->cfg.lr_mode == SASGD_LR_MEAN_STALENESS) {
-    int64_t sum = 0;
-    for (int l = 0; l < c; l++) sum += ctx->pending[(size_t)l].staleness;
-    float mean = (float)((double)sum / (double)c);
-    float a = a0 / std::max(mean, 1.0f);
-    for (int l = 0; l < c; l++) ctx->window_coef[l] = a / (float)c;
-  } else {
-    for (int l = 0; l < c; l++) {
-      const int32_t tau = ctx->pending[(size_t)l].staleness;
-      float a = ctx->cfg.lr_mode == SASGD_LR_CONSTANT ? a0 : a0 / (float)std::max(tau, 1);
-      ctx->window_coef[l] = a / (float)c;
-    }
-  }
+  int32_t taus[kMaxLearners];
+  for (int l = 0; l < c; l++) taus[l] = ctx->pending[(size_t)l].staleness;
+  window_coefficients(ctx->cfg.lr_mode, ctx->cfg.alpha0, c, taus, ctx->window_coef);
   ctx->window_count = c;
   ctx->window_closed = true;
   return SASGD_OK;
@@ -390,7 +400,7 @@ int sasgd_applyUpdate(sasgd_ctx* ctx, int64_t* out_new_timestamp) {
   const int64_t evicted = i + 1 - R;   // version whose slot theta_{i+1} takes
   if (evicted >= 0 && R > 1) {
     for (const Learner& L : ctx->learners)
-      if (L.has_weights && L.pulled_version == evicted)
+      if (L.has_weights && !L.evaluated && L.pulled_version == evicted)
         return fail(ctx, SASGD_ERANGE, "applyUpdate: a learner still holds the version this update would overwrite");
   }
   UpdateLaunch u;
@@ -415,8 +425,8 @@ int sasgd_applyUpdate(sasgd_ctx* ctx, int64_t* out_new_timestamp) {
     new_slot_b16 = ctx->ring_b16 + (size_t)slot_of(ctx, i + 1) * ctx->slot_elems_b16;
     u.shadow_out = new_slot_b16;
   } else {
-    u.theta_in = ctx->ring_f32 + (size_t)slot_of(ctx, i) * (size_t)ctx->P;
-    u.theta_out = ctx->ring_f32 + (size_t)slot_of(ctx, i + 1) * (size_t)ctx->P;
+    u.theta_in = ctx->ring_f32 + (size_t)slot_of(ctx, i) * ctx->slot_elems_f32;
+    u.theta_out = ctx->ring_f32 + (size_t)slot_of(ctx, i + 1) * ctx->slot_elems_f32;
     u.shadow_out = nullptr;
   }
   // Layers whose gradients are kept as factors get their own launch; the stretches of the flat vector between them
@@ -535,7 +545,7 @@ int sasgd_copyWeights(sasgd_ctx* ctx, int64_t version, float* host_out) {
       }
   } else {
     const float* src = ctx->cfg.compute == SASGD_BF16 ? ctx->ring_f32
-                                                      : ctx->ring_f32 + (size_t)slot_of(ctx, version) * (size_t)ctx->P;
+                                                      : ctx->ring_f32 + (size_t)slot_of(ctx, version) * ctx->slot_elems_f32;
     e = hipMemcpyAsync(host_out, src, bytes, hipMemcpyDeviceToHost, ctx->stream);
     if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
   }

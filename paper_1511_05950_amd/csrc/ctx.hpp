@@ -96,6 +96,7 @@ struct Learner {
   const int32_t* labels = nullptr;
   bool has_weights = false;
   int64_t pulled_version = -1;
+  bool evaluated = false;      // the pulled version has served an evaluation pass: it may leave the ring (see sasgd_evaluate)
   int64_t grad_timestamp = -1;
   GradState grad_state = GRAD_NONE;
   float* grad = nullptr;       // [P] fp32 (nullptr for NET_NONE)
@@ -124,6 +125,7 @@ struct sasgd_ctx {
   float* ring_f32 = nullptr;         // FP32 compute: [R][P]; BF16 compute: [1][P] master
   sasgd::bf16_t* ring_b16 = nullptr; // BF16 compute: [R][P + pack] shadow copies
   size_t slot_elems_b16 = 0;         // elements per bf16 slot (P rounded up + packed filters)
+  size_t slot_elems_f32 = 0;         // FP32 compute: elements per ring slot (P rounded up to 64)
   float* v = nullptr;                // momentum [P]
   float* sum_buf = nullptr;          // [kSumStretch] partial result of long windows (c >= kTwoPassMinC), else nullptr
   std::vector<sasgd::Learner> learners;

@@ -121,12 +121,11 @@ int net_create(const sasgd_config& cfg, Net** out, int64_t* out_P, size_t* out_p
   // the MFMA path when it can: its input is channel-padded to a multiple of the chunk (stride 1) or
   // space-to-depth transformed (stride s, no padding).
   const int chunk = net->bf16 ? 8 : 4;
-  const bool allow_mfma = getenv("SASGD_NO_MFMA") == nullptr;
   int n_factored = 0;
   auto round_chunk = [&](int x) { return (x + chunk - 1) / chunk * chunk; };
   net->inpack = InPack{C, H, W, C, H, W, 1};
   bool first_mfma = false;
-  if (allow_mfma && layers[0].kind == SASGD_CONV && layers[0].units % chunk == 0 && layers[0].window >= 1 && layers[0].stride >= 1) {
+  if (layers[0].kind == SASGD_CONV && layers[0].units % chunk == 0 && layers[0].window >= 1 && layers[0].stride >= 1) {
     const sasgd_layer& L0 = layers[0];
     if (L0.stride == 1) {
       net->inpack.Cp = round_chunk(C);
@@ -175,7 +174,7 @@ int net_create(const sasgd_config& cfg, Net** out, int64_t* out_P, size_t* out_p
           op.pack_fwd = (int64_t)pack_cursor;
           pack_cursor += (size_t)round32(L.units) * op.Kp;
         }
-      } else if (cur != 0 && allow_mfma && L.stride == 1 && C % chunk == 0 && L.units % chunk == 0) {
+      } else if (cur != 0 && L.stride == 1 && C % chunk == 0 && L.units % chunk == 0) {
         op.mfma = true;
         op.vc = VConv{C, L.window, L.units, 1, C, L.window};
         op.gf = IGemm{0, 0, N * op.cs.OH * op.cs.OW, L.units, H, W, C, op.cs.OH, op.cs.OW, L.window, L.pad,
@@ -220,7 +219,7 @@ int net_create(const sasgd_config& cfg, Net** out, int64_t* out_P, size_t* out_p
       op.b_off = P;
       P += L.units;
       op.in_t = cur;
-      if (cur != 0 && allow_mfma && in % chunk == 0 && L.units % chunk == 0 && (!net->bf16 || op.w_off % 8 == 0)) {
+      if (cur != 0 && in % chunk == 0 && L.units % chunk == 0 && (!net->bf16 || op.w_off % 8 == 0)) {
         // fully connected: the flat weight matrix [out][in] is the B operand as it lies (forward), and is read
         // transposed for the input gradient; no packed copy
         op.mfma = true;

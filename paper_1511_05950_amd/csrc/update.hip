@@ -19,6 +19,7 @@
 // per parameter of counted traffic, and fits the memory-side cache many times over).  P = 60 M, c = 54:
 // 2.43 -> 2.15 ms; the two forms cross at c of about 24.
 #include "ctx.hpp"
+#include "dev_common.hpp"
 
 #include <algorithm>
 
@@ -28,13 +29,6 @@ struct GradTable {
   const float* g[kMaxLearners];
   float coef[kMaxLearners];
 };
-
-__device__ __forceinline__ bf16_t f32_to_bf16_rne(float f) {
-  uint32_t u = __float_as_uint(f);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)0x7fc0;   // NaN
-  u += 0x7fffu + ((u >> 16) & 1u);
-  return (bf16_t)(u >> 16);
-}
 
 __device__ __forceinline__ float4 ldg_nt(const float4* p) {
   float4 r;
@@ -131,8 +125,8 @@ __global__ __launch_bounds__(256) void apply_update_kernel(const float4* theta_i
       if (NT & 2) { stg_nt(v + i, b); stg_nt(theta_out + i, a); } else { v[i] = b; theta_out[i] = a; }
       if (SHADOW) {
         uint2 o;
-        o.x = (uint32_t)f32_to_bf16_rne(a.x) | ((uint32_t)f32_to_bf16_rne(a.y) << 16);
-        o.y = (uint32_t)f32_to_bf16_rne(a.z) | ((uint32_t)f32_to_bf16_rne(a.w) << 16);
+        o.x = (uint32_t)f2bf(a.x) | ((uint32_t)f2bf(a.y) << 16);
+        o.y = (uint32_t)f2bf(a.z) | ((uint32_t)f2bf(a.w) << 16);
         shadow[i] = o;
       }
     }
@@ -201,7 +195,7 @@ __global__ void apply_update_tail_kernel(const float* theta_in, float* theta_out
   float th = theta_in[i] - vv;
   v[i] = vv;
   theta_out[i] = th;
-  if (shadow) shadow[i] = f32_to_bf16_rne(th);
+  if (shadow) shadow[i] = f2bf(th);
 }
 
 template <int ILP, int U, bool EARLY, int NT>
@@ -313,8 +307,8 @@ __global__ __launch_bounds__(256) void apply_update_fc_kernel(const float* theta
     *reinterpret_cast<float4*>(theta_out + e) = a;
     if (SHADOW) {
       uint2 o;
-      o.x = (uint32_t)f32_to_bf16_rne(a.x) | ((uint32_t)f32_to_bf16_rne(a.y) << 16);
-      o.y = (uint32_t)f32_to_bf16_rne(a.z) | ((uint32_t)f32_to_bf16_rne(a.w) << 16);
+      o.x = (uint32_t)f2bf(a.x) | ((uint32_t)f2bf(a.y) << 16);
+      o.y = (uint32_t)f2bf(a.z) | ((uint32_t)f2bf(a.w) << 16);
       *reinterpret_cast<uint2*>(shadow + e) = o;
     }
     return;
@@ -385,8 +379,8 @@ __global__ __launch_bounds__(256) void apply_update_fc_kernel(const float* theta
     stg_nt(reinterpret_cast<float4*>(theta_out + e), a);
     if (SHADOW) {
       uint2 o;
-      o.x = (uint32_t)f32_to_bf16_rne(a.x) | ((uint32_t)f32_to_bf16_rne(a.y) << 16);
-      o.y = (uint32_t)f32_to_bf16_rne(a.z) | ((uint32_t)f32_to_bf16_rne(a.w) << 16);
+      o.x = (uint32_t)f2bf(a.x) | ((uint32_t)f2bf(a.y) << 16);
+      o.y = (uint32_t)f2bf(a.z) | ((uint32_t)f2bf(a.w) << 16);
       *reinterpret_cast<uint2*>(shadow + e) = o;
     }
   }
@@ -415,7 +409,7 @@ hipError_t launch_apply_update_fc(const FcUpdateLaunch& u, hipStream_t stream) {
 
 __global__ void fp32_to_bf16_kernel(const float* __restrict__ src, bf16_t* __restrict__ dst, int64_t n) {
   int64_t stride = (int64_t)gridDim.x * blockDim.x;
-  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) dst[i] = f32_to_bf16_rne(src[i]);
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) dst[i] = f2bf(src[i]);
 }
 __global__ void bf16_to_fp32_kernel(const bf16_t* __restrict__ src, float* __restrict__ dst, int64_t n) {
   int64_t stride = (int64_t)gridDim.x * blockDim.x;

@@ -82,6 +82,35 @@ def test_evaluate_leaves_gradient_path_untouched_and_flags_bad_labels():
     ctx.destroy()
 
 
+def test_evaluation_binding_does_not_hold_its_version_in_the_ring():
+    """A learner that served an evaluation pass keeps its binding, but more than R updates may follow without the
+    eviction check of applyUpdate stopping the run; using the stale binding afterwards is refused until a new pull."""
+    from paper_1511_05950_amd import binding
+    net, mu, R = wl.CIFAR3, 2, 2
+    X = wl.images(net, 2 * mu, 96)
+    Y = wl.labels(net, 2 * mu, 97)
+    w0 = wl.init_weights(net, 98, std=0.05)
+    Xd, Yd = torch.from_numpy(X).cuda(), torch.from_numpy(Y).cuda()
+    ctx = binding.Sasgd(2, mu, 2, R, net="cifar3", alpha0=0.01, init_weights=w0)
+    rank = torch.zeros(mu, device="cuda", dtype=torch.int32)
+    ctx.getMinibatch(1, Xd[mu:], Yd[mu:])
+    ctx.pullWeights(1, 0)                                  # learner 1 binds version 0 ...
+    ctx.evaluate([1], None, rank)                          # ... and only evaluates on it
+    for i in range(R + 2):                                 # learner 0 trains on: version 0 leaves the ring
+        ctx.getMinibatch(0, Xd[:mu], Yd[:mu])
+        ctx.pullWeights(0, 0)
+        ctx.calcGradient([0])
+        ctx.pushGradient(0)
+        ctx.sumGradients()
+        assert ctx.applyUpdate() == i + 1
+    with pytest.raises(binding.SasgdError) as e:
+        ctx.calcGradient([1])                              # the evaluated binding is stale by now
+    assert e.value.code == binding.ERANGE
+    ctx.pullWeights(1, 0)
+    ctx.calcGradient([1])
+    ctx.destroy()
+
+
 @pytest.mark.parametrize("compute,net_name", [("fp32", "cifar3"), ("bf16", "cifar3"), ("bf16", "s2d")])
 def test_pixel_mean_is_subtracted_before_the_first_layer(compute, net_name):
     from paper_1511_05950_amd import binding
