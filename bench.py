@@ -1,17 +1,23 @@
 #!/usr/bin/env python3
 """Benchmark of the staleness-aware n-softsync ASGD hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload server|cifar|alex|cifar-fp32-c4|cifar-fp32-c1|alex-calc|alex-calc-shared|cifar-calc]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload all|alex|server|cifar|cifar-fp32-c4|cifar-fp32-c1|alex-calc|alex-calc-shared|cifar-calc]
 
-Default workload "server" is BASELINE config 1, the parameter-server microbenchmark: P = 60 M fp32
-parameters, lambda = 54 gradients resident in HBM, momentum 0.9, weight decay 5e-4.  One step consumes every
-learner's gradient once in each of the two protocols the config names:
-    54-softsync: 54 consecutive sumGradients+applyUpdate with c = 1   (20 B per parameter and update)
-     1-softsync:  1 sumGradients+applyUpdate with c = 54              (232 B per parameter)
-The printed value is algorithmic HBM bytes (4 (c + 4) per parameter and update) over wall time of the step.
-The other workloads run the whole path (calcGradient + sumGradients + applyUpdate) on BASELINE configs 3, 4, 0, 2;
-"alex-calc" / "cifar-calc" time calcGradient alone with all lambda learners in one batched call (alex-calc: every
-learner on a weight version of its own, as under lambda-softsync; alex-calc-shared: all on one version).
+Default workload "all": the whole metric in one line.  The line itself is BASELINE config 4 end to end in steady state
+(AlexNet-shaped net, bf16 compute with fp32 master weights, lambda = 18 learners of mu = 16, 18-softsync, seeded
+staleness uniform in 0..36): one step = one server update = one learner's calcGradient (batched with the other learners
+whose weight version already exists) + sumGradients + applyUpdate; value = training images/s; roofline = the
+calcGradient launches against the bf16 MFMA peak; roofline_hbm = applyUpdate as it runs inside that step against the HBM
+peak.  The ring is pre-warmed by 36 untimed updates whatever --warmup says, so that requested staleness is never
+clamped (the literal run from theta_0, where most early gradients read version 0, is the nested "cold_start").  Nested
+under further keys: "calc_only" (one batched calcGradient call of all 18 learners, a weight version each),
+"server_config1" (BASELINE config 1, P = 60 M fp32, 54 gradients resident: 54 updates at c = 1 and one at c = 54).
+"--workload server" prints config 1 as the line itself: one step consumes every learner's gradient once in each of the two
+protocols (54-softsync: 54 updates of 20 B per parameter; 1-softsync: one update of 232 B per parameter) and the value is
+algorithmic HBM bytes (4 (c + 4) per parameter and update) over wall time.  "cifar", "cifar-fp32-c4", "cifar-fp32-c1"
+run the whole path on BASELINE configs 3, 0, 2; "alex-calc" / "cifar-calc" time calcGradient alone with all lambda
+learners in one batched call (alex-calc: every learner on a weight version of its own, as under lambda-softsync;
+alex-calc-shared: all on one version).
 Prints ONE JSON line.
 """
 import argparse
@@ -24,10 +30,13 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
-# HBM bytes per launch of the update kernel at P = 60e6, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
-# script scaled by a plain 240 MB copy in the same run (summary: profiles/apply_update_config1.txt)
+# HBM bytes per launch of the update kernel at P = 60e6.  NOT measured by this run: taken from rocprofv3 --pmc
+# FETCH_SIZE / WRITE_SIZE runs of this script scaled by a plain 240 MB copy in the same run (summary:
+# profiles/apply_update_config1.txt); the line says so in "traffic_source".
 TRAFFIC_C1 = 1.2000e9
 TRAFFIC_C54 = 14.402e9      # the two-pass form writes and re-reads its sums: + 2 x 240 MB
+TRAFFIC_SOURCE = "rocprofv3 --pmc FETCH_SIZE/WRITE_SIZE, profiles/apply_update_config1.txt (not measured by this run)"
+PREWARM_CFG4 = 36           # updates that fill the ring of BASELINE config 4 before anything is timed
 
 
 def cpu_baseline_server(cfg, budget_s=12.0):
@@ -51,7 +60,7 @@ def cpu_baseline_server(cfg, budget_s=12.0):
         nbytes += Ps * (lam * 20 + 4 * (lam + 4))
         reps += 1
     dt = time.perf_counter() - t0
-    return {"value": nbytes / dt / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+    return {"value": nbytes / dt / 1e9, "unit": "GB/s", "cores": 1, "host_cores": os.cpu_count(), "kind": "oracle",
             "sample": "%d steps of the same two protocols on a %d-element slice of the parameter vector "
                       "(numpy fp64 oracle; bytes counted with the fp32 formula 4(c+4) per parameter)" % (reps, Ps)}
 
@@ -125,10 +134,10 @@ def bench_server(args):
                    "num_params": P, "lambda": lam, "momentum": cfg["momentum"], "weight_decay": cfg["weight_decay"]},
         "roofline": {"bound": "hbm", "kernel": "apply_update_kernel (c=1)", "achieved": round(achA, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achA / HBM_PEAK_GBS, 4), "traffic": TRAFFIC_C1,
-                     "avg_launch_us": round(kA * 1e6, 2), "bytes_per_launch": P * 20},
+                     "traffic_source": TRAFFIC_SOURCE, "avg_launch_us": round(kA * 1e6, 2), "bytes_per_launch": P * 20},
         "roofline_c54": {"bound": "hbm", "kernel": "sum_gradients_kernel + apply_update_kernel per stretch of 2 Mi parameters (c=54, 58 launches)", "achieved": round(achB, 1),
                          "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achB / HBM_PEAK_GBS, 4), "traffic": TRAFFIC_C54,
-                         "avg_launch_us": round(kB * 1e6, 2), "bytes_per_launch": P * 4 * (lam + 4)},
+                         "traffic_source": TRAFFIC_SOURCE, "avg_launch_us": round(kB * 1e6, 2), "bytes_per_launch": P * 4 * (lam + 4)},
     }
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline_server(cfg)
@@ -152,14 +161,17 @@ def cpu_baseline_net(cfg, budget_s=10.0):
         n += 1
     dt = time.perf_counter() - t0
     cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
-    return {"value": n * mu / dt, "unit": "images/s", "cores": cores, "kind": "oracle",
+    return {"value": n * mu / dt, "unit": "images/s", "cores": cores, "host_cores": os.cpu_count(), "kind": "oracle",
             "sample": "%d calcGradient calls of one mini-batch (mu = %d) by the fp64 C oracle with OpenMP; the server update "
                       "is not included" % (n, mu)}
 
 
-def bench_net(args, cfg_id):
+def bench_net(args, cfg_id, prewarm=0, cold=False):
     """Whole hot path on BASELINE config 3 (CIFAR-shaped, bf16, 1-softsync) or 4 (AlexNet-shaped, bf16, 18-softsync):
-    one step = one server update = c calcGradients (batched launches) + sumGradients + applyUpdate."""
+    one step = one server update = c calcGradients (batched launches) + sumGradients + applyUpdate.
+    prewarm: untimed updates in front of the --warmup ones (fills the ring so that no requested staleness is clamped).
+    cold: the literal run from theta_0 -- no warm-up update at all, the config's own K updates are the timed steps (one
+    identical untimed run on another context first, so that code objects are loaded)."""
     import numpy as np
     import torch
     import workloads as wl
@@ -169,31 +181,44 @@ def bench_net(args, cfg_id):
     net, lam, mu, n, c = cfg["net"], cfg["lam"], cfg["mu"], cfg["n"], cfg["c"]
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
-    K = args.warmup + args.steps
+    warm = 0 if cold else prewarm + args.warmup
+    steps = cfg["K"] if cold else args.steps
+    K = warm + steps
     rng = np.random.default_rng(wl.SEED0 + 1000 * cfg_id + 3)
     hi = {0: 4, 2: 60, 3: 2, 4: 36}[cfg_id]
     if cfg_id == 2:
         sched = wl.jitter_schedule(K, c, n, wl.SEED0 + 2003)
     else:
         sched = rng.integers(0, hi + 1, size=(K, c)).astype(np.int32)
+    if cold:
+        sched = cfg["schedule"]()              # the config's own schedule, update for update
     R = hi + 1
     pool = min(cfg["n_images"], 4096)
     pool -= pool % mu
     X = torch.randn((pool,) + net["input"], device=dev, generator=torch.Generator(device=dev).manual_seed(cfg_id))
     Y = torch.randint(0, net["classes"], (pool,), device=dev, dtype=torch.int32)
-    ctx = binding.Sasgd(lam, mu, n, R, net=net["name"], compute=cfg["compute"], alpha0=cfg["alpha0"], momentum=cfg["momentum"],
-                        weight_decay=cfg["weight_decay"], init_weights=cfg["weights"]())
+    w_init = cfg["weights"]()
+
+    def make_ctx():
+        return binding.Sasgd(lam, mu, n, R, net=net["name"], compute=cfg["compute"], alpha0=cfg["alpha0"], momentum=cfg["momentum"],
+                             weight_decay=cfg["weight_decay"], init_weights=w_init)
 
     def batch_of(i, l):
         s0 = ((i * c + l) * mu) % pool
         return X[s0:s0 + mu], Y[s0:s0 + mu]
 
+    if cold:
+        tmp = make_ctx()
+        driver.run_softsync_batched(tmp, sched, batch_of, lam)
+        torch.cuda.synchronize()
+        tmp.destroy()
+    ctx = make_ctx()
     # learners whose weights already exist are computed in one batched call (same versions, same staleness)
-    driver.run_softsync_batched(ctx, sched[:args.warmup], batch_of, lam)
+    driver.run_softsync_batched(ctx, sched[:warm], batch_of, lam)
     torch.cuda.synchronize()
     ctx.setProfiling(True)
     t0 = time.perf_counter()
-    _, calls = driver.run_softsync_batched(ctx, sched[args.warmup:], batch_of, lam, first_update=args.warmup)
+    _, calls = driver.run_softsync_batched(ctx, sched[warm:], batch_of, lam, first_update=warm)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     ms_g, n_g = ctx.phaseTime(0)
@@ -201,7 +226,7 @@ def bench_net(args, cfg_id):
     P = ctx.P
     Wf = ctx.factoredParams()      # fully connected weights whose gradient is formed inside applyUpdate from its factors
     ctx.destroy()
-    images = args.steps * c * mu
+    images = steps * c * mu
     flop_img = {0: 68.87424e6, 2: 68.87424e6, 3: 68.87424e6, 4: 6.585512448e9}[cfg_id]   # forward + backward MACs x 2 per image
     flop_img -= 2.0 * Wf           # those weight-gradient MACs are not done by calcGradient
     fp32 = cfg["compute"] == "fp32"
@@ -211,19 +236,27 @@ def bench_net(args, cfg_id):
     # algorithmic bytes of one update: theta, v read and written, a 2-byte copy in bf16 compute, and 4 bytes per pending
     # gradient for every parameter whose gradient is a written-out vector
     upd_bytes = P * (16 + (0 if fp32 else 2)) + (P - Wf) * 4 * c
+    how = ("cold start: the config's %d updates from theta_0, no warm-up update" % steps if cold else
+           "steady state: %d + %d untimed updates first" % (prewarm, args.warmup) if prewarm else "%d untimed updates first" % args.warmup)
+    upd_us = ms_u / n_u * 1e3
     out = {
         "metric": "training images/sec per GPU", "value": round(images / dt, 1), "unit": "images/s", "n_gpus": 1,
-        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(dt / args.steps * 1e3, 4),
+        "steps": steps, "warmup": warm, "ms_per_step": round(dt / steps * 1e3, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32" if fp32 else "bf16", "data": "synthetic",
-        "config": {"workload": "BASELINE config %d: %s net, lambda=%d, mu=%d, %d-softsync (c=%d), %s"
-                               % (cfg_id, net["name"], lam, mu, n, c, "fp32 compute" if fp32 else "bf16 compute, fp32 master"),
-                   "num_params": P},
+        "config": {"workload": "BASELINE config %d: %s net, lambda=%d, mu=%d, %d-softsync (c=%d), %s; %s"
+                               % (cfg_id, net["name"], lam, mu, n, c, "fp32 compute" if fp32 else "bf16 compute, fp32 master", how),
+                   "num_params": P, "ring_depth": R, "calcGradient_calls": n_g},
         "roofline": {"bound": "alu" if fp32 else "mfma", "kernel": "calcGradient phase (every launch of its %d batched calls; algorithmic "
                                                 "flop = 2 x forward+backward MACs of %d images)" % (n_g, images),
                      "achieved": round(ach, 2), "peak": peak, "unit": "TFLOP/s", "frac": round(ach / peak, 5),
                      "traffic": None, "avg_call_us": round(t_grad / n_g * 1e6, 1), "learners_per_call": round(images / mu / n_g, 2)},
-        "applyUpdate": {"avg_launch_us": round(ms_u / n_u * 1e3, 2), "bytes_per_launch": upd_bytes,
-                        "achieved_GBs": round(upd_bytes / (ms_u / n_u * 1e-3) / 1e9, 1), "factored_fc_weights": Wf},
+        "roofline_hbm": {"bound": "hbm", "kernel": "applyUpdate as it runs inside the step (all launches of one update: the factored "
+                                                   "fully connected layers and the streaming remainder)" if Wf else
+                                                   "applyUpdate as it runs inside the step",
+                         "achieved": round(upd_bytes / (upd_us * 1e-6) / 1e9, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                         "frac": round(upd_bytes / (upd_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4), "traffic": None,
+                         "avg_launch_us": round(upd_us, 2), "bytes_per_launch": upd_bytes, "factored_fc_weights": Wf},
+        "phase_ms_per_step": {"calcGradient": round(ms_g / steps, 4), "applyUpdate": round(ms_u / steps, 4)},
     }
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline_net(cfg)
@@ -297,12 +330,36 @@ def bench_calc(args, cfg_id, shared=False):
     return out
 
 
+def bench_all(args):
+    """The default line: BASELINE config 4 end to end in steady state, with the other parts of the metric nested."""
+    import copy
+    import gc
+    import torch
+    out = bench_net(args, 4, prewarm=PREWARM_CFG4)
+    sub = copy.copy(args)
+    sub.no_cpu = True
+    keep = ("value", "unit", "steps", "warmup", "ms_per_step", "config", "roofline", "roofline_hbm", "roofline_c54", "phase_ms_per_step")
+
+    def nested(res):
+        return {k: res[k] for k in keep if k in res}
+
+    gc.collect(); torch.cuda.empty_cache()
+    out["cold_start"] = nested(bench_net(sub, 4, cold=True))
+    gc.collect(); torch.cuda.empty_cache()
+    sub.steps, sub.warmup = 5, 2
+    out["calc_only"] = nested(bench_calc(sub, 4))
+    gc.collect(); torch.cuda.empty_cache()
+    sub.steps, sub.warmup, sub.calibrate_copy = 5, 2, False
+    out["server_config1"] = nested(bench_server(sub))
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="server")
+    ap.add_argument("--workload", default="all")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg (profiling runs)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run plain 240 MB device copies (reference for rocprofv3 byte counters)")
@@ -311,10 +368,16 @@ def main():
         print("bench.py: this build runs on one GPU only (lambda learners are simulated on it); use --gpus 1",
               file=sys.stderr)
         sys.exit(2)
-    if args.workload == "server":
+    if args.workload == "all":
+        out = bench_all(args)
+    elif args.workload == "alex":
+        out = bench_net(args, 4, prewarm=PREWARM_CFG4)
+    elif args.workload == "alex-cold":
+        out = bench_net(args, 4, cold=True)
+    elif args.workload == "server":
         out = bench_server(args)
-    elif args.workload in ("cifar", "alex", "cifar-fp32-c4", "cifar-fp32-c1"):
-        out = bench_net(args, {"cifar": 3, "alex": 4, "cifar-fp32-c4": 0, "cifar-fp32-c1": 2}[args.workload])
+    elif args.workload in ("cifar", "cifar-fp32-c4", "cifar-fp32-c1"):
+        out = bench_net(args, {"cifar": 3, "cifar-fp32-c4": 0, "cifar-fp32-c1": 2}[args.workload])
     elif args.workload in ("cifar-calc", "alex-calc"):
         out = bench_calc(args, {"cifar-calc": 3, "alex-calc": 4}[args.workload])
     elif args.workload == "alex-calc-shared":      # all learners on one weight version (what 1-softsync would give)
