@@ -152,6 +152,31 @@ int sasgd_sumGradients(sasgd_ctx* ctx, int32_t* out_pending);
  * overwritten holds a version some learner has pulled but not yet used. */
 int sasgd_applyUpdate(sasgd_ctx* ctx, int64_t* out_new_timestamp);
 
+/* applyUpdateNoAlloc: the server update for callers that cannot allocate device memory or create library objects
+ * around a call -- code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  It is
+ * sumGradients + applyUpdate on caller-owned vectors, without a context:
+ *     coef_l = alpha(tau_l) / c   (lr_mode, alpha0 and the staleness tau_l = staleness[l] as in sumGradients)
+ *     v <- momentum v + sum_l coef_l g_l + (sum_l coef_l) weight_decay theta_in;   theta_out = theta_in - v
+ * run by the kernels of sasgd_applyUpdate: same arithmetic, same order, bit-identical results.  Windows of 25 and
+ * more gradients over at least 2 Mi parameters take the two-launch form, whose 8 MiB of partial sums live in an array
+ * compiled into the library (one copy per GPU, held until the process ends) instead of in a context's allocation.
+ *   theta_in_dev, theta_out_dev, v_dev: device float32 [num_params], 16-byte aligned; theta_out may be theta_in.
+ *   shadow_out_dev: optional device bf16 [num_params] (8-byte aligned) receiving theta_out rounded to nearest even.
+ *   grads_dev: HOST array of c device pointers (float32 [num_params] each, 16-byte aligned); staleness: HOST int32 [c].
+ *   stream: hipStream_t the launches are enqueued on (NULL = default stream); the call does not wait for them.
+ *   err / err_len: optional host buffer that receives a message when the call fails.
+ * Limits: 1 <= c <= SASGD_NOALLOC_MAX_GRADIENTS, 1 <= num_params <= SASGD_NOALLOC_MAX_PARAMS; anything beyond is
+ * refused with EINVAL and a message.  Calls no hipMalloc / hipFree and no allocating library routine.
+ * All calls on one GPU share that GPU's array: two calls whose kernels may overlap in time on one GPU (different
+ * streams, different threads) race on it; calls on one stream are ordered and safe.  Nothing in it needs clearing:
+ * every launch that reads a stretch of sums follows the launch that wrote exactly that stretch. */
+#define SASGD_NOALLOC_MAX_GRADIENTS 64
+#define SASGD_NOALLOC_MAX_PARAMS ((int64_t)1 << 32)
+int sasgd_applyUpdateNoAlloc(const float* theta_in_dev, float* theta_out_dev, float* v_dev, uint16_t* shadow_out_dev,
+                             int64_t num_params, int32_t c, const float* const* grads_dev, const int32_t* staleness,
+                             int32_t lr_mode, float alpha0, float momentum, float weight_decay, void* stream,
+                             char* err, size_t err_len);
+
 /* ---- training-loop pieces around the hot path (Sections 4.1 - 4.3) ---------------------- */
 
 /* evaluate: forward pass only over the bound mini-batches of the listed learners, each on its

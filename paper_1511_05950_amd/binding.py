@@ -29,6 +29,7 @@ EXPORTS = [
     "sasgd_copyWeights", "sasgd_copyGradient", "sasgd_copyMomentum", "sasgd_gradientPtr",
     "sasgd_setProfiling", "sasgd_phaseTime", "sasgd_last_error", "sasgd_version",
     "sasgd_evaluate", "sasgd_setBaseRate", "sasgd_setPixelMean", "sasgd_factoredParams",
+    "sasgd_applyUpdateNoAlloc",
 ]
 
 
@@ -96,6 +97,8 @@ def load():
         lib.sasgd_evaluate.argtypes = [vp, P(i32), i32, vp, vp]
         lib.sasgd_setBaseRate.argtypes = [vp, ctypes.c_float]
         lib.sasgd_setPixelMean.argtypes = [vp, vp]
+        lib.sasgd_applyUpdateNoAlloc.argtypes = [vp, vp, vp, vp, i64, i32, P(vp), P(i32), i32, ctypes.c_float, ctypes.c_float,
+                                                 ctypes.c_float, vp, ctypes.c_char_p, ctypes.c_size_t]
         lib.sasgd_last_error.argtypes = [vp]
         lib.sasgd_last_error.restype = ctypes.c_char_p
         lib.sasgd_version.restype = ctypes.c_char_p
@@ -292,6 +295,28 @@ class Sasgd:
 
     def last_error(self):
         return load().sasgd_last_error(self._h).decode()
+
+
+def applyUpdateNoAlloc(theta_in_dev, theta_out_dev, v_dev, grads_dev, staleness, lr_mode="per_gradient", alpha0=0.01,
+                       momentum=0.0, weight_decay=0.0, shadow_out_dev=None, num_params=None, stream=None):
+    """sasgd_applyUpdateNoAlloc: the context-free server update that allocates nothing (see include/sasgd.h).
+    grads_dev: sequence of device tensors / addresses; staleness: sequence of ints."""
+    lib = load()
+    c = len(grads_dev)
+    if num_params is None:
+        num_params = int(theta_in_dev.numel())
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream().cuda_stream
+    ptrs = (ctypes.c_void_p * max(c, 1))(*[_addr(g) for g in grads_dev])
+    taus = (ctypes.c_int32 * max(c, 1))(*[int(t) for t in staleness])
+    err = ctypes.create_string_buffer(256)
+    rc = lib.sasgd_applyUpdateNoAlloc(_addr(theta_in_dev), _addr(theta_out_dev), _addr(v_dev), _addr(shadow_out_dev), num_params, c,
+                                      ptrs, taus, LR_MODES[lr_mode] if isinstance(lr_mode, str) else lr_mode, alpha0, momentum,
+                                      weight_decay, stream, err, len(err))
+    if rc != OK:
+        raise SasgdError(rc, err.value.decode())
+    return rc
 
 
 def version():

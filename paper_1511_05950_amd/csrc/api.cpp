@@ -143,6 +143,12 @@ int sasgd_create(const sasgd_config* cfg, const float* init_weights, sasgd_ctx**
     return SASGD_EHIP;
   }
 
+  {
+    // look up this device's statically allocated buffer now, so that a later sasgd_applyUpdateNoAlloc (possibly under
+    // stream capture) finds the address cached
+    float* unused = nullptr;
+    if (static_sum_buffer(&unused) != hipSuccess) (void)hipGetLastError();
+  }
   int rc = SASGD_OK;
   size_t pack_elems = 0;
   do {
@@ -488,6 +494,48 @@ int sasgd_applyUpdate(sasgd_ctx* ctx, int64_t* out_new_timestamp) {
   ctx->window_count = 0;
   ctx->timestamp = i + 1;   // every weight update increments the timestamp by one (Section 2.1)
   if (out_new_timestamp) *out_new_timestamp = ctx->timestamp;
+  return SASGD_OK;
+}
+
+int sasgd_applyUpdateNoAlloc(const float* theta_in_dev, float* theta_out_dev, float* v_dev, uint16_t* shadow_out_dev,
+                             int64_t num_params, int32_t c, const float* const* grads_dev, const int32_t* staleness,
+                             int32_t lr_mode, float alpha0, float momentum, float weight_decay, void* stream,
+                             char* err, size_t err_len) {
+  auto refuse = [&](int code, const char* msg) {
+    if (err && err_len > 0) snprintf(err, err_len, "applyUpdateNoAlloc: %s", msg);
+    return code;
+  };
+  if (!theta_in_dev || !theta_out_dev || !v_dev || !grads_dev || !staleness) return refuse(SASGD_EINVAL, "null argument");
+  if (c < 1 || c > SASGD_NOALLOC_MAX_GRADIENTS) return refuse(SASGD_EINVAL, "c must lie in 1..64");
+  if (num_params < 1 || num_params > SASGD_NOALLOC_MAX_PARAMS) return refuse(SASGD_EINVAL, "num_params must lie in 1..2^32");
+  if (lr_mode < SASGD_LR_PER_GRADIENT || lr_mode > SASGD_LR_CONSTANT) return refuse(SASGD_EINVAL, "unknown lr_mode");
+  if (!(alpha0 >= 0.f) || !(momentum >= 0.f) || !(weight_decay >= 0.f)) return refuse(SASGD_EINVAL, "alpha0, momentum and weight_decay must not be negative");
+  if (((uintptr_t)theta_in_dev | (uintptr_t)theta_out_dev | (uintptr_t)v_dev) & 15) return refuse(SASGD_EINVAL, "theta and v must be 16-byte aligned");
+  if ((uintptr_t)shadow_out_dev & 7) return refuse(SASGD_EINVAL, "shadow_out_dev must be 8-byte aligned");
+  UpdateLaunch u;
+  for (int l = 0; l < c; l++) {
+    if (!grads_dev[l] || ((uintptr_t)grads_dev[l] & 15)) return refuse(SASGD_EINVAL, "every gradient must be a 16-byte aligned device pointer");
+    if (staleness[l] < 0) return refuse(SASGD_EINVAL, "negative staleness");
+    u.grads[l] = grads_dev[l];
+  }
+  window_coefficients(lr_mode, alpha0, c, staleness, u.coef);
+  float abar = 0.f;
+  for (int l = 0; l < c; l++) abar += u.coef[l];
+  float* sums = nullptr;
+  hipError_t e = static_sum_buffer(&sums);   // a lookup after the first call on this device; never an allocation
+  if (e != hipSuccess) return refuse(SASGD_EHIP, hipGetErrorString(e));
+  u.theta_in = theta_in_dev;
+  u.theta_out = theta_out_dev;
+  u.v = v_dev;
+  u.shadow_out = shadow_out_dev;
+  u.P = num_params;
+  u.c = c;
+  u.momentum = momentum;
+  u.decay = abar * weight_decay;
+  u.reverse = 0;
+  u.sum_buf = sums;
+  e = launch_apply_update(u, (hipStream_t)stream);
+  if (e != hipSuccess) return refuse(SASGD_EHIP, hipGetErrorString(e));
   return SASGD_OK;
 }
 

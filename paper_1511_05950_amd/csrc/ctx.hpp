@@ -33,6 +33,9 @@ struct UpdateLaunch {
 constexpr int kTwoPassMinC = 25;
 constexpr int64_t kSumStretch = (int64_t)1 << 21;   // 8 MiB of sums: 512 workgroups of 4 096 parameters
 hipError_t launch_apply_update(const UpdateLaunch& u, hipStream_t stream);
+// Device address, on the current device, of the library's statically allocated buffer of kSumStretch floats (looked up
+// once per device; no allocation).  Every caller on a device shares it: launches that use it must not overlap.
+hipError_t static_sum_buffer(float** out);
 // Update of one fully connected layer (weights [out][in] followed by the bias [out]) whose gradients are kept as
 // factors.  All pointers address the first weight of the layer.
 struct FcUpdateLaunch {

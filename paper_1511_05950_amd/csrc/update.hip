@@ -22,8 +22,35 @@
 #include "dev_common.hpp"
 
 #include <algorithm>
+#include <mutex>
 
 namespace sasgd {
+
+// Buffer of partial sums for callers that may not allocate (sasgd_applyUpdateNoAlloc): one stretch of the two-pass
+// form, 8 MiB per device, held from the library's load until the process ends.  Host code never passes this name to a
+// kernel: it is a host-side stand-in, the device address comes from hipGetSymbolAddress (static_sum_buffer below).
+static __device__ __align__(256) float scratch[kSumStretch];
+
+constexpr int kMaxDevices = 64;
+static float* g_scratch_ptr[kMaxDevices];
+static std::mutex g_scratch_mutex;
+
+hipError_t static_sum_buffer(float** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));   // this device's copy of the array (the current device's)
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    g_scratch_ptr[dev] = static_cast<float*>(p);
+  }
+  *out = g_scratch_ptr[dev];
+  return hipSuccess;
+}
 
 struct GradTable {
   const float* g[kMaxLearners];
