@@ -34,6 +34,7 @@ def lib():
         _lib.cnn_loss_and_gradient.restype = ctypes.c_double
         _lib.cnn_class_scores.restype = ctypes.c_double
         _lib.cnn_num_params.restype = ctypes.c_long
+        _lib.cnn_min_relu_margin.restype = ctypes.c_double
         _lib.round_to_bf16.restype = ctypes.c_double
         _lib.round_to_bf16.argtypes = [ctypes.c_double]
     return _lib
@@ -83,6 +84,21 @@ def loss_and_gradient(net, theta, x, label, want_grad=True, round_bf16=False):
     if not np.isfinite(loss) and np.isnan(loss):
         raise ValueError("parameter vector length does not match the network")
     return float(loss), grad
+
+
+def min_relu_margin(net, theta, x):
+    """Smallest |v| / sum|terms| over every ReLU input v of this case (exact mode; see cnn_oracle.c).  Below about
+    1e-6 some ReLU input is smaller than the rounding error of a float sum of its terms, so its sign, and with it
+    the gradient, is not defined at fp32 precision."""
+    t = _table(net)
+    c, h, w = net["input"]
+    theta = np.ascontiguousarray(theta, dtype=np.float64)
+    x = np.ascontiguousarray(x, dtype=np.float64)
+    m = lib().cnn_min_relu_margin(_dp(t), ctypes.c_int(len(t)), ctypes.c_int(c), ctypes.c_int(h), ctypes.c_int(w),
+                                  ctypes.c_int(x.shape[0]), _dp(theta), ctypes.c_long(theta.size), _dp(x))
+    if np.isnan(m):
+        raise ValueError("parameter vector length does not match the network")
+    return float(m)
 
 
 def make_callback(net, round_bf16=False):

@@ -389,6 +389,75 @@ double cnn_class_scores(const olayer* layers, int nlayers, int C, int H, int W, 
   return loss_gradient_scores(layers, nlayers, C, H, W, N, theta_in, P, x, label, NULL, scores, round_bf16);
 }
 
+/*
+ * Diagnostic for the fp32 parity tests, not part of the method: how close to zero does any ReLU input of this case
+ * lie, relative to the size of the terms it is summed from?  A ReLU input v = b + sum_k w_k x_k whose magnitude is
+ * below the rounding error of its own sum (about 1e-7 sum_k |w_k x_k| in float) has no defined sign: two correct fp32
+ * evaluations that add in different orders may disagree on it, and one flipped ReLU changes the gradient by a whole
+ * term.  The tests ask for this number and take only cases in which every ReLU input is decided.
+ * Exact mode only.  Returns min over all ReLU inputs with a non-zero term sum of |v| / (|b| + sum_k |w_k x_k|), where
+ * the sum is that of the convolution or fully connected layer in front of the ReLU (a max pool in between passes the
+ * winner's sum on, an average pool the average of its window's sums); 1.0 if the network has no ReLU; NaN when P does
+ * not match.
+ */
+double cnn_min_relu_margin(const olayer* layers, int nlayers, int C, int H, int W, int N,
+                           const double* theta, long P, const double* x) {
+  size_t n0 = (size_t)N * C * H * W;
+  double* act = (double*)malloc(sizeof(double) * n0);
+  double* mag = (double*)malloc(sizeof(double) * n0);
+  memcpy(act, x, sizeof(double) * n0);
+  for (size_t i = 0; i < n0; i++) mag[i] = fabs(x[i]);
+  int c = C, h = H, w = W;
+  long pos = 0;
+  double worst = 1.0;
+  for (int li = 0; li < nlayers; li++) {
+    const olayer* L = &layers[li];
+    int oc = c, oh = h, ow = w;
+    if (L->type == L_CONV) { oc = L->a; oh = (h + 2 * L->d - L->b) / L->c + 1; ow = (w + 2 * L->d - L->b) / L->c + 1; }
+    else if (L->type == L_MAXPOOL || L->type == L_AVGPOOL) { oh = pool_out(h, L->a, L->b); ow = pool_out(w, L->a, L->b); }
+    else if (L->type == L_FC) { oc = L->a; oh = 1; ow = 1; }
+    size_t no = (size_t)N * oc * oh * ow, ni = (size_t)N * c * h * w;
+    double* out = (double*)malloc(sizeof(double) * no);
+    double* mout = (double*)malloc(sizeof(double) * no);
+    if (L->type == L_CONV || L->type == L_FC) {
+      long nw = L->type == L_CONV ? (long)oc * c * L->b * L->b : (long)oc * c * h * w;
+      if (pos + nw + oc > P) { free(out); free(mout); free(act); free(mag); return NAN; }
+      double* aw = (double*)malloc(sizeof(double) * (size_t)(nw + oc));
+      double* ax = (double*)malloc(sizeof(double) * ni);
+      for (long i = 0; i < nw + oc; i++) aw[i] = fabs(theta[pos + i]);
+      for (size_t i = 0; i < ni; i++) ax[i] = fabs(act[i]);
+      if (L->type == L_CONV) {
+        conv_forward(act, theta + pos, theta + pos + nw, out, N, c, h, w, oc, L->b, L->c, L->d);
+        conv_forward(ax, aw, aw + nw, mout, N, c, h, w, oc, L->b, L->c, L->d);
+      } else {
+        fc_forward(act, theta + pos, theta + pos + nw, out, N, c * h * w, oc);
+        fc_forward(ax, aw, aw + nw, mout, N, c * h * w, oc);
+      }
+      free(aw); free(ax);
+      pos += nw + oc;
+    } else if (L->type == L_MAXPOOL) {
+      int* arg = (int*)malloc(sizeof(int) * no);
+      maxpool_forward(act, out, arg, N * c, h, w, L->a, L->b);
+      for (size_t o = 0; o < no; o++) mout[o] = mag[(o / ((size_t)oh * ow)) * h * w + arg[o]];
+      free(arg);
+    } else if (L->type == L_AVGPOOL) {
+      avgpool_forward(act, out, N * c, h, w, L->a, L->b);
+      avgpool_forward(mag, mout, N * c, h, w, L->a, L->b);
+    } else {   /* L_RELU */
+      for (size_t i = 0; i < ni; i++) {
+        if (mag[i] > 0.0) { double m = fabs(act[i]) / mag[i]; if (m < worst) worst = m; }
+        out[i] = act[i] > 0.0 ? act[i] : 0.0;
+        mout[i] = out[i];
+      }
+    }
+    free(act); free(mag);
+    act = out; mag = mout;
+    c = oc; h = oh; w = ow;
+  }
+  free(act); free(mag);
+  return pos == P ? worst : NAN;
+}
+
 /* number of parameters of a layer table (for the parameter-count pins) */
 long cnn_num_params(const olayer* layers, int nlayers, int C, int H, int W) {
   long pos = 0;

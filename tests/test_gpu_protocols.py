@@ -78,3 +78,50 @@ def test_simulated_staleness_trace_replay():
     assert log == ref["log"]
     assert [t for (_, _, _, _, t) in log] == [int(min(s, i)) for i, s in enumerate(sched[:, 0])]
     assert rel(w - w0, ref["theta"] - w0) < 1e-3
+
+
+def test_constant_rate_diverges_and_staleness_rate_converges_through_the_server_kernels():
+    """The paper's central observation (Section 4.3) through the HIP server path: n-softsync with n = lambda (one
+    gradient per update, staleness p) on a linear least-squares model.  With the rate kept at alpha0 the delayed
+    iteration is unstable once alpha0 lambda_max exceeds 2 sin(pi / (2 (2p + 1))); with alpha0 / tau (Section 2.4) it
+    converges.  The learners' gradients A theta_j - b are formed on the host from the weight version the library holds
+    for timestamp j and pushed with that timestamp; pushGradientExternal / sumGradients / applyUpdate do the rest."""
+    from paper_1511_05950_amd import binding
+    rng = np.random.default_rng(11)
+    d, p, K = 48, 15, 600
+    Xm = rng.standard_normal((4 * d, d))
+    A = Xm.T @ Xm / (4 * d)
+    b = rng.standard_normal(d)
+    lam_max = np.linalg.eigvalsh(A).max()
+    alpha0 = 1.0 / lam_max                                   # stable without delay (limit 2 / lambda_max)
+    assert alpha0 * lam_max > 2 * np.sin(np.pi / (2 * (2 * p + 1)))
+    star = np.linalg.solve(A, b)
+    th0 = rng.standard_normal(d).astype(np.float32)
+    e0 = np.linalg.norm(th0 - star)
+    sched = np.full((K, 1), p)
+    grad_fn = lambda th, batch: (A @ th - b, 0.0)
+    out = {}
+    for mode in ("constant", "per_gradient"):
+        ctx = binding.Sasgd(p, 0, p, p + 1, net=None, num_params=d, lr_mode=mode, alpha0=alpha0, init_weights=th0)
+        log = []
+        for i in range(K):
+            tau = min(p, i)
+            th_j = ctx.copyWeights(i - tau).astype(np.float64)
+            g = torch.from_numpy((A @ th_j - b).astype(np.float32)).cuda()
+            assert ctx.pushGradientExternal(g, i - tau) == tau
+            ctx.sumGradients()
+            ctx.applyUpdate()
+            log.append((i, 0, i % p, i - tau, tau))
+            if not np.isfinite(th_j).all():
+                break
+        w = ctx.copyWeights().astype(np.float64)
+        ctx.destroy()
+        ref = protocol.run(grad_fn, th0, lambda i, l: None, sched, p, p, alpha0, mode=mode)
+        out[mode] = (w, ref, log)
+    w, ref, log = out["per_gradient"]
+    assert log == ref["log"]
+    assert np.linalg.norm(w - star) < 1e-2 * e0 and np.linalg.norm(ref["theta"] - star) < 1e-2 * e0      # converged
+    assert rel(w - th0, ref["theta"] - th0) < 1e-4
+    w, ref, log = out["constant"]
+    assert np.linalg.norm(ref["theta"] - star) > 1e3 * e0                                                 # the oracle diverges
+    assert (not np.isfinite(w).all()) or np.linalg.norm(w - star) > 1e3 * e0                              # and so do the kernels

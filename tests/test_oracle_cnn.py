@@ -290,3 +290,25 @@ def test_bf16_decision_flips_limit_reproducibility_on_deep_relu_nets():
         _, gr = cnn.loss_and_gradient(net, theta, x, y, round_bf16=True)
         out[name] = np.linalg.norm(gr - ge) / np.linalg.norm(ge)
     assert out["smooth"] < 1e-2 < out["deep"], out
+
+
+def test_min_relu_margin_hand_cases():
+    # 1x1 convolution over two channels of a 1x1 image: v = w0 x0 + w1 x1 + b in front of the ReLU
+    net = {"name": "m", "input": (2, 1, 1), "classes": 2, "layers": [("conv", 1, 1, 1, 0), ("relu",), ("fc", 2)]}
+    x = np.array([[[[1.0]], [[2.0]]]])
+    tail = [0.3, 0.0, -0.2, 0.0]
+    # v = 3 - 2*1 + 0.5 = 1.5, terms 3 + 2 + 0.5
+    assert abs(cnn.min_relu_margin(net, np.array([3.0, -1.0, 0.5] + tail), x) - 1.5 / 5.5) < 1e-15
+    # a nearly cancelling sum: v = 1e-9 of terms summing to 2
+    m = cnn.min_relu_margin(net, np.array([1.0, -(0.5 - 5e-10), 0.0] + tail), x)
+    assert abs(m - 1e-9 / 2.0) < 1e-15
+    # the minimum is taken over images and over every ReLU of the network, behind pooling layers too
+    net2 = {"name": "m2", "input": (1, 2, 2), "classes": 2,
+            "layers": [("conv", 1, 1, 1, 0), ("maxpool", 2, 2), ("relu",), ("fc", 2), ("relu",), ("fc", 2)]}
+    x2 = np.array([[[[1.0, -3.0], [0.5, 0.25]]], [[[4.0, 4.0], [4.0, 4.0]]]])
+    th2 = np.array([2.0, -1.0,            # conv: v = 2 x - 1 -> image 0 max at x = 1: v = 1, terms 2 + 1
+                    1.0, -1.0, 0.5, 0.25,  # fc 1 -> 2 on relu(v): image 0: 1.5 (terms 1.5), -0.75 (terms 1.25); image 1 (v = 7): 7.5, -6.75
+                    1.0, 0.0, 0.0, 1.0, 0.0, 0.0])
+    assert abs(cnn.min_relu_margin(net2, th2, x2) - 1.0 / 3.0) < 1e-15
+    with pytest.raises(ValueError):
+        cnn.min_relu_margin(net, np.zeros(3), x)
