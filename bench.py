@@ -223,6 +223,7 @@ def bench_net(args, cfg_id, prewarm=0, cold=False):
     dt = time.perf_counter() - t0
     ms_g, n_g = ctx.phaseTime(0)
     ms_u, n_u = ctx.phaseTime(1)
+    _, n_pass = ctx.phaseTime(2)   # passes over the vector: consecutive updates are applied in one pass (fused steps)
     P = ctx.P
     Wf = ctx.factoredParams()      # fully connected weights whose gradient is formed inside applyUpdate from its factors
     ctx.destroy()
@@ -236,9 +237,14 @@ def bench_net(args, cfg_id, prewarm=0, cold=False):
     # algorithmic bytes of one update: theta, v read and written, a 2-byte copy in bf16 compute, and 4 bytes per pending
     # gradient for every parameter whose gradient is a written-out vector
     upd_bytes = P * (16 + (0 if fp32 else 2)) + (P - Wf) * 4 * c
+    # algorithmic bytes of one pass that applies k updates: theta and v read once, v written once (fp32 master weights
+    # too in bf16 compute), and per update its weight version (fp32 ring slot or bf16 copy) and its gradients
+    k_pass = n_u / max(n_pass, 1)
+    pass_bytes = P * (12 + (0 if fp32 else 4)) + k_pass * (P * (4 if fp32 else 2) + (P - Wf) * 4 * c)
     how = ("cold start: the config's %d updates from theta_0, no warm-up update" % steps if cold else
            "steady state: %d + %d untimed updates first" % (prewarm, args.warmup) if prewarm else "%d untimed updates first" % args.warmup)
     upd_us = ms_u / n_u * 1e3
+    pass_us = ms_u / max(n_pass, 1) * 1e3
     out = {
         "metric": "training images/sec per GPU", "value": round(images / dt, 1), "unit": "images/s", "n_gpus": 1,
         "steps": steps, "warmup": warm, "ms_per_step": round(dt / steps * 1e3, 4),
@@ -250,12 +256,14 @@ def bench_net(args, cfg_id, prewarm=0, cold=False):
                                                 "flop = 2 x forward+backward MACs of %d images)" % (n_g, images),
                      "achieved": round(ach, 2), "peak": peak, "unit": "TFLOP/s", "frac": round(ach / peak, 5),
                      "traffic": None, "avg_call_us": round(t_grad / n_g * 1e6, 1), "learners_per_call": round(images / mu / n_g, 2)},
-        "roofline_hbm": {"bound": "hbm", "kernel": "applyUpdate as it runs inside the step (all launches of one update: the factored "
-                                                   "fully connected layers and the streaming remainder)" if Wf else
-                                                   "applyUpdate as it runs inside the step",
-                         "achieved": round(upd_bytes / (upd_us * 1e-6) / 1e9, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                         "frac": round(upd_bytes / (upd_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4), "traffic": None,
-                         "avg_launch_us": round(upd_us, 2), "bytes_per_launch": upd_bytes, "factored_fc_weights": Wf},
+        "roofline_hbm": {"bound": "hbm", "kernel": "applyUpdate as it runs inside the step: one pass over theta and v applies the updates that "
+                                                   "are ready together (%.2f per pass on average); bytes = theta, v read and v%s written once per "
+                                                   "pass + per update its weight version and its gradients" % (k_pass, "" if fp32 else ", theta"),
+                         "achieved": round(pass_bytes / (pass_us * 1e-6) / 1e9, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                         "frac": round(pass_bytes / (pass_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4), "traffic": None,
+                         "avg_launch_us": round(pass_us, 2), "bytes_per_launch": int(pass_bytes), "updates_per_pass": round(k_pass, 3),
+                         "per_update_us": round(upd_us, 2), "lone_update_bytes": upd_bytes,
+                         "lone_update_equivalent_GBs": round(upd_bytes / (upd_us * 1e-6) / 1e9, 1), "factored_fc_weights": Wf},
         "phase_ms_per_step": {"calcGradient": round(ms_g / steps, 4), "applyUpdate": round(ms_u / steps, 4)},
     }
     if not args.no_cpu:

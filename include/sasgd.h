@@ -53,7 +53,7 @@ enum { SASGD_FP32 = 0, SASGD_BF16 = 1 };
 enum { SASGD_LR_PER_GRADIENT = 0, SASGD_LR_MEAN_STALENESS = 1, SASGD_LR_CONSTANT = 2 };
 enum { SASGD_CONV = 0, SASGD_MAXPOOL = 1, SASGD_AVGPOOL = 2, SASGD_RELU = 3, SASGD_FC = 4 };
 /* flags */
-enum { SASGD_FLAG_FLAT_FC_GRADIENT = 1 };   /* see sasgd_config.flags */
+enum { SASGD_FLAG_FLAT_FC_GRADIENT = 1, SASGD_FLAG_EAGER_UPDATES = 2 };   /* see sasgd_config.flags */
 
 /* One layer of a custom network (SASGD_NET_CUSTOM).  The loss, softmax cross-entropy averaged
  * over the mini-batch, follows the last layer implicitly.
@@ -84,7 +84,10 @@ typedef struct {
                            (mu x out and mu x in values) and applyUpdate forms the product on the fly in the
                            same fp32 arithmetic.  The 4 bytes per weight of gradient written by the learner
                            and read by the server disappear; copyGradient / gradientPtr expand the product on
-                           demand.  The flag forces the written-out gradient instead.                        */
+                           demand.  The flag forces the written-out gradient instead.
+                           SASGD_FLAG_EAGER_UPDATES: applyUpdate enqueues its kernels before it returns.  By default
+                           the kernels of an update whose gradients all come from the library's learners wait until
+                           something needs their result (see sasgd_applyUpdate).                              */
   int64_t num_params;   /* NET_NONE: length P of the parameter vector; otherwise 0 or the expected
                            P, checked against the network                                            */
   float alpha0;         /* base learning rate                                                        */
@@ -149,8 +152,20 @@ int sasgd_sumGradients(sasgd_ctx* ctx, int32_t* out_pending);
 /* applyUpdate: theta_{i+1} = theta_i - v with v <- m v + sum_l coef_l g_l + (sum_l coef_l) wd theta_i
  * (the n-softsync rule of Section 2.2 when m = wd = 0), written to ring slot (i+1) mod R; the
  * timestamp becomes i+1.  Errors: ESTATE without a closed window; ERANGE if the slot to be
- * overwritten holds a version some learner has pulled but not yet used. */
+ * overwritten holds a version some learner has pulled but not yet used.
+ * Deferred launch: when every gradient of the window was computed by the library's learners (pushGradient) and the
+ * window has fewer than 25 gradients, the host bookkeeping is done at once but the kernels are enqueued later --
+ * at the next calcGradient, evaluate, getter, sasgd_flush or sasgd_destroy, or when 8 updates or 64 gradients have
+ * gathered -- so that consecutive updates become ONE pass over theta and v: they are read once, the steps are applied
+ * in order in registers (the arithmetic of the separate launches, bit for bit) and written once, and every step still
+ * writes its weight version.  With n = lambda (one gradient per update) this is most of the server's memory traffic.
+ * Windows holding a gradient pushed from outside (pushGradientExternal) are never deferred: their kernels are enqueued
+ * before applyUpdate returns, as SASGD_FLAG_EAGER_UPDATES makes every update do. */
 int sasgd_applyUpdate(sasgd_ctx* ctx, int64_t* out_new_timestamp);
+
+/* Enqueue the kernels of all deferred updates now (no-op if there are none).  Call it before waiting on the stream for
+ * the server's work, e.g. in front of a timing point. */
+int sasgd_flush(sasgd_ctx* ctx);
 
 /* applyUpdateNoAlloc: the server update for callers that cannot allocate device memory or create library objects
  * around a call -- code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  It is
@@ -223,7 +238,8 @@ int sasgd_gradientPtr(sasgd_ctx* ctx, int32_t learner, float** out_dev);
 
 /* Accumulated device time of the two hot phases since the last reset, measured with HIP events
  * on the context's stream when profiling is on (blocking query).
- * which: 0 = calcGradient launches, 1 = applyUpdate kernel. */
+ * which: 0 = calcGradient launches (calls = calcGradient calls), 1 = applyUpdate kernels (calls = updates applied),
+ * 2 = the same time as 1 with calls = passes over the vector (a pass applies one or several deferred updates). */
 int sasgd_setProfiling(sasgd_ctx* ctx, int32_t on);
 int sasgd_phaseTime(sasgd_ctx* ctx, int32_t which, double* out_ms_total, int64_t* out_calls);
 

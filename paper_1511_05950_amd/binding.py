@@ -20,6 +20,7 @@ LR_PER_GRADIENT, LR_MEAN_STALENESS, LR_CONSTANT = 0, 1, 2
 LAYER_KINDS = {"conv": 0, "maxpool": 1, "avgpool": 2, "relu": 3, "fc": 4}
 LR_MODES = {"per_gradient": 0, "mean_staleness": 1, "constant": 2}
 FLAG_FLAT_FC_GRADIENT = 1
+FLAG_EAGER_UPDATES = 2
 COMPUTE = {"fp32": 0, "bf16": 1}
 
 EXPORTS = [
@@ -29,7 +30,7 @@ EXPORTS = [
     "sasgd_copyWeights", "sasgd_copyGradient", "sasgd_copyMomentum", "sasgd_gradientPtr",
     "sasgd_setProfiling", "sasgd_phaseTime", "sasgd_last_error", "sasgd_version",
     "sasgd_evaluate", "sasgd_setBaseRate", "sasgd_setPixelMean", "sasgd_factoredParams",
-    "sasgd_applyUpdateNoAlloc",
+    "sasgd_applyUpdateNoAlloc", "sasgd_flush",
 ]
 
 
@@ -83,6 +84,7 @@ def load():
         lib.sasgd_pushGradientExternal.argtypes = [vp, vp, i64, P(i32)]
         lib.sasgd_sumGradients.argtypes = [vp, P(i32)]
         lib.sasgd_applyUpdate.argtypes = [vp, P(i64)]
+        lib.sasgd_flush.argtypes = [vp]
         lib.sasgd_timestamp.argtypes = [vp, P(i64)]
         lib.sasgd_numParams.argtypes = [vp, P(i64)]
         lib.sasgd_gradientsPerUpdate.argtypes = [vp, P(i32)]
@@ -238,6 +240,9 @@ class Sasgd:
         ts = ctypes.c_int64()
         self._check(load().sasgd_applyUpdate(self._h, ctypes.byref(ts)))
         return ts.value
+
+    def flush(self):
+        self._check(load().sasgd_flush(self._h))
 
     # -- getters
     def timestamp(self):

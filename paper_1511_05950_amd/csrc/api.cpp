@@ -66,10 +66,11 @@ const void* version_ptr(const sasgd_ctx* ctx, int64_t version) {
   return ctx->ring_f32 + (size_t)slot_of(ctx, version) * ctx->slot_elems_f32;
 }
 
-void prof_begin(sasgd_ctx* ctx, int which) {
+void prof_begin(sasgd_ctx* ctx, int which, int count = 1) {
   if (!ctx->profiling) return;
   sasgd_ctx::EvPair ev;
   ev.which = which;
+  ev.count = count;
   if (hipEventCreate(&ev.a) != hipSuccess || hipEventCreate(&ev.b) != hipSuccess) return;
   (void)hipEventRecord(ev.a, ctx->stream);
   ctx->events.push_back(ev);
@@ -83,7 +84,8 @@ void prof_collect(sasgd_ctx* ctx) {
     float ms = 0.f;
     if (hipEventSynchronize(ev.b) == hipSuccess && hipEventElapsedTime(&ms, ev.a, ev.b) == hipSuccess) {
       ctx->phase_ms[ev.which] += ms;
-      ctx->phase_calls[ev.which] += 1;
+      ctx->phase_calls[ev.which] += ev.count;
+      if (ev.which == 1) ctx->update_passes += 1;
     }
     (void)hipEventDestroy(ev.a);
     (void)hipEventDestroy(ev.b);
@@ -106,6 +108,135 @@ void window_coefficients(int lr_mode, float a0, int c, const int32_t* tau, float
       coef[l] = a / (float)c;
     }
   }
+}
+
+
+// Device work of `n` consecutive updates ctx->deferred[0 .. n): one launch per piece of the vector (flat stretch or
+// factored fully connected layer) that applies the n steps in order, then the per-version filter repack.
+hipError_t enqueue_updates(sasgd_ctx* ctx, int n) {
+  const std::vector<DeferredUpdate>& D = ctx->deferred;
+  const bool bf = ctx->cfg.compute == SASGD_BF16;
+  const size_t Ppad = ((size_t)ctx->P + 63) & ~(size_t)63;
+  UpdateLaunch u;
+  StepTable st;
+  memset(&st, 0, sizeof(st));
+  st.steps = n;
+  const Pending* src[kMaxLearners];
+  int total = 0;
+  bf16_t* slots_b16[kMaxFusedSteps] = {nullptr};
+  for (int t = 0; t < n; t++) {
+    st.first[t] = total;
+    for (size_t l = 0; l < D[(size_t)t].grads.size(); l++) {
+      src[total] = &D[(size_t)t].grads[l];
+      u.grads[total] = D[(size_t)t].grads[l].grad;
+      u.coef[total] = D[(size_t)t].coef[l];
+      total++;
+    }
+    st.decay[t] = D[(size_t)t].decay;
+    const int64_t made = D[(size_t)t].i + 1;
+    if (bf) {
+      slots_b16[t] = ctx->ring_b16 + (size_t)slot_of(ctx, made) * ctx->slot_elems_b16;
+      st.shadow_out[t] = slots_b16[t];
+    } else {
+      st.theta_out[t] = ctx->ring_f32 + (size_t)slot_of(ctx, made) * ctx->slot_elems_f32;
+    }
+  }
+  st.first[n] = total;
+  if (!bf)   // a ring slot that a later step of this pass takes again is not written twice
+    for (int t = 0; t < n; t++)
+      for (int t2 = t + 1; t2 < n; t2++)
+        if (st.theta_out[t2] == st.theta_out[t]) st.theta_out[t] = nullptr;
+  const int64_t i0 = D[0].i;
+  u.P = ctx->P;
+  u.c = total;
+  u.momentum = ctx->cfg.momentum;
+  u.decay = st.decay[0];
+  u.v = ctx->v;
+  u.sum_buf = ctx->sum_buf;
+  u.reverse = (int)(i0 & 1);   // consecutive single updates walk in opposite directions (last-level cache reuse)
+  u.theta_in = bf ? ctx->ring_f32 : ctx->ring_f32 + (size_t)slot_of(ctx, i0) * ctx->slot_elems_f32;
+  u.theta_out = bf ? ctx->ring_f32 : ctx->ring_f32 + (size_t)slot_of(ctx, i0 + 1) * ctx->slot_elems_f32;
+  u.shadow_out = st.shadow_out[0];
+  float* final_theta = bf ? ctx->ring_f32 : nullptr;   // fp32 compute: the last step's ring slot holds the result
+  // Layers whose gradients are kept as factors get their own launch; the stretches of the flat vector between them
+  // go through the streaming kernel.
+  FactoredLayer fl[kMaxFactoredLayers];
+  const int nfl = ctx->net ? net_factored_layers(ctx->net, fl, kMaxFactoredLayers) : 0;
+  prof_begin(ctx, 1, n);
+  hipError_t e = hipSuccess;
+  auto flat_range = [&](int64_t begin, int64_t end) {
+    if (end <= begin) return hipSuccess;
+    UpdateLaunch r = u;
+    r.theta_in += begin;
+    r.theta_out += begin;
+    r.v += begin;
+    if (r.shadow_out) r.shadow_out += begin;
+    for (int l = 0; l < total; l++) r.grads[l] += begin;
+    r.P = end - begin;
+    if (n == 1) return launch_apply_update(r, ctx->stream);
+    StepTable sr = st;
+    for (int t = 0; t < n; t++) {
+      if (sr.theta_out[t]) sr.theta_out[t] += begin;
+      if (sr.shadow_out[t]) sr.shadow_out[t] += begin;
+    }
+    return launch_apply_updates_fused(r, sr, final_theta ? final_theta + begin : nullptr, ctx->stream);
+  };
+  int64_t cursor = 0;
+  for (int k = 0; k < nfl && e == hipSuccess; k++) {
+    const FactoredLayer& F = fl[k];
+    e = flat_range(cursor, F.w_off);
+    if (e != hipSuccess) break;
+    FcUpdateLaunch fu;
+    fu.theta_in = u.theta_in + F.w_off;
+    fu.theta_out = u.theta_out + F.w_off;
+    fu.v = u.v + F.w_off;
+    fu.shadow_out = u.shadow_out ? u.shadow_out + F.w_off : nullptr;
+    fu.in = F.in; fu.out = F.out; fu.N = F.N; fu.NP = F.NP;
+    fu.c = total;
+    for (int l = 0; l < total; l++) {
+      const Pending& pd = *src[l];
+      fu.grads[l] = pd.grad + F.w_off;
+      fu.coef[l] = u.coef[l];
+      fu.fx[l] = pd.factors_ws ? (const bf16_t*)pd.factors_ws + F.fx_off : nullptr;
+      fu.fdyT[l] = pd.factors_ws ? (const bf16_t*)pd.factors_ws + F.fdy_off : nullptr;
+    }
+    fu.momentum = u.momentum;
+    fu.decay = u.decay;
+    StepTable sr = st;
+    for (int t = 0; t < n; t++)
+      if (sr.shadow_out[t]) sr.shadow_out[t] += F.w_off;
+    e = launch_apply_update_fc(fu, ctx->stream, &sr);
+    cursor = F.w_off + (int64_t)F.out * F.in + F.out;
+  }
+  if (e == hipSuccess) e = flat_range(cursor, ctx->P);
+  prof_end(ctx);
+  if (e == hipSuccess && bf && ctx->net) {
+    const void* flat[kMaxFusedSteps];
+    void* packed[kMaxFusedSteps];
+    for (int t = 0; t < n; t++) { flat[t] = slots_b16[t]; packed[t] = slots_b16[t] + Ppad; }
+    e = net_prepare_versions(ctx->net, flat, packed, n, ctx->stream);
+  }
+  return e;
+}
+
+// Launches the kernels of every deferred update, in order, as few passes over the vector as the tables allow.
+int flush_updates(sasgd_ctx* ctx) {
+  while (!ctx->deferred.empty()) {
+    int n = 0, total = 0;
+    while (n < (int)ctx->deferred.size() && n < kMaxFusedSteps && total + (int)ctx->deferred[(size_t)n].grads.size() <= kMaxLearners) {
+      total += (int)ctx->deferred[(size_t)n].grads.size();
+      n++;
+    }
+    if ((int)ctx->deferred[0].grads.size() >= kTwoPassMinC) n = 1;   // long windows go alone (two-pass form)
+    else
+      for (int t = 1; t < n; t++)
+        if ((int)ctx->deferred[(size_t)t].grads.size() >= kTwoPassMinC) { n = t; break; }
+    if (n < 1) n = 1;
+    hipError_t e = enqueue_updates(ctx, n);
+    ctx->deferred.erase(ctx->deferred.begin(), ctx->deferred.begin() + n);
+    if (e != hipSuccess) return fail_hip(ctx, e, "applyUpdate");
+  }
+  return SASGD_OK;
 }
 
 }  // namespace
@@ -228,6 +359,7 @@ int sasgd_create(const sasgd_config* cfg, const float* init_weights, sasgd_ctx**
 
 int sasgd_destroy(sasgd_ctx* ctx) {
   if (!ctx) return SASGD_EINVAL;
+  (void)flush_updates(ctx);
   (void)hipStreamSynchronize(ctx->stream);
   prof_collect(ctx);
   if (ctx->net) net_destroy(ctx->net);
@@ -270,6 +402,10 @@ int sasgd_calcGradient(sasgd_ctx* ctx, const int32_t* learners, int32_t count, f
   if (!ctx) return SASGD_EINVAL;
   if (!ctx->net) return fail(ctx, SASGD_EINVAL, "calcGradient: context has no network");
   if (!learners || count < 1 || count > ctx->cfg.lambda) return fail(ctx, SASGD_EINVAL, "calcGradient: bad learner list");
+  {   // the weight versions these learners read, and the buffers they overwrite, belong to updates that may still be deferred
+    const int rc = flush_updates(ctx);
+    if (rc != SASGD_OK) return rc;
+  }
   bool seen[kMaxLearners] = {false};
   LearnerBind binds[kMaxLearners];
   int ids[kMaxLearners];
@@ -309,6 +445,10 @@ int sasgd_evaluate(sasgd_ctx* ctx, const int32_t* learners, int32_t count, float
   if (!ctx->net) return fail(ctx, SASGD_EINVAL, "evaluate: context has no network");
   if (!learners || count < 1 || count > ctx->cfg.lambda) return fail(ctx, SASGD_EINVAL, "evaluate: bad learner list");
   if (!out_rank_dev || ((uintptr_t)out_rank_dev & 3)) return fail(ctx, SASGD_EINVAL, "evaluate: out_rank_dev must be a device int32 array");
+  {
+    const int rc = flush_updates(ctx);
+    if (rc != SASGD_OK) return rc;
+  }
   bool seen[kMaxLearners] = {false};
   LearnerBind binds[kMaxLearners];
   int ids[kMaxLearners];
@@ -409,92 +549,48 @@ int sasgd_applyUpdate(sasgd_ctx* ctx, int64_t* out_new_timestamp) {
       if (L.has_weights && !L.evaluated && L.pulled_version == evicted)
         return fail(ctx, SASGD_ERANGE, "applyUpdate: a learner still holds the version this update would overwrite");
   }
-  UpdateLaunch u;
-  u.P = ctx->P;
-  u.c = ctx->window_count;
+  DeferredUpdate d;
+  d.i = i;
   float abar = 0.f;
-  for (int l = 0; l < u.c; l++) {
-    u.grads[l] = ctx->pending[(size_t)l].grad;
-    u.coef[l] = ctx->window_coef[l];
+  bool own = true;                       // every gradient of the window lives in a learner's buffers
+  for (int l = 0; l < ctx->window_count; l++) {
+    d.grads.push_back(ctx->pending[(size_t)l]);
+    d.coef.push_back(ctx->window_coef[l]);
     abar += ctx->window_coef[l];
+    own = own && ctx->pending[(size_t)l].learner >= 0;
   }
-  u.momentum = ctx->cfg.momentum;
-  u.decay = abar * ctx->cfg.weight_decay;
-  u.v = ctx->v;
-  u.sum_buf = ctx->sum_buf;
-  u.reverse = (int)(i & 1);   // consecutive updates walk in opposite directions (last-level cache reuse)
-  const size_t Ppad = ((size_t)ctx->P + 63) & ~(size_t)63;
-  bf16_t* new_slot_b16 = nullptr;
-  if (ctx->cfg.compute == SASGD_BF16) {
-    u.theta_in = ctx->ring_f32;
-    u.theta_out = ctx->ring_f32;
-    new_slot_b16 = ctx->ring_b16 + (size_t)slot_of(ctx, i + 1) * ctx->slot_elems_b16;
-    u.shadow_out = new_slot_b16;
-  } else {
-    u.theta_in = ctx->ring_f32 + (size_t)slot_of(ctx, i) * ctx->slot_elems_f32;
-    u.theta_out = ctx->ring_f32 + (size_t)slot_of(ctx, i + 1) * ctx->slot_elems_f32;
-    u.shadow_out = nullptr;
+  d.decay = abar * ctx->cfg.weight_decay;
+  // Deferral: the kernels of consecutive updates are launched together, as one pass over the vector (fused steps),
+  // once something needs their result.  Only windows whose gradients the library owns wait (a caller's buffer may
+  // change as soon as this call returns), and long windows keep their two-pass form.
+  const bool defer = !(ctx->cfg.flags & SASGD_FLAG_EAGER_UPDATES) && own && ctx->window_count < kTwoPassMinC;
+  int queued = 0;
+  for (const DeferredUpdate& q : ctx->deferred) queued += (int)q.grads.size();
+  if (!defer || (int)ctx->deferred.size() == kMaxFusedSteps || queued + ctx->window_count > kMaxLearners) {
+    const int rc = flush_updates(ctx);
+    if (rc != SASGD_OK) return rc;
   }
-  // Layers whose gradients are kept as factors get their own launch; the stretches of the flat vector between them
-  // go through the streaming kernel.
-  FactoredLayer fl[kMaxFactoredLayers];
-  const int nfl = ctx->net ? net_factored_layers(ctx->net, fl, kMaxFactoredLayers) : 0;
-  prof_begin(ctx, 1);
-  hipError_t e = hipSuccess;
-  if (nfl == 0) {
-    e = launch_apply_update(u, ctx->stream);
-  } else {
-    auto flat_range = [&](int64_t begin, int64_t end) {
-      if (end <= begin) return hipSuccess;
-      UpdateLaunch r = u;
-      r.theta_in += begin;
-      r.theta_out += begin;
-      r.v += begin;
-      if (r.shadow_out) r.shadow_out += begin;
-      for (int l = 0; l < u.c; l++) r.grads[l] += begin;
-      r.P = end - begin;
-      return launch_apply_update(r, ctx->stream);
-    };
-    int64_t cursor = 0;
-    for (int k = 0; k < nfl && e == hipSuccess; k++) {
-      const FactoredLayer& F = fl[k];
-      e = flat_range(cursor, F.w_off);
-      if (e != hipSuccess) break;
-      FcUpdateLaunch fu;
-      fu.theta_in = u.theta_in + F.w_off;
-      fu.theta_out = u.theta_out + F.w_off;
-      fu.v = u.v + F.w_off;
-      fu.shadow_out = u.shadow_out ? u.shadow_out + F.w_off : nullptr;
-      fu.in = F.in; fu.out = F.out; fu.N = F.N; fu.NP = F.NP;
-      fu.c = u.c;
-      for (int l = 0; l < u.c; l++) {
-        const Pending& pd = ctx->pending[(size_t)l];
-        fu.grads[l] = pd.grad + F.w_off;
-        fu.coef[l] = u.coef[l];
-        fu.fx[l] = pd.factors_ws ? (const bf16_t*)pd.factors_ws + F.fx_off : nullptr;
-        fu.fdyT[l] = pd.factors_ws ? (const bf16_t*)pd.factors_ws + F.fdy_off : nullptr;
-      }
-      fu.momentum = u.momentum;
-      fu.decay = u.decay;
-      e = launch_apply_update_fc(fu, ctx->stream);
-      cursor = F.w_off + (int64_t)F.out * F.in + F.out;
-    }
-    if (e == hipSuccess) e = flat_range(cursor, ctx->P);
+  const int c_now = ctx->window_count;
+  ctx->deferred.push_back(std::move(d));
+  if (!defer) {
+    const int rc = flush_updates(ctx);
+    if (rc != SASGD_OK) { ctx->deferred.clear(); return rc; }
   }
-  prof_end(ctx);
-  if (e == hipSuccess && new_slot_b16 && ctx->net)
-    e = net_prepare_version(ctx->net, new_slot_b16, new_slot_b16 + Ppad, ctx->stream);
-  if (e != hipSuccess) return fail_hip(ctx, e, "applyUpdate");
-  for (int l = 0; l < u.c; l++) {
+  for (int l = 0; l < c_now; l++) {
     const int lr = ctx->pending[(size_t)l].learner;
     if (lr >= 0) ctx->learners[(size_t)lr].grad_state = GRAD_NONE;
   }
-  ctx->pending.erase(ctx->pending.begin(), ctx->pending.begin() + u.c);
+  ctx->pending.erase(ctx->pending.begin(), ctx->pending.begin() + c_now);
   ctx->window_closed = false;
   ctx->window_count = 0;
   ctx->timestamp = i + 1;   // every weight update increments the timestamp by one (Section 2.1)
   if (out_new_timestamp) *out_new_timestamp = ctx->timestamp;
   return SASGD_OK;
+}
+
+int sasgd_flush(sasgd_ctx* ctx) {
+  if (!ctx) return SASGD_EINVAL;
+  return flush_updates(ctx);
 }
 
 int sasgd_applyUpdateNoAlloc(const float* theta_in_dev, float* theta_out_dev, float* v_dev, uint16_t* shadow_out_dev,
@@ -578,6 +674,10 @@ int sasgd_gradientTimestamp(sasgd_ctx* ctx, int32_t learner, int64_t* out) {
 int sasgd_copyWeights(sasgd_ctx* ctx, int64_t version, float* host_out) {
   if (!ctx || !host_out) return SASGD_EINVAL;
   if (!version_in_ring(ctx, version)) return fail(ctx, SASGD_ERANGE, "copyWeights: version not in the ring");
+  {
+    const int rc = flush_updates(ctx);
+    if (rc != SASGD_OK) return rc;
+  }
   const size_t bytes = (size_t)ctx->P * sizeof(float);
   hipError_t e;
   if (ctx->cfg.compute == SASGD_BF16 && version != ctx->timestamp) {
@@ -621,6 +721,10 @@ int sasgd_copyGradient(sasgd_ctx* ctx, int32_t learner, float* host_out) {
   Learner& L = ctx->learners[(size_t)learner];
   if (!L.grad) return fail(ctx, SASGD_EINVAL, "copyGradient: context has no network");
   if (L.grad_timestamp < 0) return fail(ctx, SASGD_ESTATE, "copyGradient: learner has not computed a gradient");
+  {
+    const int rc = flush_updates(ctx);
+    if (rc != SASGD_OK) return rc;
+  }
   hipError_t e = expand_factored(ctx, L);
   if (e == hipSuccess) e = hipMemcpyAsync(host_out, L.grad, (size_t)ctx->P * sizeof(float), hipMemcpyDeviceToHost, ctx->stream);
   if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
@@ -630,6 +734,10 @@ int sasgd_copyGradient(sasgd_ctx* ctx, int32_t learner, float* host_out) {
 
 int sasgd_copyMomentum(sasgd_ctx* ctx, float* host_out) {
   if (!ctx || !host_out) return SASGD_EINVAL;
+  {
+    const int rc = flush_updates(ctx);
+    if (rc != SASGD_OK) return rc;
+  }
   hipError_t e = hipMemcpyAsync(host_out, ctx->v, (size_t)ctx->P * sizeof(float), hipMemcpyDeviceToHost, ctx->stream);
   if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
   if (e != hipSuccess) return fail_hip(ctx, e, "copyMomentum");
@@ -639,6 +747,10 @@ int sasgd_copyMomentum(sasgd_ctx* ctx, float* host_out) {
 int sasgd_gradientPtr(sasgd_ctx* ctx, int32_t learner, float** out_dev) {
   if (!ctx || !out_dev || learner < 0 || learner >= ctx->cfg.lambda) return SASGD_EINVAL;
   if (!ctx->learners[(size_t)learner].grad) return fail(ctx, SASGD_EINVAL, "gradientPtr: context has no network");
+  {
+    const int rc = flush_updates(ctx);
+    if (rc != SASGD_OK) return rc;
+  }
   hipError_t e = expand_factored(ctx, ctx->learners[(size_t)learner]);
   if (e != hipSuccess) return fail_hip(ctx, e, "gradientPtr");
   *out_dev = ctx->learners[(size_t)learner].grad;
@@ -647,18 +759,21 @@ int sasgd_gradientPtr(sasgd_ctx* ctx, int32_t learner, float** out_dev) {
 
 int sasgd_setProfiling(sasgd_ctx* ctx, int32_t on) {
   if (!ctx) return SASGD_EINVAL;
+  (void)flush_updates(ctx);
   prof_collect(ctx);
   ctx->profiling = on != 0;
   ctx->phase_ms[0] = ctx->phase_ms[1] = 0.0;
   ctx->phase_calls[0] = ctx->phase_calls[1] = 0;
+  ctx->update_passes = 0;
   return SASGD_OK;
 }
 
 int sasgd_phaseTime(sasgd_ctx* ctx, int32_t which, double* out_ms_total, int64_t* out_calls) {
-  if (!ctx || which < 0 || which > 1) return SASGD_EINVAL;
+  if (!ctx || which < 0 || which > 2) return SASGD_EINVAL;
+  (void)flush_updates(ctx);
   prof_collect(ctx);
-  if (out_ms_total) *out_ms_total = ctx->phase_ms[which];
-  if (out_calls) *out_calls = ctx->phase_calls[which];
+  if (out_ms_total) *out_ms_total = ctx->phase_ms[which == 2 ? 1 : which];
+  if (out_calls) *out_calls = which == 2 ? ctx->update_passes : ctx->phase_calls[which];
   return SASGD_OK;
 }
 

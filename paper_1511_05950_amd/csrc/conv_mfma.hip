@@ -34,7 +34,9 @@ constexpr int LDA = BK + 8;      // row stride (elements) of k-contiguous LDS ti
 // fwd: B = Wp[n][tap][cp] (k = tap * C + cp, Kp = padded ks*ks*C);   rows beyond K and k beyond the filter are zero
 // bwd: B = Wt[c][tap'][n] (k = tap' * K + n, tap' = flipped tap, Kpt = padded ks*ks*K), stride-1 layers only
 // One thread produces one lane's 16-byte chunk (8 consecutive k of one row); index arithmetic is 32-bit.
-__global__ __launch_bounds__(256) void pack_filters_kernel(const bf16_t* __restrict__ flat, bf16_t* __restrict__ packed, PackTable t) {
+__global__ __launch_bounds__(256) void pack_filters_kernel(PackVersions pv, PackTable t) {
+  const bf16_t* __restrict__ flat = (const bf16_t*)pv.flat[blockIdx.y];      // blockIdx.y = weight version
+  bf16_t* __restrict__ packed = (bf16_t*)pv.packed[blockIdx.y];
   const int64_t chunks = t.total >> 3;
   for (int64_t gc = (int64_t)blockIdx.x * 256 + threadIdx.x; gc < chunks; gc += (int64_t)gridDim.x * 256) {
     int li = 0;                                   // layer this chunk belongs to
@@ -97,7 +99,9 @@ struct PackFastTable {
 };
 constexpr int kPackMaxTaps = 25;
 
-__global__ __launch_bounds__(256) void pack_filters_lds_kernel(const bf16_t* __restrict__ flat, bf16_t* __restrict__ packed, PackFastTable t) {
+__global__ __launch_bounds__(256) void pack_filters_lds_kernel(PackVersions pv, PackFastTable t) {
+  const bf16_t* __restrict__ flat = (const bf16_t*)pv.flat[blockIdx.y];      // blockIdx.y = weight version
+  bf16_t* __restrict__ packed = (bf16_t*)pv.packed[blockIdx.y];
   __shared__ __attribute__((aligned(16))) bf16_t tile[32 * 16 * kPackMaxTaps];
   int li = 0;
   while (li + 1 < t.count && (int)blockIdx.x >= t.job[li + 1].first_block) li++;
@@ -143,8 +147,9 @@ __global__ __launch_bounds__(256) void pack_filters_lds_kernel(const bf16_t* __r
   }
 }
 
-hipError_t launch_pack_filters(const void* flat, void* packed, const PackTable& t, hipStream_t s) {
-  if (t.count == 0 || t.total == 0) return hipSuccess;
+hipError_t launch_pack_filters(const PackVersions& pv, int versions, const PackTable& t, hipStream_t s) {
+  if (t.count == 0 || t.total == 0 || versions < 1) return hipSuccess;
+  if (versions > kMaxPackVersions) return hipErrorInvalidValue;
   PackTable slow;
   PackFastTable fast;
   slow.count = 0; slow.total = 0;
@@ -171,10 +176,10 @@ hipError_t launch_pack_filters(const void* flat, void* packed, const PackTable& 
   if (slow.count > 0) {
     const int64_t chunks = slow.total / 8;
     int blocks = (int)((chunks + 255) / 256 < 8192 ? (chunks + 255) / 256 : 8192);
-    hipLaunchKernelGGL(pack_filters_kernel, dim3(blocks), dim3(256), 0, s, (const bf16_t*)flat, (bf16_t*)packed, slow);
+    hipLaunchKernelGGL(pack_filters_kernel, dim3(blocks, (unsigned)versions), dim3(256), 0, s, pv, slow);
   }
   if (fast.count > 0)
-    hipLaunchKernelGGL(pack_filters_lds_kernel, dim3((unsigned)blocks_fast), dim3(256), 0, s, (const bf16_t*)flat, (bf16_t*)packed, fast);
+    hipLaunchKernelGGL(pack_filters_lds_kernel, dim3((unsigned)blocks_fast, (unsigned)versions), dim3(256), 0, s, pv, fast);
   return hipGetLastError();
 }
 

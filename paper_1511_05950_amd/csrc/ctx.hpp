@@ -29,10 +29,26 @@ struct UpdateLaunch {
   int reverse;             // walk the vector from its end (same result; see apply_update_kernel)
   float* sum_buf;          // kSumStretch floats for the two-pass form of long windows, or nullptr: always one pass
 };
+// Several consecutive updates in ONE pass over the vector ("fused steps"): theta and v are read once, the steps are applied
+// one after the other in registers -- the arithmetic of the single launches in the same order, bit-identical -- and
+// written once; every step still writes its own weight version (ring slot / bf16 copy).  Step t owns the gradient-table
+// entries [first[t], first[t + 1]).
+constexpr int kMaxFusedSteps = 8;
+struct StepTable {
+  int32_t steps;
+  int32_t first[kMaxFusedSteps + 1];
+  float decay[kMaxFusedSteps];          // (sum of the step's coefficients) * weight_decay
+  float* theta_out[kMaxFusedSteps];     // fp32 weights after step t (ring slot), or nullptr: not kept (fp32 master in place)
+  bf16_t* shadow_out[kMaxFusedSteps];   // bf16 copy of the weights after step t, or nullptr
+};
 // Windows of at least kTwoPassMinC gradients are applied in two passes per stretch of kSumStretch parameters.
 constexpr int kTwoPassMinC = 25;
 constexpr int64_t kSumStretch = (int64_t)1 << 21;   // 8 MiB of sums: 512 workgroups of 4 096 parameters
 hipError_t launch_apply_update(const UpdateLaunch& u, hipStream_t stream);
+// Fused steps over a flat stretch: u supplies theta_in, v, P, momentum, the gradient table (u.c entries in all, at most
+// kMaxLearners) -- its theta_out / shadow_out / decay are ignored in favour of st's per-step ones; the weights after the
+// last step are also written to `final_theta` (may be theta_in).
+hipError_t launch_apply_updates_fused(const UpdateLaunch& u, const StepTable& st, float* final_theta, hipStream_t stream);
 // Device address, on the current device, of the library's statically allocated buffer of kSumStretch floats (looked up
 // once per device; no allocation).  Every caller on a device shares it: launches that use it must not overlap.
 hipError_t static_sum_buffer(float** out);
@@ -52,7 +68,9 @@ struct FcUpdateLaunch {
   float momentum;
   float decay;
 };
-hipError_t launch_apply_update_fc(const FcUpdateLaunch& u, hipStream_t stream);
+// st == nullptr: one step (u.shadow_out, u.decay).  Otherwise fused steps: st's first / decay / shadow_out are used (its
+// theta_out is ignored: the layer's weights are written once, to u.theta_out).
+hipError_t launch_apply_update_fc(const FcUpdateLaunch& u, hipStream_t stream, const StepTable* st = nullptr);
 hipError_t launch_fp32_to_bf16(const float* src, bf16_t* dst, int64_t n, hipStream_t stream);
 hipError_t launch_bf16_to_fp32(const bf16_t* src, float* dst, int64_t n, hipStream_t stream);
 
@@ -73,6 +91,8 @@ size_t net_workspace_bytes(const Net* net);
 hipError_t net_set_workspace(Net* net, int learner, void* ws, hipStream_t stream);
 // Per weight version: derive the kernel-friendly copies (bf16 repacked conv filters) from the flat vector.
 hipError_t net_prepare_version(Net* net, const void* flat, void* packed, hipStream_t stream);
+// The same for several versions in one launch per kernel.
+hipError_t net_prepare_versions(Net* net, const void* const* flat, void* const* packed, int versions, hipStream_t stream);
 // out_rank_dev == nullptr: forward, loss, backward (gradients into binds[k].grad).
 // out_rank_dev != nullptr: evaluation pass, forward and loss only, plus the rank of each image's true class.
 hipError_t net_calc_gradient(Net* net, const int* learners, const LearnerBind* binds, int count,
@@ -107,12 +127,23 @@ struct Learner {
   bool fc_expanded = false;    // the factored parts of the current gradient have been written out into `grad`
 };
 
+struct Pending;
+// An update whose window is closed and whose host bookkeeping is done, but whose device work has not been enqueued yet.
+struct DeferredUpdate;
+
 struct Pending {
   const void* factors_ws;   // workspace holding the fully connected factors of this gradient, or nullptr (written out)
   const float* grad;
   int64_t timestamp;   // j
   int32_t staleness;   // tau = i - j at push time
   int32_t learner;     // -1 for external gradients
+};
+
+struct DeferredUpdate {
+  int64_t i = 0;                 // timestamp before the update: it makes version i + 1
+  std::vector<Pending> grads;    // the window, in arrival order
+  std::vector<float> coef;
+  float decay = 0.f;             // (sum of coefficients) * weight_decay
 };
 
 }  // namespace sasgd
@@ -133,6 +164,7 @@ struct sasgd_ctx {
   float* sum_buf = nullptr;          // [kSumStretch] partial result of long windows (c >= kTwoPassMinC), else nullptr
   std::vector<sasgd::Learner> learners;
   std::vector<sasgd::Pending> pending;
+  std::vector<sasgd::DeferredUpdate> deferred;   // updates applied on the host whose kernels are not launched yet
   bool window_closed = false;
   int32_t window_count = 0;
   float window_coef[sasgd::kMaxLearners];
@@ -141,8 +173,9 @@ struct sasgd_ctx {
   std::string error;
   // profiling
   bool profiling = false;
-  struct EvPair { hipEvent_t a, b; int which; };
+  struct EvPair { hipEvent_t a, b; int which; int count; };
   std::vector<EvPair> events;
   double phase_ms[2] = {0, 0};
   int64_t phase_calls[2] = {0, 0};
+  int64_t update_passes = 0;         // launches groups of the update phase (one pass may apply several updates)
 };

@@ -119,7 +119,13 @@ struct PackTable {
   int count;
   int64_t total;
 };
-hipError_t launch_pack_filters(const void* flat, void* packed, const PackTable& t, hipStream_t s);
+// Several weight versions in one launch (blockIdx.y): flat bf16 vector and packed-filter region of each.
+constexpr int kMaxPackVersions = 8;
+struct PackVersions {
+  const void* flat[kMaxPackVersions];
+  void* packed[kMaxPackVersions];
+};
+hipError_t launch_pack_filters(const PackVersions& pv, int versions, const PackTable& t, hipStream_t s);
 // ---- fp32 MFMA path (conv_mfma_f32.hip); dgrad: g gathers over dy, the filter is read transposed and flipped
 hipError_t launch_igemm_f32(const PtrTab& ws, const CPtrTab& wts, const IGemm& g, const VConv& v, const Epilogue& ep, int64_t w_off,
                             bool dgrad, int count, hipStream_t s);

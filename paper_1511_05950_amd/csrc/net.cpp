@@ -6,6 +6,7 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <algorithm>
 #include <vector>
 
 #include "kernels.hpp"
@@ -356,9 +357,19 @@ hipError_t net_set_workspace(Net* net, int learner, void* ws, hipStream_t stream
 #define TRY(x) do { hipError_t e__ = (x); if (e__ != hipSuccess) return e__; } while (0)
 
 // Derive the packed bf16 filters of every MFMA convolution from the flat bf16 copy of one weight version.
-hipError_t net_prepare_version(Net* net, const void* flat, void* packed, hipStream_t stream) {
+hipError_t net_prepare_versions(Net* net, const void* const* flat, void* const* packed, int versions, hipStream_t stream) {
   if (net->pack.count == 0) return hipSuccess;
-  return launch_pack_filters(flat, packed, net->pack, stream);
+  for (int v0 = 0; v0 < versions; v0 += kMaxPackVersions) {
+    PackVersions pv;
+    memset(&pv, 0, sizeof(pv));
+    const int nv = std::min(kMaxPackVersions, versions - v0);
+    for (int k = 0; k < nv; k++) { pv.flat[k] = flat[v0 + k]; pv.packed[k] = packed[v0 + k]; }
+    TRY(launch_pack_filters(pv, nv, net->pack, stream));
+  }
+  return hipSuccess;
+}
+hipError_t net_prepare_version(Net* net, const void* flat, void* packed, hipStream_t stream) {
+  return net_prepare_versions(net, &flat, &packed, 1, stream);
 }
 
 // fp32 MFMA path: 128 x 32 tiles, contraction steps of 16 (four 4-channel chunks)

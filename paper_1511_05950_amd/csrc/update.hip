@@ -21,6 +21,8 @@
 #include "ctx.hpp"
 #include "dev_common.hpp"
 
+#include <string.h>
+
 #include <algorithm>
 #include <mutex>
 
@@ -211,6 +213,93 @@ __global__ __launch_bounds__(256) void sum_gradients_kernel(float4* __restrict__
   }
 }
 
+// Fused steps over a flat stretch (see StepTable): per element the operations of apply_update_kernel, step after step.
+template <int ILP>
+__global__ __launch_bounds__(256) void apply_updates_fused_kernel(const float4* theta_in, float4* theta_final, float4* v, int64_t n4,
+                                                                  GradTable t, StepTable st, float m) {
+  const int64_t base = (int64_t)blockIdx.x * (256 * ILP) + threadIdx.x;
+  float4 th[ILP], vv[ILP];
+#pragma unroll
+  for (int e = 0; e < ILP; e++) {
+    const int64_t i = base + e * 256;
+    if (i < n4) { th[e] = ldg_nt(theta_in + i); vv[e] = ldg_nt(v + i); }
+  }
+  for (int step = 0; step < st.steps; step++) {
+    float4 s[ILP];
+#pragma unroll
+    for (int e = 0; e < ILP; e++) s[e] = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int l = st.first[step]; l < st.first[step + 1]; l++) {   // arrival order
+      const float cf = t.coef[l];
+      float4 g[ILP];
+#pragma unroll
+      for (int e = 0; e < ILP; e++) {
+        const int64_t i = base + e * 256;
+        if (i < n4) g[e] = ldg_nt(reinterpret_cast<const float4*>(t.g[l]) + i);
+      }
+#pragma unroll
+      for (int e = 0; e < ILP; e++) {
+        s[e].x = fmaf(cf, g[e].x, s[e].x);
+        s[e].y = fmaf(cf, g[e].y, s[e].y);
+        s[e].z = fmaf(cf, g[e].z, s[e].z);
+        s[e].w = fmaf(cf, g[e].w, s[e].w);
+      }
+    }
+    const float decay = st.decay[step];
+    float4* tout = reinterpret_cast<float4*>(st.theta_out[step]);
+    uint2* shadow = reinterpret_cast<uint2*>(st.shadow_out[step]);
+#pragma unroll
+    for (int e = 0; e < ILP; e++) {
+      const int64_t i = base + e * 256;
+      if (i < n4) {
+        float4 a = th[e], b = vv[e];
+        b.x = fmaf(m, b.x, s[e].x) + decay * a.x;
+        b.y = fmaf(m, b.y, s[e].y) + decay * a.y;
+        b.z = fmaf(m, b.z, s[e].z) + decay * a.z;
+        b.w = fmaf(m, b.w, s[e].w) + decay * a.w;
+        a.x -= b.x;
+        a.y -= b.y;
+        a.z -= b.z;
+        a.w -= b.w;
+        th[e] = a;
+        vv[e] = b;
+        if (tout) stg_nt(tout + i, a);
+        if (shadow) {
+          uint2 o;
+          o.x = (uint32_t)f2bf(a.x) | ((uint32_t)f2bf(a.y) << 16);
+          o.y = (uint32_t)f2bf(a.z) | ((uint32_t)f2bf(a.w) << 16);
+          shadow[i] = o;
+        }
+      }
+    }
+  }
+#pragma unroll
+  for (int e = 0; e < ILP; e++) {
+    const int64_t i = base + e * 256;
+    if (i < n4) {
+      stg_nt(v + i, vv[e]);
+      if (theta_final) stg_nt(theta_final + i, th[e]);
+    }
+  }
+}
+
+// Scalar tail of the fused steps (P not a multiple of 4): at most 3 elements.
+__global__ void apply_updates_fused_tail_kernel(const float* theta_in, float* theta_final, float* v, int64_t begin, int64_t P, GradTable t,
+                                                StepTable st, float m) {
+  const int64_t i = begin + threadIdx.x;
+  if (i >= P) return;
+  float th = theta_in[i], vv = v[i];
+  for (int step = 0; step < st.steps; step++) {
+    float s = 0.f;
+    for (int l = st.first[step]; l < st.first[step + 1]; l++) s = fmaf(t.coef[l], t.g[l][i], s);
+    vv = fmaf(m, vv, s) + st.decay[step] * th;
+    th = th - vv;
+    if (st.theta_out[step]) st.theta_out[step][i] = th;
+    if (st.shadow_out[step]) st.shadow_out[step][i] = f2bf(th);
+  }
+  v[i] = vv;
+  if (theta_final) theta_final[i] = th;
+}
+
 // Scalar tail (P not a multiple of 4): at most 3 elements.
 __global__ void apply_update_tail_kernel(const float* theta_in, float* theta_out, float* v, bf16_t* shadow,
                                          int64_t begin, int64_t P, int c, GradTable t, float m, float decay) {
@@ -296,6 +385,30 @@ hipError_t launch_apply_update(const UpdateLaunch& u, hipStream_t stream) {
   return hipSuccess;
 }
 
+hipError_t launch_apply_updates_fused(const UpdateLaunch& u, const StepTable& st, float* final_theta, hipStream_t stream) {
+  if (u.P <= 0) return hipSuccess;
+  if (st.steps < 1 || st.steps > kMaxFusedSteps || st.first[0] != 0 || st.first[st.steps] != u.c || u.c > kMaxLearners) return hipErrorInvalidValue;
+  if (u.P / 4 > (int64_t)0x7fffffff * 256) return hipErrorInvalidValue;
+  GradTable t;
+  for (int l = 0; l < kMaxLearners; l++) {
+    t.g[l] = l < u.c ? u.grads[l] : nullptr;
+    t.coef[l] = l < u.c ? u.coef[l] : 0.f;
+  }
+  const int64_t n4 = u.P / 4;
+  if (n4 > 0) {
+    const int blocks = (int)((n4 + 256 * 4 - 1) / (256 * 4));
+    hipLaunchKernelGGL((apply_updates_fused_kernel<4>), dim3(blocks), dim3(256), 0, stream, reinterpret_cast<const float4*>(u.theta_in),
+                       reinterpret_cast<float4*>(final_theta), reinterpret_cast<float4*>(u.v), n4, t, st, u.momentum);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  if (n4 * 4 < u.P) {
+    hipLaunchKernelGGL(apply_updates_fused_tail_kernel, dim3(1), dim3(64), 0, stream, u.theta_in, final_theta, u.v, n4 * 4, u.P, t, st, u.momentum);
+    return hipGetLastError();
+  }
+  return hipSuccess;
+}
+
 // ------------------------------------------------------------------ update of a fully connected layer from factors
 // For a fully connected layer with a mini-batch of N images the weight gradient is dW[o][i] = sum_n dy[n][o] x[n][i].
 // A learner keeps x [N][in] and dy transposed [out][NP] (bf16) instead of writing dW; this kernel forms the product
@@ -311,86 +424,110 @@ struct FcFactors {
 
 constexpr int kFcRows = 4;           // output units per workgroup (2, 8 and 16 measured slower at config 4)
 
+// Steps: see StepTable (one step = the plain update; st.theta_out is not used here, the weights are written once).
 template <bool SHADOW>
-__global__ __launch_bounds__(256) void apply_update_fc_kernel(const float* theta_in, float* theta_out, float* v, bf16_t* shadow, int in,
-                                                              int out, int N, int NP, int c, GradTable t, FcFactors f, float m,
-                                                              float decay) {
+__global__ __launch_bounds__(256) void apply_update_fc_kernel(const float* theta_in, float* theta_out, float* v, int in, int out, int N,
+                                                              int NP, GradTable t, FcFactors f, StepTable st, float m) {
   const int nrb = (out + kFcRows - 1) / kFcRows;
   const int col = (blockIdx.x * 256 + threadIdx.x) * 4;
   if ((int)blockIdx.y == nrb) {       // bias: elements out * in + col .. col + 3
     if (col >= out) return;
     const int64_t e = (int64_t)out * in + col;
-    float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
-    for (int l = 0; l < c; l++) {
-      const float4 g = *reinterpret_cast<const float4*>(t.g[l] + e);
-      s.x = fmaf(t.coef[l], g.x, s.x); s.y = fmaf(t.coef[l], g.y, s.y);
-      s.z = fmaf(t.coef[l], g.z, s.z); s.w = fmaf(t.coef[l], g.w, s.w);
-    }
     float4 a = *reinterpret_cast<const float4*>(theta_in + e), b = *reinterpret_cast<const float4*>(v + e);
-    b.x = fmaf(m, b.x, s.x) + decay * a.x; b.y = fmaf(m, b.y, s.y) + decay * a.y;
-    b.z = fmaf(m, b.z, s.z) + decay * a.z; b.w = fmaf(m, b.w, s.w) + decay * a.w;
-    a.x -= b.x; a.y -= b.y; a.z -= b.z; a.w -= b.w;
+    for (int step = 0; step < st.steps; step++) {
+      float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+      for (int l = st.first[step]; l < st.first[step + 1]; l++) {
+        const float4 g = *reinterpret_cast<const float4*>(t.g[l] + e);
+        s.x = fmaf(t.coef[l], g.x, s.x); s.y = fmaf(t.coef[l], g.y, s.y);
+        s.z = fmaf(t.coef[l], g.z, s.z); s.w = fmaf(t.coef[l], g.w, s.w);
+      }
+      const float decay = st.decay[step];
+      b.x = fmaf(m, b.x, s.x) + decay * a.x; b.y = fmaf(m, b.y, s.y) + decay * a.y;
+      b.z = fmaf(m, b.z, s.z) + decay * a.z; b.w = fmaf(m, b.w, s.w) + decay * a.w;
+      a.x -= b.x; a.y -= b.y; a.z -= b.z; a.w -= b.w;
+      if (SHADOW) {
+        uint2 o;
+        o.x = (uint32_t)f2bf(a.x) | ((uint32_t)f2bf(a.y) << 16);
+        o.y = (uint32_t)f2bf(a.z) | ((uint32_t)f2bf(a.w) << 16);
+        *reinterpret_cast<uint2*>(st.shadow_out[step] + e) = o;
+      }
+    }
     *reinterpret_cast<float4*>(v + e) = b;
     *reinterpret_cast<float4*>(theta_out + e) = a;
-    if (SHADOW) {
-      uint2 o;
-      o.x = (uint32_t)f2bf(a.x) | ((uint32_t)f2bf(a.y) << 16);
-      o.y = (uint32_t)f2bf(a.z) | ((uint32_t)f2bf(a.w) << 16);
-      *reinterpret_cast<uint2*>(shadow + e) = o;
-    }
     return;
   }
   if (col >= in) return;
   const int o0 = blockIdx.y * kFcRows;
-  float4 th[kFcRows], vv[kFcRows], s[kFcRows];
+  float4 th[kFcRows], vv[kFcRows];
 #pragma unroll
   for (int r = 0; r < kFcRows; r++) {
-    s[r] = make_float4(0.f, 0.f, 0.f, 0.f);
     if (o0 + r < out) {
       const int64_t e = (int64_t)(o0 + r) * in + col;
       th[r] = ldg_nt(reinterpret_cast<const float4*>(theta_in + e));
       vv[r] = ldg_nt(reinterpret_cast<const float4*>(v + e));
     }
   }
-  for (int l = 0; l < c; l++) {
-    const float cf = t.coef[l];
-    if (f.x[l]) {
-      float4 p[kFcRows];
+  for (int step = 0; step < st.steps; step++) {
+    float4 s[kFcRows];
 #pragma unroll
-      for (int r = 0; r < kFcRows; r++) p[r] = make_float4(0.f, 0.f, 0.f, 0.f);
-      for (int n0 = 0; n0 < NP; n0 += 8) {
-        uint2 xr[8];
+    for (int r = 0; r < kFcRows; r++) s[r] = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int l = st.first[step]; l < st.first[step + 1]; l++) {
+      const float cf = t.coef[l];
+      if (f.x[l]) {
+        float4 p[kFcRows];
 #pragma unroll
-        for (int k = 0; k < 8; k++)
-          xr[k] = n0 + k < N ? *reinterpret_cast<const uint2*>(f.x[l] + (int64_t)(n0 + k) * in + col) : make_uint2(0u, 0u);
+        for (int r = 0; r < kFcRows; r++) p[r] = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int n0 = 0; n0 < NP; n0 += 8) {
+          uint2 xr[8];
+#pragma unroll
+          for (int k = 0; k < 8; k++)
+            xr[k] = n0 + k < N ? *reinterpret_cast<const uint2*>(f.x[l] + (int64_t)(n0 + k) * in + col) : make_uint2(0u, 0u);
+#pragma unroll
+          for (int r = 0; r < kFcRows; r++) {
+            const int o = min(o0 + r, out - 1);           // rows beyond the layer compute a value nobody stores
+            const uint4 d8 = *reinterpret_cast<const uint4*>(f.dyT[l] + (int64_t)o * NP + n0);   // same address for the whole workgroup
+            const uint32_t dw[4] = {d8.x, d8.y, d8.z, d8.w};
+#pragma unroll
+            for (int k = 0; k < 8; k++) {
+              const float d = __uint_as_float((k & 1) ? (dw[k >> 1] & 0xffff0000u) : (dw[k >> 1] << 16));
+              p[r].x = fmaf(d, __uint_as_float(xr[k].x << 16), p[r].x);
+              p[r].y = fmaf(d, __uint_as_float(xr[k].x & 0xffff0000u), p[r].y);
+              p[r].z = fmaf(d, __uint_as_float(xr[k].y << 16), p[r].z);
+              p[r].w = fmaf(d, __uint_as_float(xr[k].y & 0xffff0000u), p[r].w);
+            }
+          }
+        }
 #pragma unroll
         for (int r = 0; r < kFcRows; r++) {
-          const int o = min(o0 + r, out - 1);           // rows beyond the layer compute a value nobody stores
-          const uint4 d8 = *reinterpret_cast<const uint4*>(f.dyT[l] + (int64_t)o * NP + n0);   // same address for the whole workgroup
-          const uint32_t dw[4] = {d8.x, d8.y, d8.z, d8.w};
+          s[r].x = fmaf(cf, p[r].x, s[r].x); s[r].y = fmaf(cf, p[r].y, s[r].y);
+          s[r].z = fmaf(cf, p[r].z, s[r].z); s[r].w = fmaf(cf, p[r].w, s[r].w);
+        }
+      } else {
 #pragma unroll
-          for (int k = 0; k < 8; k++) {
-            const float d = __uint_as_float((k & 1) ? (dw[k >> 1] & 0xffff0000u) : (dw[k >> 1] << 16));
-            p[r].x = fmaf(d, __uint_as_float(xr[k].x << 16), p[r].x);
-            p[r].y = fmaf(d, __uint_as_float(xr[k].x & 0xffff0000u), p[r].y);
-            p[r].z = fmaf(d, __uint_as_float(xr[k].y << 16), p[r].z);
-            p[r].w = fmaf(d, __uint_as_float(xr[k].y & 0xffff0000u), p[r].w);
+        for (int r = 0; r < kFcRows; r++) {
+          if (o0 + r < out) {
+            const float4 g = ldg_nt(reinterpret_cast<const float4*>(t.g[l] + (int64_t)(o0 + r) * in + col));
+            s[r].x = fmaf(cf, g.x, s[r].x); s[r].y = fmaf(cf, g.y, s[r].y);
+            s[r].z = fmaf(cf, g.z, s[r].z); s[r].w = fmaf(cf, g.w, s[r].w);
           }
         }
       }
+    }
+    const float decay = st.decay[step];
 #pragma unroll
-      for (int r = 0; r < kFcRows; r++) {
-        s[r].x = fmaf(cf, p[r].x, s[r].x); s[r].y = fmaf(cf, p[r].y, s[r].y);
-        s[r].z = fmaf(cf, p[r].z, s[r].z); s[r].w = fmaf(cf, p[r].w, s[r].w);
-      }
-    } else {
-#pragma unroll
-      for (int r = 0; r < kFcRows; r++) {
-        if (o0 + r < out) {
-          const float4 g = ldg_nt(reinterpret_cast<const float4*>(t.g[l] + (int64_t)(o0 + r) * in + col));
-          s[r].x = fmaf(cf, g.x, s[r].x); s[r].y = fmaf(cf, g.y, s[r].y);
-          s[r].z = fmaf(cf, g.z, s[r].z); s[r].w = fmaf(cf, g.w, s[r].w);
-        }
+    for (int r = 0; r < kFcRows; r++) {
+      if (o0 + r >= out) continue;
+      float4 a = th[r], b = vv[r];
+      b.x = fmaf(m, b.x, s[r].x) + decay * a.x; b.y = fmaf(m, b.y, s[r].y) + decay * a.y;
+      b.z = fmaf(m, b.z, s[r].z) + decay * a.z; b.w = fmaf(m, b.w, s[r].w) + decay * a.w;
+      a.x -= b.x; a.y -= b.y; a.z -= b.z; a.w -= b.w;
+      th[r] = a;
+      vv[r] = b;
+      if (SHADOW) {
+        uint2 o;
+        o.x = (uint32_t)f2bf(a.x) | ((uint32_t)f2bf(a.y) << 16);
+        o.y = (uint32_t)f2bf(a.z) | ((uint32_t)f2bf(a.w) << 16);
+        *reinterpret_cast<uint2*>(st.shadow_out[step] + (int64_t)(o0 + r) * in + col) = o;
       }
     }
   }
@@ -398,22 +535,12 @@ __global__ __launch_bounds__(256) void apply_update_fc_kernel(const float* theta
   for (int r = 0; r < kFcRows; r++) {
     if (o0 + r >= out) continue;
     const int64_t e = (int64_t)(o0 + r) * in + col;
-    float4 a = th[r], b = vv[r];
-    b.x = fmaf(m, b.x, s[r].x) + decay * a.x; b.y = fmaf(m, b.y, s[r].y) + decay * a.y;
-    b.z = fmaf(m, b.z, s[r].z) + decay * a.z; b.w = fmaf(m, b.w, s[r].w) + decay * a.w;
-    a.x -= b.x; a.y -= b.y; a.z -= b.z; a.w -= b.w;
-    stg_nt(reinterpret_cast<float4*>(v + e), b);
-    stg_nt(reinterpret_cast<float4*>(theta_out + e), a);
-    if (SHADOW) {
-      uint2 o;
-      o.x = (uint32_t)f2bf(a.x) | ((uint32_t)f2bf(a.y) << 16);
-      o.y = (uint32_t)f2bf(a.z) | ((uint32_t)f2bf(a.w) << 16);
-      *reinterpret_cast<uint2*>(shadow + e) = o;
-    }
+    stg_nt(reinterpret_cast<float4*>(v + e), vv[r]);
+    stg_nt(reinterpret_cast<float4*>(theta_out + e), th[r]);
   }
 }
 
-hipError_t launch_apply_update_fc(const FcUpdateLaunch& u, hipStream_t stream) {
+hipError_t launch_apply_update_fc(const FcUpdateLaunch& u, hipStream_t stream, const StepTable* steps) {
   if (u.in < 4 || u.out < 4 || (u.in & 3) || (u.out & 3) || u.c < 1 || u.c > kMaxLearners) return hipErrorInvalidValue;
   GradTable t;
   FcFactors f;
@@ -423,14 +550,28 @@ hipError_t launch_apply_update_fc(const FcUpdateLaunch& u, hipStream_t stream) {
     f.x[l] = l < u.c ? u.fx[l] : nullptr;
     f.dyT[l] = l < u.c ? u.fdyT[l] : nullptr;
   }
+  StepTable st;
+  if (steps) {
+    st = *steps;
+    if (st.steps < 1 || st.steps > kMaxFusedSteps || st.first[0] != 0 || st.first[st.steps] != u.c) return hipErrorInvalidValue;
+  } else {
+    memset(&st, 0, sizeof(st));
+    st.steps = 1;
+    st.first[1] = u.c;
+    st.decay[0] = u.decay;
+    st.shadow_out[0] = u.shadow_out;
+  }
+  bool shadow = st.shadow_out[0] != nullptr;
+  for (int k = 0; k < st.steps; k++)
+    if ((st.shadow_out[k] != nullptr) != shadow) return hipErrorInvalidValue;
   const int widest = u.in > u.out ? u.in : u.out;
   dim3 grid((unsigned)((widest + 1023) / 1024), (unsigned)((u.out + kFcRows - 1) / kFcRows + 1));
-  if (u.shadow_out)
-    hipLaunchKernelGGL((apply_update_fc_kernel<true>), grid, dim3(256), 0, stream, u.theta_in, u.theta_out, u.v, u.shadow_out, u.in, u.out,
-                       u.N, u.NP, u.c, t, f, u.momentum, u.decay);
+  if (shadow)
+    hipLaunchKernelGGL((apply_update_fc_kernel<true>), grid, dim3(256), 0, stream, u.theta_in, u.theta_out, u.v, u.in, u.out, u.N, u.NP, t, f,
+                       st, u.momentum);
   else
-    hipLaunchKernelGGL((apply_update_fc_kernel<false>), grid, dim3(256), 0, stream, u.theta_in, u.theta_out, u.v, u.shadow_out, u.in, u.out,
-                       u.N, u.NP, u.c, t, f, u.momentum, u.decay);
+    hipLaunchKernelGGL((apply_update_fc_kernel<false>), grid, dim3(256), 0, stream, u.theta_in, u.theta_out, u.v, u.in, u.out, u.N, u.NP, t, f,
+                       st, u.momentum);
   return hipGetLastError();
 }
 

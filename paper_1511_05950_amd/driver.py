@@ -43,6 +43,7 @@ def run_softsync(ctx, schedule, batch_of, lam, loss_out=None, on_gradient=None, 
             ctx.setBaseRate(float(base_rates[k]))
         ctx.sumGradients()
         ctx.applyUpdate()
+    ctx.flush()                                 # nothing of this run is left waiting for a later call
     return log
 
 
@@ -88,6 +89,7 @@ def run_softsync_batched(ctx, schedule, batch_of, lam, loss_out=None, first_upda
             log.append((i, l, learner, j, tau))
         ctx.sumGradients()
         ctx.applyUpdate()
+    ctx.flush()
     return log, calls
 
 
