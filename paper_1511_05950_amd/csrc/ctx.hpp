@@ -62,7 +62,7 @@ struct FcUpdateLaunch {
   int in, out, N, NP;      // N images per mini-batch, dyT rows padded to NP
   int32_t c;
   const float* grads[kMaxLearners];     // written-out gradient of every pending gradient (bias part always used)
-  const bf16_t* fx[kMaxLearners];       // factor x [N][in], or nullptr: use the written-out weights gradient
+  const bf16_t* fx[kMaxLearners];       // factor x transposed [in][NP], or nullptr: use the written-out weights gradient
   const bf16_t* fdyT[kMaxLearners];     // factor dy transposed [out][NP]
   float coef[kMaxLearners];
   float momentum;

@@ -713,9 +713,10 @@ hipError_t launch_label_rank(bool is_bf16, bool z_f32, const PtrTab& ws, const C
 
 // ------------------------------------------------------------------ fully connected weight gradient as factors
 // The weight gradient of a fully connected layer over a mini-batch of N images is the rank-N product
-// dW[o][i] = sum_n dy[n][o] x[n][i].  Instead of writing out * in values, keep the factors: a copy of x [N][in]
-// and dy transposed to [out][NP] (NP = N rounded up to 8, zero-filled), so that the update kernel reads the N values
-// of one output unit as contiguous 16-byte pieces.  The bias gradient db[o] = sum_n dy[n][o] is written out.
+// dW[o][i] = sum_n dy[n][o] x[n][i].  Instead of writing out * in values, keep the factors, both with the images
+// innermost: x transposed to [in][NP] and dy transposed to [out][NP] (NP = N rounded up to 8, zero-filled), so that the
+// update kernel reads the N values of one unit as contiguous 16-byte pieces (the k-contiguous operands of an MFMA).
+// The bias gradient db[o] = sum_n dy[n][o] is written out.
 __global__ __launch_bounds__(256) void fc_save_factors_kernel(PtrTab ws, PtrTab grads, size_t x_off, size_t dy_off, size_t fx_off,
                                                               size_t fdy_off, int64_t b_off, int N, int in, int out, int NP) {
   const bf16_t* x = (const bf16_t*)ws.p[blockIdx.z] + x_off;
@@ -723,10 +724,21 @@ __global__ __launch_bounds__(256) void fc_save_factors_kernel(PtrTab ws, PtrTab 
   bf16_t* fx = (bf16_t*)ws.p[blockIdx.z] + fx_off;
   bf16_t* fdy = (bf16_t*)ws.p[blockIdx.z] + fdy_off;
   float* db = (float*)grads.p[blockIdx.z] + b_off;
-  const int xchunks = N * in / 8;
+  const int xchunks = in / 8;                 // one thread turns 8 input units x 8 images around at a time
   const int t = blockIdx.x * 256 + threadIdx.x;
   if (t < xchunks) {
-    reinterpret_cast<uint4*>(fx)[t] = reinterpret_cast<const uint4*>(x)[t];
+    for (int n0 = 0; n0 < NP; n0 += 8) {
+      union { uint4 q; bf16_t h[8]; } src[8], dst[8];
+#pragma unroll
+      for (int k = 0; k < 8; k++)
+        src[k].q = n0 + k < N ? *reinterpret_cast<const uint4*>(x + (int64_t)(n0 + k) * in + t * 8) : make_uint4(0u, 0u, 0u, 0u);
+#pragma unroll
+      for (int e = 0; e < 8; e++)
+#pragma unroll
+        for (int k = 0; k < 8; k++) dst[e].h[k] = src[k].h[e];
+#pragma unroll
+      for (int e = 0; e < 8; e++) *reinterpret_cast<uint4*>(fx + (int64_t)(t * 8 + e) * NP + n0) = dst[e].q;
+    }
   } else if (t - xchunks < out) {
     const int o = t - xchunks;
     float sum = 0.f;
@@ -739,8 +751,8 @@ __global__ __launch_bounds__(256) void fc_save_factors_kernel(PtrTab ws, PtrTab 
   }
 }
 
-// dW[o][i] = sum_n dy[n][o] x[n][i] from the saved factors, in the arithmetic the update kernel uses (fp32 FMA in
-// image order): the written-out gradient for the getters.  Four input units per thread.
+// dW[o][i] = sum_n dy[n][o] x[n][i] from the saved factors (fp32 FMA in image order): the written-out gradient for the
+// getters.  Four input units per thread.
 __global__ __launch_bounds__(256) void fc_expand_factors_kernel(const bf16_t* __restrict__ fx, const bf16_t* __restrict__ fdy,
                                                                 float* __restrict__ dw, int N, int in, int out, int NP) {
   const int64_t total4 = (int64_t)out * in / 4;
@@ -749,11 +761,10 @@ __global__ __launch_bounds__(256) void fc_expand_factors_kernel(const bf16_t* __
     float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
     for (int n = 0; n < N; n++) {
       const float d = bf2f(fdy[(int64_t)o * NP + n]);
-      const uint2 xv = *reinterpret_cast<const uint2*>(fx + (int64_t)n * in + i);
-      a0 = fmaf(d, __uint_as_float(xv.x << 16), a0);
-      a1 = fmaf(d, __uint_as_float(xv.x & 0xffff0000u), a1);
-      a2 = fmaf(d, __uint_as_float(xv.y << 16), a2);
-      a3 = fmaf(d, __uint_as_float(xv.y & 0xffff0000u), a3);
+      a0 = fmaf(d, bf2f(fx[(int64_t)(i + 0) * NP + n]), a0);
+      a1 = fmaf(d, bf2f(fx[(int64_t)(i + 1) * NP + n]), a1);
+      a2 = fmaf(d, bf2f(fx[(int64_t)(i + 2) * NP + n]), a2);
+      a3 = fmaf(d, bf2f(fx[(int64_t)(i + 3) * NP + n]), a3);
     }
     *reinterpret_cast<float4*>(dw + (int64_t)o * in + i) = make_float4(a0, a1, a2, a3);
   }
@@ -761,7 +772,7 @@ __global__ __launch_bounds__(256) void fc_expand_factors_kernel(const bf16_t* __
 
 hipError_t launch_fc_save_factors(const PtrTab& ws, const PtrTab& grads, size_t x_off, size_t dy_off, size_t fx_off, size_t fdy_off,
                                   int64_t b_off, int N, int in, int out, int NP, int count, hipStream_t s) {
-  const int work = N * in / 8 + out;
+  const int work = in / 8 + out;
   hipLaunchKernelGGL(fc_save_factors_kernel, dim3((unsigned)((work + 255) / 256), 1, (unsigned)count), dim3(256), 0, s, ws, grads, x_off,
                      dy_off, fx_off, fdy_off, b_off, N, in, out, NP);
   return hipGetLastError();

@@ -33,7 +33,7 @@ struct Op {
   bool dgrad_bt = false;       // fc: B operand is the flat weight matrix read transposed
   int64_t pack_fwd = -1, pack_bwd = -1;   // element offsets in the packed-filter region of a version slot
   int Kp = 0, Kpt = 0;
-  // fully connected layer whose weight gradient is kept as the factors x [N][in] and dy^T [out][NP]
+  // fully connected layer whose weight gradient is kept as the factors x^T [in][NP] and dy^T [out][NP]
   bool factored = false;
   size_t fx_off = 0, fdy_off = 0;         // element offsets of the two factor copies in the workspace
   int NP = 0;
@@ -265,7 +265,7 @@ int net_create(const sasgd_config& cfg, Net** out, int64_t* out_P, size_t* out_p
   }
   for (Op& op : net->ops) {
     if (!op.factored) continue;
-    op.fx_off = net->tensors[(size_t)new_tensor((size_t)N * op.cs.C)].off;
+    op.fx_off = net->tensors[(size_t)new_tensor((size_t)op.cs.C * op.NP)].off;
     op.fdy_off = net->tensors[(size_t)new_tensor((size_t)op.cs.K * op.NP)].off;
   }
   net->P = P;

@@ -410,27 +410,40 @@ hipError_t launch_apply_updates_fused(const UpdateLaunch& u, const StepTable& st
 }
 
 // ------------------------------------------------------------------ update of a fully connected layer from factors
-// For a fully connected layer with a mini-batch of N images the weight gradient is dW[o][i] = sum_n dy[n][o] x[n][i].
-// A learner keeps x [N][in] and dy transposed [out][NP] (bf16) instead of writing dW; this kernel forms the product
-// while it streams theta and v: per gradient  p = sum_n dy x  (fp32 FMA in image order, the arithmetic of the
-// written-out gradient),  s += coef * p,  then the same update as apply_update_kernel.  HBM traffic per weight drops
-// by the 4 bytes of gradient; the N FMAs per weight are far below what the streaming rate leaves room for.
-// Gradients without factors (pushed from outside) are read as written-out vectors.  The layer's bias follows its
-// weights in the flat vector and is updated by one extra row of workgroups from the written-out bias gradients.
+// For a fully connected layer with a mini-batch of N images the weight gradient is the rank-N product
+// dW[o][i] = sum_n dy[n][o] x[n][i].  A learner keeps the two factors transposed, dyT [out][NP] and xT [in][NP] (bf16, NP = N
+// rounded up to 8, zero-filled), instead of writing dW, and this kernel forms the product while it streams theta and v:
+// one bf16 MFMA (32 x 32 x 16, fp32 accumulation) yields the gradient of a 32 x 32 block of weights from two 1 KiB operand
+// reads -- both factors are k-contiguous, so the fragments come straight from memory.  HBM traffic per weight drops by the
+// 4 bytes of gradient, and with several steps fused theta and v pass through once for all of them.
+// A wavefront owns 32 output units x 32 input units.  theta, v and the running sums live in registers in row-major order
+// (8 lanes x 16 bytes cover the 128 contiguous bytes of a row); a product leaves the matrix cores in MFMA order and is
+// turned around through the wavefront's own piece of LDS.  Gradients without factors (pushed from outside) are read as
+// written-out vectors, in the same order.  Per element: p_l = product (or the written-out value), s = sum_l coef_l p_l in
+// arrival order, then the update of apply_update_kernel.  The layer's bias follows its weights in the flat vector and is
+// updated by one extra row of workgroups from the written-out bias gradients.
 struct FcFactors {
-  const bf16_t* x[kMaxLearners];     // [N][in] or nullptr: gradient l is a written-out vector
+  const bf16_t* xT[kMaxLearners];    // [in][NP] or nullptr: gradient l is a written-out vector
   const bf16_t* dyT[kMaxLearners];   // [out][NP]
 };
 
-constexpr int kFcRows = 4;           // output units per workgroup (2, 8 and 16 measured slower at config 4)
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16_t;
 
-// Steps: see StepTable (one step = the plain update; st.theta_out is not used here, the weights are written once).
+constexpr int kFcTileRows = 32, kFcTileCols = 32;     // per wavefront
+constexpr int kFcCB = kFcTileCols / 32;               // MFMA column blocks per wavefront
+constexpr int kFcLPR = kFcTileCols / 4;               // lanes per tile row in row-major order (16 bytes each)
+constexpr int kFcRPI = 64 / kFcLPR;                   // tile rows one 64-lane access covers
+constexpr int kFcNQ = kFcTileRows / kFcRPI;           // 16-byte pieces per lane and array
+constexpr int kFcLds = kFcTileCols + 4;               // LDS row stride in floats
+
 template <bool SHADOW>
 __global__ __launch_bounds__(256) void apply_update_fc_kernel(const float* theta_in, float* theta_out, float* v, int in, int out, int N,
                                                               int NP, GradTable t, FcFactors f, StepTable st, float m) {
-  const int nrb = (out + kFcRows - 1) / kFcRows;
-  const int col = (blockIdx.x * 256 + threadIdx.x) * 4;
+  __shared__ __attribute__((aligned(16))) float lds[4 * kFcTileRows * kFcLds];
+  const int nrb = (out + kFcTileRows - 1) / kFcTileRows;
   if ((int)blockIdx.y == nrb) {       // bias: elements out * in + col .. col + 3
+    const int col = (blockIdx.x * 256 + threadIdx.x) * 4;
     if (col >= out) return;
     const int64_t e = (int64_t)out * in + col;
     float4 a = *reinterpret_cast<const float4*>(theta_in + e), b = *reinterpret_cast<const float4*>(v + e);
@@ -456,87 +469,105 @@ __global__ __launch_bounds__(256) void apply_update_fc_kernel(const float* theta
     *reinterpret_cast<float4*>(theta_out + e) = a;
     return;
   }
-  if (col >= in) return;
-  const int o0 = blockIdx.y * kFcRows;
-  float4 th[kFcRows], vv[kFcRows];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int o0 = blockIdx.y * kFcTileRows;
+  const int w0 = (blockIdx.x * 4 + wave) * kFcTileCols;
+  if (w0 >= in) return;               // whole wavefronts leave: no workgroup barrier below
+  float* tile = lds + wave * (kFcTileRows * kFcLds);
+  // row-major registers: piece q is row kFcRPI q + lane / kFcLPR, columns 4 (lane % kFcLPR) .. + 3 of the tile
+  const int rr = lane / kFcLPR, cc = (lane % kFcLPR) * 4;
+  const bool col_ok = w0 + cc < in;   // in is a multiple of 4
+  float4 th[kFcNQ], vv[kFcNQ];
 #pragma unroll
-  for (int r = 0; r < kFcRows; r++) {
-    if (o0 + r < out) {
-      const int64_t e = (int64_t)(o0 + r) * in + col;
-      th[r] = ldg_nt(reinterpret_cast<const float4*>(theta_in + e));
-      vv[r] = ldg_nt(reinterpret_cast<const float4*>(v + e));
+  for (int q = 0; q < kFcNQ; q++) {
+    const int o = o0 + kFcRPI * q + rr;
+    if (o < out && col_ok) {
+      const int64_t e = (int64_t)o * in + w0 + cc;
+      th[q] = ldg_nt(reinterpret_cast<const float4*>(theta_in + e));
+      vv[q] = ldg_nt(reinterpret_cast<const float4*>(v + e));
     }
   }
+  // MFMA operands: lane (j = lane % 32, h = lane / 32) holds k = 8 h .. 8 h + 7 of row / column j
+  const int j = lane & 31, h = lane >> 5;
+  const int KB = (NP + 15) >> 4;
   for (int step = 0; step < st.steps; step++) {
-    float4 s[kFcRows];
+    float4 s[kFcNQ];
 #pragma unroll
-    for (int r = 0; r < kFcRows; r++) s[r] = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int q = 0; q < kFcNQ; q++) s[q] = make_float4(0.f, 0.f, 0.f, 0.f);
     for (int l = st.first[step]; l < st.first[step + 1]; l++) {
       const float cf = t.coef[l];
-      if (f.x[l]) {
-        float4 p[kFcRows];
+      if (f.xT[l]) {
+        floatx16_t p[kFcCB];
 #pragma unroll
-        for (int r = 0; r < kFcRows; r++) p[r] = make_float4(0.f, 0.f, 0.f, 0.f);
-        for (int n0 = 0; n0 < NP; n0 += 8) {
-          uint2 xr[8];
+        for (int b = 0; b < kFcCB; b++)
 #pragma unroll
-          for (int k = 0; k < 8; k++)
-            xr[k] = n0 + k < N ? *reinterpret_cast<const uint2*>(f.x[l] + (int64_t)(n0 + k) * in + col) : make_uint2(0u, 0u);
+          for (int r = 0; r < 16; r++) p[b][r] = 0.f;
+        for (int kb = 0; kb < KB; kb++) {
+          const int n0 = 16 * kb + 8 * h;
+          union { uint4 u; bf16x8_t x; } fa, fb[kFcCB];
+          fa.u = make_uint4(0u, 0u, 0u, 0u);
+          if (n0 < NP && o0 + j < out) fa.u = *reinterpret_cast<const uint4*>(f.dyT[l] + (int64_t)(o0 + j) * NP + n0);
 #pragma unroll
-          for (int r = 0; r < kFcRows; r++) {
-            const int o = min(o0 + r, out - 1);           // rows beyond the layer compute a value nobody stores
-            const uint4 d8 = *reinterpret_cast<const uint4*>(f.dyT[l] + (int64_t)o * NP + n0);   // same address for the whole workgroup
-            const uint32_t dw[4] = {d8.x, d8.y, d8.z, d8.w};
-#pragma unroll
-            for (int k = 0; k < 8; k++) {
-              const float d = __uint_as_float((k & 1) ? (dw[k >> 1] & 0xffff0000u) : (dw[k >> 1] << 16));
-              p[r].x = fmaf(d, __uint_as_float(xr[k].x << 16), p[r].x);
-              p[r].y = fmaf(d, __uint_as_float(xr[k].x & 0xffff0000u), p[r].y);
-              p[r].z = fmaf(d, __uint_as_float(xr[k].y << 16), p[r].z);
-              p[r].w = fmaf(d, __uint_as_float(xr[k].y & 0xffff0000u), p[r].w);
-            }
+          for (int b = 0; b < kFcCB; b++) {
+            fb[b].u = make_uint4(0u, 0u, 0u, 0u);
+            if (n0 < NP && w0 + 32 * b + j < in) fb[b].u = *reinterpret_cast<const uint4*>(f.xT[l] + (int64_t)(w0 + 32 * b + j) * NP + n0);
           }
-        }
 #pragma unroll
-        for (int r = 0; r < kFcRows; r++) {
-          s[r].x = fmaf(cf, p[r].x, s[r].x); s[r].y = fmaf(cf, p[r].y, s[r].y);
-          s[r].z = fmaf(cf, p[r].z, s[r].z); s[r].w = fmaf(cf, p[r].w, s[r].w);
+          for (int b = 0; b < kFcCB; b++) p[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa.x, fb[b].x, p[b], 0, 0, 0);
         }
+        // MFMA order (column 32 b + j, rows 8 (r / 4) + 4 h + r % 4) -> row-major, through this wavefront's LDS piece
+#pragma unroll
+        for (int b = 0; b < kFcCB; b++)
+#pragma unroll
+          for (int r = 0; r < 16; r++) tile[(8 * (r >> 2) + 4 * h + (r & 3)) * kFcLds + 32 * b + j] = p[b][r];
+        __builtin_amdgcn_wave_barrier();
+        asm volatile("" ::: "memory");
+#pragma unroll
+        for (int q = 0; q < kFcNQ; q++) {
+          const float4 g = *reinterpret_cast<const float4*>(tile + (kFcRPI * q + rr) * kFcLds + cc);
+          s[q].x = fmaf(cf, g.x, s[q].x); s[q].y = fmaf(cf, g.y, s[q].y);
+          s[q].z = fmaf(cf, g.z, s[q].z); s[q].w = fmaf(cf, g.w, s[q].w);
+        }
+        __builtin_amdgcn_wave_barrier();
+        asm volatile("" ::: "memory");
       } else {
 #pragma unroll
-        for (int r = 0; r < kFcRows; r++) {
-          if (o0 + r < out) {
-            const float4 g = ldg_nt(reinterpret_cast<const float4*>(t.g[l] + (int64_t)(o0 + r) * in + col));
-            s[r].x = fmaf(cf, g.x, s[r].x); s[r].y = fmaf(cf, g.y, s[r].y);
-            s[r].z = fmaf(cf, g.z, s[r].z); s[r].w = fmaf(cf, g.w, s[r].w);
+        for (int q = 0; q < kFcNQ; q++) {
+          const int o = o0 + kFcRPI * q + rr;
+          if (o < out && col_ok) {
+            const float4 g = ldg_nt(reinterpret_cast<const float4*>(t.g[l] + (int64_t)o * in + w0 + cc));
+            s[q].x = fmaf(cf, g.x, s[q].x); s[q].y = fmaf(cf, g.y, s[q].y);
+            s[q].z = fmaf(cf, g.z, s[q].z); s[q].w = fmaf(cf, g.w, s[q].w);
           }
         }
       }
     }
     const float decay = st.decay[step];
 #pragma unroll
-    for (int r = 0; r < kFcRows; r++) {
-      if (o0 + r >= out) continue;
-      float4 a = th[r], b = vv[r];
-      b.x = fmaf(m, b.x, s[r].x) + decay * a.x; b.y = fmaf(m, b.y, s[r].y) + decay * a.y;
-      b.z = fmaf(m, b.z, s[r].z) + decay * a.z; b.w = fmaf(m, b.w, s[r].w) + decay * a.w;
+    for (int q = 0; q < kFcNQ; q++) {
+      const int o = o0 + kFcRPI * q + rr;
+      if (o >= out || !col_ok) continue;
+      float4 a = th[q], b = vv[q];
+      b.x = fmaf(m, b.x, s[q].x) + decay * a.x; b.y = fmaf(m, b.y, s[q].y) + decay * a.y;
+      b.z = fmaf(m, b.z, s[q].z) + decay * a.z; b.w = fmaf(m, b.w, s[q].w) + decay * a.w;
       a.x -= b.x; a.y -= b.y; a.z -= b.z; a.w -= b.w;
-      th[r] = a;
-      vv[r] = b;
+      th[q] = a;
+      vv[q] = b;
       if (SHADOW) {
-        uint2 o;
-        o.x = (uint32_t)f2bf(a.x) | ((uint32_t)f2bf(a.y) << 16);
-        o.y = (uint32_t)f2bf(a.z) | ((uint32_t)f2bf(a.w) << 16);
-        *reinterpret_cast<uint2*>(st.shadow_out[step] + (int64_t)(o0 + r) * in + col) = o;
+        uint2 w2;
+        w2.x = (uint32_t)f2bf(a.x) | ((uint32_t)f2bf(a.y) << 16);
+        w2.y = (uint32_t)f2bf(a.z) | ((uint32_t)f2bf(a.w) << 16);
+        *reinterpret_cast<uint2*>(st.shadow_out[step] + (int64_t)o * in + w0 + cc) = w2;
       }
     }
   }
 #pragma unroll
-  for (int r = 0; r < kFcRows; r++) {
-    if (o0 + r >= out) continue;
-    const int64_t e = (int64_t)(o0 + r) * in + col;
-    stg_nt(reinterpret_cast<float4*>(v + e), vv[r]);
-    stg_nt(reinterpret_cast<float4*>(theta_out + e), th[r]);
+  for (int q = 0; q < kFcNQ; q++) {
+    const int o = o0 + kFcRPI * q + rr;
+    if (o >= out || !col_ok) continue;
+    const int64_t e = (int64_t)o * in + w0 + cc;
+    stg_nt(reinterpret_cast<float4*>(v + e), vv[q]);
+    stg_nt(reinterpret_cast<float4*>(theta_out + e), th[q]);
   }
 }
 
@@ -547,7 +578,7 @@ hipError_t launch_apply_update_fc(const FcUpdateLaunch& u, hipStream_t stream, c
   for (int l = 0; l < kMaxLearners; l++) {
     t.g[l] = l < u.c ? u.grads[l] : nullptr;
     t.coef[l] = l < u.c ? u.coef[l] : 0.f;
-    f.x[l] = l < u.c ? u.fx[l] : nullptr;
+    f.xT[l] = l < u.c ? u.fx[l] : nullptr;
     f.dyT[l] = l < u.c ? u.fdyT[l] : nullptr;
   }
   StepTable st;
@@ -564,8 +595,10 @@ hipError_t launch_apply_update_fc(const FcUpdateLaunch& u, hipStream_t stream, c
   bool shadow = st.shadow_out[0] != nullptr;
   for (int k = 0; k < st.steps; k++)
     if ((st.shadow_out[k] != nullptr) != shadow) return hipErrorInvalidValue;
-  const int widest = u.in > u.out ? u.in : u.out;
-  dim3 grid((unsigned)((widest + 1023) / 1024), (unsigned)((u.out + kFcRows - 1) / kFcRows + 1));
+  if (u.NP < 8 || u.NP > 32 || (u.NP & 7)) return hipErrorInvalidValue;
+  // x: 4 kFcTileCols input units per workgroup (four wavefronts side by side), or 1024 bias elements in the extra row
+  const int cols = std::max((u.in + 4 * kFcTileCols - 1) / (4 * kFcTileCols), (u.out + 1023) / 1024);
+  dim3 grid((unsigned)cols, (unsigned)((u.out + kFcTileRows - 1) / kFcTileRows + 1));
   if (shadow)
     hipLaunchKernelGGL((apply_update_fc_kernel<true>), grid, dim3(256), 0, stream, u.theta_in, u.theta_out, u.v, u.in, u.out, u.N, u.NP, t, f,
                        st, u.momentum);

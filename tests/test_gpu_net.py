@@ -1,8 +1,11 @@
 """GPU parity of calcGradient and of whole n-softsync runs against the CPU oracle, through the C ABI.
 
-Error measure: ||a - b||_2 / ||b||_2 over the whole flat vector and over each layer's weight and bias
+Error measures.  (1) ||a - b||_2 / ||b||_2 over the whole flat vector and over each layer's weight and bias
 tensor (the largest is checked).  Bounds: per gradient 1e-4 (fp32 compute) and 2e-2 (bf16 compute);
-weights after K updates 1e-3 (fp32); timestamps and staleness exact.
+weights after K updates 1e-3 (fp32); timestamps and staleness exact.  (2) Element by element, so that one
+wrong element of a large tensor (a ragged tile edge, a last row) cannot hide in a norm:
+|a - b| <= tol (|b| + rms(b's tensor)) for EVERY element; tol is 1e-3 in fp32 and, in bf16 compute, the value stated
+at each test (a wholly wrong element -- zero, garbage, a neighbour's value -- sits at about 1).
 
 bf16 compute: a ReLU sign or a max-pool winner decided on a bfloat16 value can differ from the decision on
 the exact value, and one flipped decision moves a whole term of a weight-gradient sum.  Such decisions are
@@ -10,6 +13,8 @@ therefore compared in the kernel's precision: the reference for bf16 runs is the
 mode (same rounding points, sums in fp64).  Against the exact oracle the 2e-2 bound is checked where the
 sums are long enough for flips to average out (the mu = 128 configuration), and reported otherwise.
 """
+import os
+
 import numpy as np
 import pytest
 
@@ -20,6 +25,7 @@ torch = pytest.importorskip("torch")
 pytestmark = pytest.mark.gpu
 
 TOL = {"fp32": 1e-4, "bf16": 2e-2}
+ELEM_TOL = {"fp32": 1e-3, "bf16": 0.25}       # element-wise bound; bf16: single elements carry up to a few bf16 roundings
 
 
 def rel(a, b):
@@ -43,14 +49,62 @@ def layer_errors(net, g, ref):
     return max(errs), errs
 
 
-def one_gradient(net, mu, compute, seed, scale=0.3, lam=2, exact=False):
-    """calcGradient of `lam` learners with different batches on the same weights vs the oracle."""
-    from paper_1511_05950_amd import binding
+def elem_error(net, g, ref):
+    """Largest |a - b| / (|b| + rms(b's tensor)) over all elements, and where it is."""
+    g = np.asarray(g, np.float64)
+    ref = np.asarray(ref, np.float64)
+    worst, where = 0.0, None
+    pos = 0
+    for ws, nb in wl.param_shapes(net):
+        for n in (int(np.prod(ws)), nb):
+            b = ref[pos:pos + n]
+            rms = np.sqrt(np.mean(b * b))
+            if rms > 0:
+                r = np.abs(g[pos:pos + n] - b) / (np.abs(b) + rms)
+                k = int(np.argmax(r))
+                if r[k] > worst:
+                    worst, where = float(r[k]), pos + k
+            pos += n
+    return worst, where
+
+
+def draw_case(net, lam, mu, seed, scale):
     rng = np.random.default_rng(seed)
+    theta = (rng.standard_normal(wl.num_params(net)) * scale).astype(np.float32)
+    return theta, wl.images(net, lam * mu, seed + 1), wl.labels(net, lam * mu, seed + 2)
+
+
+MIN_MARGIN = 2e-7
+SPREAD_FACTOR = 1.5     # a GPU tensor may lie this much further from the oracle than the oracle's own evaluations lie apart
+
+
+def decided_seed(net, lam, mu, seed, scale, tries=16):
+    """The first seed of seed, seed + 1, ... whose case has every ReLU input decided at fp32 precision: the oracle's
+    smallest |ReLU input| / sum |its terms| is at least MIN_MARGIN.  Below that the sign of some ReLU input depends on
+    the order of an fp32 sum, the 1e-4 bound has no meaning for the case (one flipped ReLU moves early-layer gradients
+    by 1e-3), and the case is passed over -- by the oracle's number, never by a GPU result.
+    MIN_MARGIN = 2e-7 is three float roundings (2^-24 each) of the whole term sum.  An fp32 accumulation of K terms is
+    off by about sqrt(K) roundings of ONE term, i.e. 2^-24 / sqrt(K) of the term sum: below 1e-8 for the K <= 6 400 of
+    these nets (the flips that were seen sat at 6e-9 and 2e-8), so the margin leaves a factor of ten.  The largest test
+    net has 280 000 ReLU inputs per case, whose smallest margin is typically 1e-6: a larger threshold would pass over
+    nearly every draw."""
+    for s in range(seed, seed + tries):
+        theta, X, _ = draw_case(net, lam, mu, s, scale)
+        m = min(cnn.min_relu_margin(net, theta, X[L * mu:(L + 1) * mu]) for L in range(lam))
+        if m >= MIN_MARGIN:
+            if s != seed:
+                print("seed %d -> %d: a ReLU input of the drawn case lies within %.1e of its terms' magnitude" % (seed, s, MIN_MARGIN))
+            return s
+    pytest.skip("no drawn case with every ReLU input decided at fp32 precision (margin %.1e)" % MIN_MARGIN)
+
+
+def one_gradient(net, mu, compute, seed, scale=0.3, lam=2, exact=False, both=False):
+    """calcGradient of `lam` learners with different batches on the same weights vs the oracle.
+    both: also return the exact oracle's gradient (bf16 runs are judged against the reduced-precision mode and
+    reported against the exact one)."""
+    from paper_1511_05950_amd import binding
     P = wl.num_params(net)
-    theta = (rng.standard_normal(P) * scale).astype(np.float32)
-    X = wl.images(net, lam * mu, seed + 1)
-    Y = wl.labels(net, lam * mu, seed + 2)
+    theta, X, Y = draw_case(net, lam, mu, seed, scale)
     Xd, Yd = torch.from_numpy(X).cuda(), torch.from_numpy(Y).cuda()
     ctx = binding.Sasgd(lam, mu, lam, 2, net=net, compute=compute, init_weights=theta)
     assert ctx.P == P
@@ -64,9 +118,22 @@ def one_gradient(net, mu, compute, seed, scale=0.3, lam=2, exact=False):
         g = ctx.copyGradient(L)
         rl, rg = cnn.loss_and_gradient(net, theta, X[L * mu:(L + 1) * mu], Y[L * mu:(L + 1) * mu],
                                        round_bf16=(compute == "bf16" and not exact))
-        out.append((g, rg, float(loss[L].item()), rl))
+        if both:
+            _, eg = cnn.loss_and_gradient(net, theta, X[L * mu:(L + 1) * mu], Y[L * mu:(L + 1) * mu])
+            out.append((g, rg, float(loss[L].item()), rl, eg))
+        else:
+            out.append((g, rg, float(loss[L].item()), rl))
     ctx.destroy()
     return out
+
+
+def check_gradient(net, compute, g, rg, loss, rl, tag, elem_tol=None):
+    worst, errs = layer_errors(net, g, rg)
+    assert worst < TOL[compute], (tag, compute, errs)
+    ew, at = elem_error(net, g, rg)
+    assert ew < (ELEM_TOL[compute] if elem_tol is None else elem_tol), (tag, compute, "element", at, ew)
+    assert abs(loss - rl) < (1e-5 if compute == "fp32" else 2e-2) * max(1.0, abs(rl))
+    return worst, ew
 
 
 TINY = {
@@ -93,15 +160,15 @@ TINY = {
 @pytest.mark.parametrize("name", sorted(TINY))
 def test_tiny_net_gradient(name, compute):
     net = TINY[name]
-    # patch_5x5 feeds 140 000 values through ReLUs; with the seed of the other nets one learner has two of them at
-    # 6e-9 and 2e-8 of the sum of their terms' magnitudes (fp64, PyTorch on the CPU), below what fp32 sums resolve:
-    # the sign of such a value depends on the summation order, and one flipped ReLU moves the early layers' gradients
-    # by 1e-3.  With the next seed the closest value is 5e-7 away.
-    seed = sum(map(ord, name)) + (1 if name == "patch_5x5" else 0)
-    for (g, rg, loss, rl) in one_gradient(net, 3, compute, seed=seed):
-        worst, errs = layer_errors(net, g, rg)
-        assert worst < TOL[compute], (name, compute, errs)
-        assert abs(loss - rl) < (1e-5 if compute == "fp32" else 2e-2) * max(1.0, abs(rl))
+    seed = sum(map(ord, name))
+    if compute == "fp32":
+        seed = decided_seed(net, 2, 3, seed, 0.3)
+    for (g, rg, loss, rl, eg) in one_gradient(net, 3, compute, seed=seed, both=True):
+        worst, ew = check_gradient(net, compute, g, rg, loss, rl, name)
+        if compute == "bf16":           # reported, not asserted: the distance to the exact oracle (bf16 rounding of every tensor)
+            print("%s bf16: vs reduced-precision oracle %.1e (element %.1e), vs exact oracle %.1e" % (name, worst, ew, layer_errors(net, g, eg)[0]))
+        else:
+            print("%s fp32: vs oracle %.1e (element %.1e)" % (name, worst, ew))
 
 
 @pytest.mark.parametrize("compute,mu", [("fp32", 4), ("bf16", 4), ("bf16", 128)])
@@ -110,7 +177,7 @@ def test_cifar3_gradient(compute, mu):
     for (g, rg, loss, rl) in one_gradient(net, mu, compute, seed=3, scale=0.05):
         worst, errs = layer_errors(net, g, rg)
         print(compute, mu, "per-layer relative errors:", ["%.2e" % e for e in errs])
-        assert worst < TOL[compute], (compute, errs)
+        check_gradient(net, compute, g, rg, loss, rl, "cifar3 mu=%d" % mu)
 
 
 def test_cifar3_bf16_against_exact_oracle():
@@ -172,7 +239,8 @@ def test_config2_200_updates():
 def test_config3_first_updates(mode):
     """BASELINE config 3 as bench.py runs it (CIFAR-shaped, bf16 compute, lambda = 18 learners of mu = 128 in one batched
     call, 1-softsync: c = 18 gradients averaged per update, staleness in {0, 1, 2}), its first two updates, in both
-    readings of its learning rate (per gradient, and one rate per update from the mean staleness)."""
+    readings of its learning rate (per gradient, and one rate per update from the mean staleness), against the
+    oracle's reduced-precision mode and its exact mode."""
     from paper_1511_05950_amd import binding, driver
     cfgd = wl.config(3)
     net, lam, mu, n, c = cfgd["net"], cfgd["lam"], cfgd["mu"], cfgd["n"], cfgd["c"]
@@ -186,12 +254,60 @@ def test_config3_first_updates(mode):
     log = driver.run_softsync(ctx, sched, lambda i, l: (Xd[sl(i, l)], Yd[sl(i, l)]), lam)
     w, v = ctx.copyWeights(), ctx.copyMomentum()
     ctx.destroy()
-    ref = protocol.run(cnn.make_callback(net, round_bf16=True), w0, lambda i, l: (X[sl(i, l)], Y[sl(i, l)]), sched, lam, n,
-                       cfgd["alpha0"], cfgd["momentum"], cfgd["weight_decay"], mode)
-    assert log == ref["log"]
-    assert [t for (_, _, _, _, t) in log[:c]] == [0] * c      # every first-update gradient reads theta_0
-    assert rel(w - w0, ref["theta"] - w0) < 2e-2
-    assert rel(v, ref["v"]) < 2e-2
+    refs = {}
+    for reduced in (True, False):
+        refs[reduced] = protocol.run(cnn.make_callback(net, round_bf16=reduced), w0, lambda i, l: (X[sl(i, l)], Y[sl(i, l)]), sched, lam, n,
+                                     cfgd["alpha0"], cfgd["momentum"], cfgd["weight_decay"], mode)
+    # The update is the average of 18 (then 36) gradients of random-label mini-batches: what is particular to a mini-batch
+    # averages out, the error of rounding the SHARED weights and activations to bf16 does not, so the update's distance to
+    # the exact oracle is several times a single gradient's.  The bound is the stated 2e-2 against the reduced-precision
+    # oracle, and against the exact one SPREAD_FACTOR times the distance between the oracle's own two modes where
+    # that exceeds 2e-2.
+    _, own = layer_errors(net, refs[True]["theta"] - w0, refs[False]["theta"] - w0)
+    for reduced in (True, False):
+        ref = refs[reduced]
+        assert log == ref["log"]
+        assert [t for (_, _, _, _, t) in log[:c]] == [0] * c      # every first-update gradient reads theta_0
+        worst, errs = layer_errors(net, w - w0, ref["theta"] - w0)
+        tol = [2e-2] * len(errs) if reduced else [max(2e-2, SPREAD_FACTOR * e) for e in own]
+        print("config 3 (%s), 2 updates, update vs %s oracle:" % (mode, "reduced-precision" if reduced else "exact"), ["%.1e" % e for e in errs])
+        if not reduced:
+            print("   oracle's reduced-precision mode vs its exact mode:", ["%.1e" % e for e in own])
+        assert all(e < t for e, t in zip(errs, tol)), (errs, tol)
+        assert rel(v, ref["v"]) < tol[0]
+
+
+def test_config3_all_100_updates():
+    """BASELINE config 3 in full: 100 updates of c = 18 gradients (1 800 mini-batches of 128 images) through the
+    batched driver.  The bookkeeping log must equal the oracle's exactly; the update theta_100 - theta_0 and the momentum
+    are compared, whole and per tensor, with the oracle's two runs stored in tests/golden/config3_run.npz (written by
+    tests/golden/make_config_runs.py from the oracle alone): 2e-2 against the reduced-precision mode; against the exact
+    mode 2e-2 where the distance between the oracle's own two runs allows it, SPREAD_FACTOR times that distance elsewhere
+    (see test_config3_first_updates)."""
+    from paper_1511_05950_amd import binding, driver
+    gold = np.load(os.path.join(GOLDEN, "config3_run.npz"))
+    cfgd = wl.config(3)
+    net, lam, mu, n = cfgd["net"], cfgd["lam"], cfgd["mu"], cfgd["n"]
+    sched = cfgd["schedule"]()
+    X, Y, w0 = cfgd["images"](), cfgd["labels"](), cfgd["weights"]()
+    Xd, Yd = torch.from_numpy(X).cuda(), torch.from_numpy(Y).cuda()
+    ctx = binding.Sasgd(lam, mu, n, int(sched.max()) + 1, net="cifar3", compute="bf16", lr_mode=cfgd["lr_mode"], alpha0=cfgd["alpha0"],
+                        momentum=cfgd["momentum"], weight_decay=cfgd["weight_decay"], init_weights=w0)
+    log, calls = driver.run_softsync_batched(ctx, sched, lambda i, l: (Xd[wl.batch_slice(cfgd, i, l)], Yd[wl.batch_slice(cfgd, i, l)]), lam)
+    w, v = ctx.copyWeights(), ctx.copyMomentum()
+    assert ctx.timestamp() == 100
+    ctx.destroy()
+    assert np.array_equal(np.asarray(log, dtype=np.int64), gold["log"])
+    upd = w.astype(np.float64) - w0.astype(np.float64)
+    _, own = layer_errors(net, gold["update_reduced"], gold["update_exact"])       # the oracle's two modes against each other
+    print("config 3, 100 updates, oracle's reduced-precision run vs its exact run:", ["%.1e" % e for e in own])
+    for tag in ("reduced", "exact"):
+        worst, errs = layer_errors(net, upd, gold["update_" + tag])
+        ev = rel(v, gold["v_" + tag])
+        tol = [2e-2] * len(errs) if tag == "reduced" else [max(2e-2, SPREAD_FACTOR * e) for e in own]
+        print("config 3, 100 updates vs %s oracle run: update" % tag, ["%.1e" % e for e in errs], "momentum %.1e" % ev)
+        assert all(e < t for e, t in zip(errs, tol)), (tag, errs, tol)
+        assert ev < tol[0], (tag, ev)
 
 
 def test_batched_driver_matches_plain_driver():
@@ -223,84 +339,211 @@ def cosine(a, b):
     return float(a @ b / (np.linalg.norm(a) * np.linalg.norm(b)))
 
 
-def alex_gradient(net, netarg, w0, X, Y):
+GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+
+
+def alex8_spread():
+    """Per-tensor spread between CPU evaluations of the AlexNet-shaped bf16 gradient, measured with the oracle alone
+    (tests/golden/make_alex8_bf16_spread.py): name -> (|R-E|/|E|, |R32-R|/|R|, |R32-E|/|E|), E the exact oracle, R its
+    reduced-precision mode, R32 the reduced-precision mode with float running sums."""
+    rows = {}
+    for line in open(os.path.join(GOLDEN, "alex8_bf16_spread.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        name, a, b, c = line.split()
+        rows[name] = (float(a), float(b), float(c))
+    return rows
+
+
+def alex8_tensor_names():
+    return ["whole"] + [n + s for n in ("conv1", "conv2", "conv3", "conv4", "conv5", "fc6", "fc7", "fc8") for s in (".w", ".b")]
+
+
+
+def alex8_tolerances():
+    """Bound per tensor (order of layer_errors) against the reduced-precision oracle and against the exact one: the
+    stated 2e-2 wherever the CPU-measured spread allows it, SPREAD_FACTOR times that spread elsewhere."""
+    sp = alex8_spread()
+    vs_reduced = [max(2e-2, SPREAD_FACTOR * sp[n][1]) for n in alex8_tensor_names()]
+    vs_exact = [max(2e-2, SPREAD_FACTOR * sp[n][0]) for n in alex8_tensor_names()]
+    return vs_reduced, vs_exact
+
+
+def alex_learners(net, netarg, w0, X, Y, versions=1, lam=1, push_seed=0):
+    """calcGradient of `lam` learners in ONE call at mu = len(X) / lam, learner L on weight version L * versions // lam.
+    Versions 1, 2, ... are made from w0 by server updates with seeded random gradients.  Returns the gradients, the
+    losses and, per learner, the weights it read (as the library holds them)."""
     from paper_1511_05950_amd import binding
-    mu = X.shape[0]
-    ctx = binding.Sasgd(2, mu, 2, 1, net=netarg, compute="bf16", init_weights=w0)
-    loss = torch.zeros(1, device="cuda")
-    ctx.getMinibatch(1, torch.from_numpy(X).cuda(), torch.from_numpy(Y).cuda())
-    ctx.pullWeights(1, 0)
-    ctx.calcGradient([1], loss)
-    g = ctx.copyGradient(1)
+    mu = X.shape[0] // lam
+    ctx = binding.Sasgd(max(lam, 2), mu, max(lam, 2), versions, net=netarg, compute="bf16", alpha0=0.5, init_weights=w0)
+    rng = np.random.default_rng(push_seed)
+    for _ in range(versions - 1):
+        push = torch.from_numpy((rng.standard_normal(ctx.P) * 0.004).astype(np.float32)).cuda()
+        ctx.pushGradientExternal(push, ctx.timestamp())
+        ctx.sumGradients()
+        ctx.applyUpdate()
+        torch.cuda.synchronize()
+        del push
+    Xd, Yd = torch.from_numpy(X).cuda(), torch.from_numpy(Y).cuda()
+    loss = torch.zeros(lam, device="cuda")
+    ids = list(range(lam)) if lam > 1 else [1]
+    ver = []
+    for k, L in enumerate(ids):
+        ctx.getMinibatch(L, Xd[k * mu:(k + 1) * mu], Yd[k * mu:(k + 1) * mu])
+        j = k * versions // lam
+        assert ctx.pullWeights(L, ctx.timestamp() - j) == j
+        ver.append(j)
+    ctx.calcGradient(ids, loss)
+    grads = [ctx.copyGradient(L) for L in ids]
+    weights = {j: ctx.copyWeights(j) for j in sorted(set(ver))}
     ctx.destroy()
-    return g, float(loss.item())
+    return grads, [float(v) for v in loss.cpu()], [weights[j] for j in ver]
 
 
 def test_alex8_shapes_smooth_variant_full_size():
     """Every kernel of config 4 at its real shape (mu = 16, 3x224x224, 62.4 M parameters) on the decision-free
-    variant of the network (no ReLU, average pooling): bf16 compute must match the oracle to 2e-2 per tensor."""
+    variant of the network (no ReLU, average pooling): bf16 compute must match the oracle to 2e-2 per tensor, and
+    element by element."""
     net = wl.ALEX8_SMOOTH
     w0 = wl.init_weights(net, wl.SEED0 + 4002, std=0.02)
     X, Y = wl.images(net, 16, 77), wl.labels(net, 16, 78)
-    g, loss = alex_gradient(net, net, w0, X, Y)
+    (g,), (loss,), _ = alex_learners(net, net, w0, X, Y)
     rl, rg = cnn.loss_and_gradient(net, w0, X, Y, round_bf16=True)
     worst, errs = layer_errors(net, g, rg)
-    print("alex8_smooth bf16 vs reduced-precision oracle:", ["%.1e" % e for e in errs])
+    ew, at = elem_error(net, g, rg)
+    print("alex8_smooth bf16 vs reduced-precision oracle:", ["%.1e" % e for e in errs], "element-wise %.2e" % ew)
     assert worst < 2e-2, errs
+    assert ew < ELEM_TOL["bf16"], (at, ew)
     el, eg = cnn.loss_and_gradient(net, w0, X, Y)
     worst, errs = layer_errors(net, g, eg)
-    print("alex8_smooth bf16 vs exact oracle:", ["%.1e" % e for e in errs])
+    ew, at = elem_error(net, g, eg)
+    print("alex8_smooth bf16 vs exact oracle:", ["%.1e" % e for e in errs], "element-wise %.2e" % ew)
     assert worst < 2e-2, errs
+    assert ew < ELEM_TOL["bf16"], (at, ew)
     assert abs(loss - el) < 1e-3 * abs(el)
 
 
 def test_alex8_gradient_full_size():
-    """One learner step of BASELINE config 4 at full size.  With ReLU and max pooling in an eight-layer net the
-    bf16 gradient is reproducible only to a few per cent by ANY two evaluations that sum in a different order:
-    activations carry ~0.2 % quantisation noise, so ~0.2 % of the ReLU signs differ, and each flipped sign moves a
-    whole term of the weight-gradient sums (relative error ~ sqrt(fraction flipped)).  The oracle shows the same
-    spread between its own exact and reduced-precision modes (tests/test_oracle_cnn.py).  Checked here: the loss,
-    the last layer (no decision between it and the loss) at 2e-2, the rest at the flip-limited level."""
+    """One learner step of BASELINE config 4 at full size.  With ReLU and max pooling in an eight-layer net whose
+    initial weights leave every pre-activation near zero, a bf16 gradient is reproducible only to a few per cent by ANY
+    two evaluations: storing a tensor in bf16 moves values by 2^-9, the differences spread to every later activation
+    within two layers, and a share of the ReLU signs and pooling winners comes out differently; each flip moves a
+    whole term of a weight-gradient sum.  tests/golden/alex8_bf16_spread.txt has the CPU evidence (oracle only): its
+    exact mode, its reduced-precision mode and that mode with float running sums lie 3 - 24 % apart per tensor on this
+    very case.  The bound per tensor is the stated 2e-2 where that spread allows it (the last layer, with no decision
+    between it and the loss) and SPREAD_FACTOR times the spread elsewhere; the loss must match to 1e-5."""
     net = wl.ALEX8
     cfgd = wl.config(4)
     w0 = cfgd["weights"]()
     X, Y = wl.images(net, cfgd["mu"], 77), wl.labels(net, cfgd["mu"], 78)
-    g, loss = alex_gradient(net, "alex8", w0, X, Y)
+    (g,), (loss,), _ = alex_learners(net, "alex8", w0, X, Y)
+    tol_r, tol_e = alex8_tolerances()
     rl, rg = cnn.loss_and_gradient(net, w0, X, Y, round_bf16=True)
     worst, errs = layer_errors(net, g, rg)
     print("alex8 bf16 vs reduced-precision oracle:", ["%.1e" % e for e in errs])
+    print("                          bounds      :", ["%.1e" % e for e in tol_r])
     assert abs(loss - rl) < 1e-5 * abs(rl)
-    assert errs[-2] < 2e-2 and errs[-1] < 2e-2           # fc8 weights and bias
-    assert worst < 1.5e-1 and cosine(g, rg) > 0.99, (errs, cosine(g, rg))
+    assert all(e < t for e, t in zip(errs, tol_r)), (errs, tol_r)
+    assert tol_r[-2] == 2e-2 and tol_r[-1] == 2e-2            # fc8 weights and bias stay at the stated bound
+    assert cosine(g, rg) > 0.995
     el, eg = cnn.loss_and_gradient(net, w0, X, Y)
-    print("alex8 bf16 vs exact oracle: whole gradient %.2e, cosine %.5f" % (rel(g, eg), cosine(g, eg)))
-    assert rel(g, eg) < 1.5e-1 and cosine(g, eg) > 0.99
+    worst, errs = layer_errors(net, g, eg)
+    print("alex8 bf16 vs exact oracle            :", ["%.1e" % e for e in errs], "cosine %.5f" % cosine(g, eg))
+    print("                          bounds      :", ["%.1e" % e for e in tol_e])
+    assert all(e < t for e, t in zip(errs, tol_e)), (errs, tol_e)
+    assert cosine(g, eg) > 0.995
 
 
-def test_config4_first_updates():
-    """BASELINE config 4 as bench.py runs it (AlexNet-shaped, bf16, 18-softsync, ring of 37 versions, batched
-    driver): the first 4 updates.  Bookkeeping must be exact; the update (theta_K - theta_0) is compared at the
-    flip-limited level explained in test_alex8_gradient_full_size."""
+def test_alex8_six_learners_on_three_versions_full_size():
+    """The situation bench.py times at full size: several learners of ONE batched call, each pair on a weight version
+    of its own (lambda-softsync), which switches the convolution kernels to their XCD-contiguous tile order and 256-row
+    tiles.  Every learner's gradient against the oracle on the weights that learner read: element by element on the
+    decision-free variant, at the spread-derived per-tensor bounds on the network itself (one learner per version)."""
+    mu, lam, versions = 16, 6, 3
+    net = wl.ALEX8_SMOOTH
+    w0 = wl.init_weights(net, wl.SEED0 + 4002, std=0.02)
+    X, Y = wl.images(net, lam * mu, 81), wl.labels(net, lam * mu, 82)
+    grads, losses, weights = alex_learners(net, net, w0, X, Y, versions=versions, lam=lam, push_seed=83)
+    assert rel(weights[2], weights[0]) > 1e-2 and rel(weights[4], weights[2]) > 1e-2     # the versions do differ
+    for L in range(lam):
+        print("smooth variant, learner %d" % L, flush=True)
+        rl, rg = cnn.loss_and_gradient(net, weights[L], X[L * mu:(L + 1) * mu], Y[L * mu:(L + 1) * mu], round_bf16=True)
+        worst, errs = layer_errors(net, grads[L], rg)
+        ew, at = elem_error(net, grads[L], rg)
+        assert worst < 2e-2, (L, errs)
+        assert ew < ELEM_TOL["bf16"], (L, at, ew)
+        assert abs(losses[L] - rl) < 1e-3 * abs(rl)
+    net = wl.ALEX8
+    w0 = wl.config(4)["weights"]()
+    grads, losses, weights = alex_learners(net, "alex8", w0, X, Y, versions=versions, lam=lam, push_seed=84)
+    tol_r, _ = alex8_tolerances()
+    for L in (1, 2, 5):                                       # one learner of every version
+        print("alex8, learner %d" % L, flush=True)
+        rl, rg = cnn.loss_and_gradient(net, weights[L], X[L * mu:(L + 1) * mu], Y[L * mu:(L + 1) * mu], round_bf16=True)
+        worst, errs = layer_errors(net, grads[L], rg)
+        print("   ", ["%.1e" % e for e in errs])
+        assert abs(losses[L] - rl) < 1e-5 * abs(rl)
+        assert all(e < t for e, t in zip(errs, tol_r)), (L, errs, tol_r)
+
+
+def sample_rel(a, b):
+    nb = np.linalg.norm(b)
+    return float(np.linalg.norm(a - b) / nb) if nb > 0 else float(np.linalg.norm(a))
+
+
+def test_config4_all_20_updates():
+    """BASELINE config 4 in full, as bench.py runs it (AlexNet-shaped, bf16, 18-softsync, ring of 37 versions, batched
+    driver): all 20 updates.  Bookkeeping must equal the oracle's log exactly.  The update theta_20 - theta_0 is compared
+    with the oracle's runs (tests/golden/config4_run.npz, written by tests/golden/make_config_runs.py from the oracle
+    alone) on the stored sample of every tensor -- its edges and 16 384 seeded draws.  Over 20 updates two bf16
+    evaluations drift further apart than on one gradient (the second evaluates its later gradients on slightly different
+    weights), so the bounds come from the oracle's own runs of the same 20 updates: against the reduced-precision run
+    SPREAD_FACTOR times the distance between that run and the run with float running sums, against the exact run
+    SPREAD_FACTOR times the distance between the reduced-precision and the exact run, never below the stated 2e-2."""
     from paper_1511_05950_amd import binding, driver
+    gold = np.load(os.path.join(GOLDEN, "config4_run.npz"))
     cfgd = wl.config(4)
     net, lam, mu, n = cfgd["net"], cfgd["lam"], cfgd["mu"], cfgd["n"]
-    K = 4
-    sched = cfgd["schedule"]()[:K]
-    X, Y, w0 = wl.images(net, K * mu, 5), wl.labels(net, K * mu, 6), cfgd["weights"]()
+    sched = cfgd["schedule"]()
+    X, Y, w0 = cfgd["images"](), cfgd["labels"](), cfgd["weights"]()
     Xd, Yd = torch.from_numpy(X).cuda(), torch.from_numpy(Y).cuda()
     ctx = binding.Sasgd(lam, mu, n, 37, net="alex8", compute="bf16", alpha0=cfgd["alpha0"], momentum=cfgd["momentum"],
                         weight_decay=cfgd["weight_decay"], init_weights=w0)
-    log, calls = driver.run_softsync_batched(ctx, sched, lambda i, l: (Xd[i * mu:(i + 1) * mu], Yd[i * mu:(i + 1) * mu]), lam)
+    log, calls = driver.run_softsync_batched(ctx, sched, lambda i, l: (Xd[wl.batch_slice(cfgd, i, l)], Yd[wl.batch_slice(cfgd, i, l)]), lam)
     w = ctx.copyWeights()
-    old = ctx.copyWeights(K - 1)                      # bf16 copy of the previous version, from the ring
+    old = ctx.copyWeights(len(sched) - 1)             # bf16 copy of the previous version, from the ring
+    assert ctx.timestamp() == len(sched)
     ctx.destroy()
-    ref = protocol.run(cnn.make_callback(net, round_bf16=True), w0, lambda i, l: (X[i * mu:(i + 1) * mu], Y[i * mu:(i + 1) * mu]),
-                       sched, lam, n, cfgd["alpha0"], cfgd["momentum"], cfgd["weight_decay"])
-    assert log == ref["log"] and calls == 1           # all four gradients read theta_0: one batched call
-    assert rel(w, ref["theta"]) < 1e-3
-    assert rel(w - w0, ref["theta"] - w0) < 1.5e-1 and cosine(w - w0, ref["theta"] - w0) > 0.99
-    assert rel(old, ref["thetas"][K - 1]) < 5e-3      # bf16 rounding of the ring copy: 2^-9 per element
+    assert np.array_equal(np.asarray(log, dtype=np.int64), gold["log"])          # timestamps, staleness, learners: exact
+    versions = sorted({int(j) for (_, _, _, j, _) in log})
+    print("batched calls %d, weight versions read: %s" % (calls, versions))
+    assert len(versions) > 1                          # stale ring slots other than theta_0 are read at full size
     assert np.all((old.view(np.uint32) & 0xFFFF) == 0)
+    idx = gold["idx"].astype(np.int64)
+    upd = (w.astype(np.float64) - w0.astype(np.float64))[idx]
+    # sample positions per tensor, in the order of the stored sample
+    bounds, pos = [], 0
+    for ws, nb in wl.param_shapes(net):
+        for cnt in (int(np.prod(ws)), nb):
+            bounds.append((pos, pos + cnt))
+            pos += cnt
+
+    def per_tensor(a, b):
+        out = [sample_rel(a, b)]
+        for (lo, hi) in bounds:
+            sel = (idx >= lo) & (idx < hi)
+            out.append(sample_rel(a[sel], b[sel]))
+        return out
+
+    run_e, run_r, run_r32 = (gold[k].astype(np.float64) for k in ("update_exact", "update_reduced", "update_r32"))
+    own = {"reduced": per_tensor(run_r32, run_r), "exact": per_tensor(run_r, run_e)}
+    for tag, ref in (("reduced", run_r), ("exact", run_e)):
+        errs = per_tensor(upd, ref)
+        tol = [max(2e-2, SPREAD_FACTOR * e) for e in own[tag]]
+        print("config 4, update after 20 steps vs %s oracle run:" % tag, ["%.1e" % e for e in errs], "cosine %.5f" % cosine(upd, ref))
+        print("   the oracle's own runs apart (%s):" % ("float sums vs reduced" if tag == "reduced" else "reduced vs exact"), ["%.1e" % e for e in own[tag]])
+        assert all(e < t for e, t in zip(errs, tol)), (tag, errs, tol)
+        assert cosine(upd, ref) > 0.995
 
 
 def test_learner_protocol_errors():
@@ -514,9 +757,7 @@ def test_patch_kernel_tiles_spanning_many_small_images():
     # 3 x 3 feature maps: a 128-position tile covers 14 images, each with its own band of halo rows in the patch
     net = wl.tiny_net(3, 5, 5, 6, conv=((32, 3, 1, 0), (64, 3, 1, 1), (96, 2, 1, 1)), pool="avgpool", fc_hidden=16)
     for (g, rg, loss, rl) in one_gradient(net, 40, "bf16", seed=95, lam=2):
-        worst, errs = layer_errors(net, g, rg)
-        assert worst < TOL["bf16"], errs
-        assert abs(loss - rl) < 2e-2 * max(1.0, abs(rl))
+        check_gradient(net, "bf16", g, rg, loss, rl, "small images")
 
 
 @pytest.mark.parametrize("compute", ["fp32", "bf16"])
@@ -527,10 +768,9 @@ def test_largest_learner_count_in_one_call(compute):
     net = TINY["mfma_pad3"]
     # weights of scale 0.1: at the other tests' 0.3 one of these 64 two-image batches is classified with a loss of 3e-12
     # and its gradient (norm 3e-9) has no meaningful relative error
-    for (g, rg, loss, rl) in one_gradient(net, 2, compute, seed=164, scale=0.1, lam=64):
-        worst, errs = layer_errors(net, g, rg)
-        assert worst < TOL[compute], (compute, errs)
-        assert abs(loss - rl) < (1e-5 if compute == "fp32" else 2e-2) * max(1.0, abs(rl))
+    seed = decided_seed(net, 64, 2, 164, 0.1) if compute == "fp32" else 164
+    for (g, rg, loss, rl) in one_gradient(net, 2, compute, seed=seed, scale=0.1, lam=64):
+        check_gradient(net, compute, g, rg, loss, rl, "64 learners")
     theta = np.zeros(wl.num_params(net), dtype=np.float32)
     with pytest.raises(binding.SasgdError):
         binding.Sasgd(65, 2, 65, 2, net=net, compute=compute, init_weights=theta)
@@ -542,7 +782,8 @@ def test_single_image_minibatch(name, compute):
     """mu = 1: the smallest mini-batch (the mean over the mini-batch is the gradient of the one image; every GEMM has
     fewer rows than a tile)."""
     net = TINY[name]
-    for (g, rg, loss, rl) in one_gradient(net, 1, compute, seed=7 + sum(map(ord, name)), scale=0.1, lam=3):
-        worst, errs = layer_errors(net, g, rg)
-        assert worst < TOL[compute], (name, compute, errs)
-        assert abs(loss - rl) < (1e-5 if compute == "fp32" else 2e-2) * max(1.0, abs(rl))
+    seed = 7 + sum(map(ord, name))
+    if compute == "fp32":
+        seed = decided_seed(net, 3, 1, seed, 0.1)
+    for (g, rg, loss, rl) in one_gradient(net, 1, compute, seed=seed, scale=0.1, lam=3):
+        check_gradient(net, compute, g, rg, loss, rl, name)
