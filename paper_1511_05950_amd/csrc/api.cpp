@@ -340,6 +340,12 @@ int sasgd_create(const sasgd_config* cfg, const float* init_weights, sasgd_ctx**
         if (ez != hipSuccess) { rc = fail_hip(ctx, ez, "clearing workspace"); break; }
       }
       if (rc != SASGD_OK) break;
+      if (net_group_workspace_bytes(ctx->net) > 0) {
+        void* g = ctx_alloc(ctx, net_group_workspace_bytes(ctx->net));
+        if (!g) { rc = fail(ctx, SASGD_ENOMEM, "group staging area"); break; }
+        hipError_t eg = net_set_group_workspace(ctx->net, g, ctx->stream);
+        if (eg != hipSuccess) { rc = fail_hip(ctx, eg, "clearing the group staging area"); break; }
+      }
       hipError_t ez = hipStreamSynchronize(ctx->stream);
       if (ez != hipSuccess) { rc = fail_hip(ctx, ez, "clearing workspace"); break; }
     }

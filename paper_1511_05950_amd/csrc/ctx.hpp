@@ -87,6 +87,10 @@ int net_create(const sasgd_config& cfg, Net** out, int64_t* out_P, size_t* out_p
 void net_destroy(Net* net);
 // Device memory the net needs per learner, in bytes (activations, gradient activations, argmax).
 size_t net_workspace_bytes(const Net* net);
+// Staging area in which learners that share a weight version stack their mini-batches for the fully connected layers
+// (bytes; 0 if the network has no such layer).  One per context.
+size_t net_group_workspace_bytes(const Net* net);
+hipError_t net_set_group_workspace(Net* net, void* ws, hipStream_t stream);
 // Registers a learner's workspace and initialises it (zeros, plus the constant blocks the kernels read).
 hipError_t net_set_workspace(Net* net, int learner, void* ws, hipStream_t stream);
 // Per weight version: derive the kernel-friendly copies (bf16 repacked conv filters) from the flat vector.

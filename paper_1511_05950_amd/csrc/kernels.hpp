@@ -169,6 +169,9 @@ hipError_t launch_softmax_ce(bool is_bf16, bool z_f32, const PtrTab& ws, const C
                              size_t loss_byte_off, int N, int K, float* loss_out, int count, hipStream_t s);
 hipError_t launch_label_rank(bool is_bf16, bool z_f32, const PtrTab& ws, const CPtrTab& labels, size_t z_off, int N, int K,
                              int32_t* rank_out, int count, hipStream_t s);
+// Copies [bytes_per_member] between every member's workspace (at member_off_bytes) and consecutive pieces of `stage`.
+hipError_t launch_stack_rows(const PtrTab& members, int count, size_t member_off_bytes, void* stage, int64_t bytes_per_member,
+                             bool to_stage, hipStream_t s);
 hipError_t launch_fc_save_factors(const PtrTab& ws, const PtrTab& grads, size_t x_off, size_t dy_off, size_t fx_off, size_t fdy_off,
                                   int64_t b_off, int N, int in, int out, int NP, int count, hipStream_t s);
 hipError_t launch_fc_expand_factors(const void* fx, const void* fdy, float* dw, int N, int in, int out, int NP, hipStream_t s);

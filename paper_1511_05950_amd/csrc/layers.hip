@@ -711,6 +711,30 @@ hipError_t launch_label_rank(bool is_bf16, bool z_f32, const PtrTab& ws, const C
   return hipGetLastError();
 }
 
+// ------------------------------------------------------------------ stacking the mini-batches of several learners
+// Learners that read the same weight version take a fully connected layer as ONE matrix product on their stacked
+// mini-batches: member k's rows ([bytes_per_member] at byte offset member_off of its workspace) are copied to / from rows
+// k * bytes_per_member of a staging area.  16-byte pieces; blockIdx.z = member.
+__global__ __launch_bounds__(256) void stack_rows_kernel(PtrTab members, size_t member_off, char* stage, int64_t bytes_per_member,
+                                                         int to_stage) {
+  char* own = (char*)members.p[blockIdx.z] + member_off;
+  char* stg = stage + (int64_t)blockIdx.z * bytes_per_member;
+  const uint4* src = reinterpret_cast<const uint4*>(to_stage ? own : stg);
+  uint4* dst = reinterpret_cast<uint4*>(to_stage ? stg : own);
+  const int64_t n = bytes_per_member >> 4;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) dst[i] = src[i];
+}
+
+hipError_t launch_stack_rows(const PtrTab& members, int count, size_t member_off_bytes, void* stage, int64_t bytes_per_member,
+                             bool to_stage, hipStream_t s) {
+  if (bytes_per_member <= 0 || (bytes_per_member & 15) || (member_off_bytes & 15)) return hipErrorInvalidValue;
+  const int64_t n = bytes_per_member >> 4;
+  const unsigned blocks = (unsigned)((n + 255) / 256 < 256 ? (n + 255) / 256 : 256);
+  hipLaunchKernelGGL(stack_rows_kernel, dim3(blocks, 1, (unsigned)count), dim3(256), 0, s, members, member_off_bytes, (char*)stage,
+                     bytes_per_member, to_stage ? 1 : 0);
+  return hipGetLastError();
+}
+
 // ------------------------------------------------------------------ fully connected weight gradient as factors
 // The weight gradient of a fully connected layer over a mini-batch of N images is the rank-N product
 // dW[o][i] = sum_n dy[n][o] x[n][i].  Instead of writing out * in values, keep the factors, both with the images

@@ -37,6 +37,10 @@ struct Op {
   bool factored = false;
   size_t fx_off = 0, fdy_off = 0;         // element offsets of the two factor copies in the workspace
   int NP = 0;
+  // fully connected layer that learners on one weight version run as ONE product on their stacked mini-batches:
+  // element offset of the stacked layer input in the group staging area
+  bool stacked = false;
+  size_t gx_off = 0;
 };
 
 struct Tensor {
@@ -63,6 +67,11 @@ struct Net {
   size_t loss_off = 0;         // per-image losses, mu floats (byte offset)
   size_t zero_off = 0;         // 256 zero bytes (element offset), target of out-of-range loads
   size_t scratch_off = 0, scratch_bytes = 0;   // split-contraction partials (bytes from the workspace base)
+  // group staging area (one per context): a block of zeros, the stacked input of every stacked layer (kept for the
+  // backward pass), stacked output / output gradient / input gradient, split partials.  Element offsets of bf16.
+  int lambda = 0;
+  void* group_ws = nullptr;
+  size_t g_bytes = 0, g_zero_off = 0, g_y_off = 0, g_dy_off = 0, g_dx_off = 0, g_scratch_off = 0, g_scratch_bytes = 0;
   void* ws[kMaxLearners] = {nullptr};
   const float* pixel_mean = nullptr;   // optional [C][H][W] fp32, subtracted while the input is re-laid out
 };
@@ -335,6 +344,31 @@ int net_create(const sasgd_config& cfg, Net** out, int64_t* out_P, size_t* out_p
     bytes = net->scratch_off + sb;
   }
   net->ws_bytes = bytes + 256;
+  // group staging area
+  net->lambda = cfg.lambda;
+  if (net->bf16 && cfg.lambda > 1) {
+    const size_t R = (size_t)cfg.lambda * N;
+    size_t g = 256, max_in = 0, max_out = 0;
+    net->g_zero_off = 0;
+    for (Op& op : net->ops) {
+      if (!(op.is_fc && op.mfma)) continue;
+      const size_t in = (size_t)op.cs.C, outn = (size_t)op.cs.K;
+      if ((N * in * 2) % 16 || (N * outn * (op.out_f32 ? 4 : 2)) % 16 || R * std::max(in, outn) * 4 >= ((size_t)1 << 31)) continue;
+      op.stacked = true;
+      op.gx_off = g;
+      g += (R * in + 63) & ~(size_t)63;
+      max_in = std::max(max_in, in);
+      max_out = std::max(max_out, outn);
+    }
+    if (max_in > 0) {
+      net->g_y_off = g;  g += (2 * R * max_out + 63) & ~(size_t)63;     // room for fp32 class scores
+      net->g_dy_off = g; g += (R * max_out + 63) & ~(size_t)63;
+      net->g_dx_off = g; g += (R * max_in + 63) & ~(size_t)63;
+      net->g_scratch_off = (g * 2 + 255) & ~(size_t)255;
+      net->g_scratch_bytes = std::min((size_t)128 << 20, 8 * R * std::max(max_in, max_out) * 4);
+      net->g_bytes = net->g_scratch_off + net->g_scratch_bytes + 256;
+    }
+  }
   *out = net;
   *out_P = P;
   *out_pack_elems = net->pack_elems;
@@ -342,6 +376,11 @@ int net_create(const sasgd_config& cfg, Net** out, int64_t* out_P, size_t* out_p
 }
 
 void net_destroy(Net* net) { delete net; }
+size_t net_group_workspace_bytes(const Net* net) { return net->g_bytes; }
+hipError_t net_set_group_workspace(Net* net, void* ws, hipStream_t stream) {
+  net->group_ws = ws;
+  return hipMemsetAsync(ws, 0, net->g_bytes, stream);   // the kernels rely on its block of zeros
+}
 size_t net_workspace_bytes(const Net* net) { return net->ws_bytes; }
 hipError_t net_set_workspace(Net* net, int learner, void* ws, hipStream_t stream) {
   net->ws[learner] = ws;
@@ -415,6 +454,57 @@ hipError_t net_calc_gradient(Net* net, const int* learners, const LearnerBind* b
   }
   const bool bf = net->bf16;
   const std::vector<Tensor>& T = net->tensors;
+  // Learners that read the same weight version: the stacked fully connected layers take each such group (two members
+  // and more) as one matrix product; `single` lists the others.  Groups lie one after the other in the staging area.
+  struct Group { int first_row_block; std::vector<int> idx; };
+  std::vector<Group> groups;
+  std::vector<int> single;
+  if (net->group_ws && count > 1) {
+    std::vector<char> taken((size_t)count, 0);
+    int blocks = 0;
+    for (int a = 0; a < count; a++) {
+      if (taken[(size_t)a]) continue;
+      Group g;
+      g.first_row_block = blocks;
+      for (int b2 = a; b2 < count; b2++)
+        if (!taken[(size_t)b2] && wts.p[b2] == wts.p[a]) { g.idx.push_back(b2); taken[(size_t)b2] = 1; }
+      if (g.idx.size() >= 2) { blocks += (int)g.idx.size(); groups.push_back(g); }
+      else single.push_back(a);
+    }
+  }
+  PtrTab ws1, grads1;
+  CPtrTab wts1;
+  memset(&ws1, 0, sizeof(ws1)); memset(&grads1, 0, sizeof(grads1)); memset(&wts1, 0, sizeof(wts1));
+  for (size_t k = 0; k < single.size(); k++) {
+    ws1.p[k] = ws.p[single[k]]; grads1.p[k] = grads.p[single[k]]; wts1.p[k] = wts.p[single[k]];
+  }
+  const int count1 = (int)single.size();
+  // One stacked fully connected product of a group: rows from every member's workspace (element offset src_off, `width`
+  // values per image) are stacked at stage_in, the product runs on the staging area against the group's weights, and
+  // the result rows (out_width values of out_esz bytes per image, at stage_out) go back to dst_off of every member.
+  auto stacked_product = [&](const Group& G, IGemm g, Epilogue ep, bool bt, size_t src_off, size_t stage_in, int width, size_t dst_off,
+                             size_t stage_out, int out_width, int out_esz) -> hipError_t {
+    PtrTab mem, gws;
+    CPtrTab gwt;
+    memset(&mem, 0, sizeof(mem)); memset(&gws, 0, sizeof(gws)); memset(&gwt, 0, sizeof(gwt));
+    const int k = (int)G.idx.size();
+    for (int q = 0; q < k; q++) mem.p[q] = ws.p[G.idx[(size_t)q]];
+    gws.p[0] = net->group_ws;
+    gwt.p[0] = wts.p[G.idx[0]];
+    const size_t row0 = (size_t)G.first_row_block * net->mu;
+    if (stage_in != (size_t)-1)
+      TRY(launch_stack_rows(mem, k, src_off * 2, (char*)net->group_ws + (stage_in + row0 * width) * 2, (int64_t)net->mu * width * 2, true, stream));
+    g.M = net->mu * k;
+    g.zero_off = net->g_zero_off;
+    igemm_set_magics(g, 2);
+    const int bm = 128, bn = g.Ncols <= 32 ? 32 : (g.Ncols <= 64 ? 64 : 128);
+    const int64_t tiles = (int64_t)((g.M + bm - 1) / bm) * ((g.Ncols + bn - 1) / bn);
+    g.scratch_off = net->g_scratch_off;
+    g.splits = choose_splits(tiles, 1, (g.Kchunks + 3) / 4, (size_t)g.M * g.Ncols * 4, net->g_scratch_bytes);
+    ep.out_off = stage_out + row0 * out_width * (out_esz / 2);
+    TRY(launch_igemm(gws, gwt, g, ep, bt, 1, stream));
+    return launch_stack_rows(mem, k, dst_off * 2, (char*)net->group_ws + ep.out_off * 2, (int64_t)net->mu * out_width * out_esz, false, stream);
+  };
   // ---- forward
   TRY(launch_pack_input(bf, imgs, ws, T[0].off, count, net->mu, net->inpack, net->pixel_mean, stream));
   for (const Op& op : net->ops) {
@@ -426,6 +516,18 @@ hipError_t net_calc_gradient(Net* net, const int* learners, const LearnerBind* b
           IGemm gf = op.gf;
           set_splits_f32(net, gf, count);
           TRY(launch_igemm_f32(ws, wts, gf, op.vc, ep, op.w_off, false, count, stream));
+        } else if (op.mfma && op.stacked && !groups.empty()) {
+          Epilogue ep{yo, 0, op.b_off, 1, op.relu ? 1 : 0, 0, op.out_f32 ? 1 : 0};
+          if (count1 > 0) {
+            IGemm gf = op.gf;
+            set_splits(net, gf, (gf.Kchunks + 3) / 4, count1);
+            TRY(launch_igemm(ws1, wts1, gf, ep, false, count1, stream));
+          }
+          for (const Group& G : groups) {
+            IGemm gf = op.gf;
+            gf.a_off = op.gx_off + (size_t)G.first_row_block * net->mu * op.cs.C;
+            TRY(stacked_product(G, gf, ep, false, xi, op.gx_off, op.cs.C, yo, net->g_y_off, op.cs.K, op.out_f32 ? 4 : 2));
+          }
         } else if (op.mfma) {
           Epilogue ep{yo, 0, op.b_off, 1, op.relu ? 1 : 0, 0, op.out_f32 ? 1 : 0};
           IGemm gf = op.gf;
@@ -453,6 +555,31 @@ hipError_t net_calc_gradient(Net* net, const int* learners, const LearnerBind* b
     return launch_label_rank(bf, net->scores_f32, ws, labs, T[(size_t)net->ops.back().out_t].off, net->mu, net->classes, out_rank_dev,
                              count, stream);
   // ---- backward
+  // input gradient of a fully connected layer on the MFMA path: per learner, or stacked per group of one weight version
+  auto fc_dgrad = [&](const Op& op, const Tensor& tin, size_t dy_off, size_t dx_off) -> hipError_t {
+    Epilogue ep{dx_off, tin.off, 0, 0, 0, tin.relu ? 1 : 0, 0};
+    if (!(op.stacked && !groups.empty())) {
+      IGemm gd = op.gd;
+      gd.a_off = dy_off;
+      set_splits(net, gd, (gd.Kchunks + 3) / 4, count);
+      return launch_igemm(ws, wts, gd, ep, op.dgrad_bt, count, stream);
+    }
+    if (count1 > 0) {
+      IGemm gd = op.gd;
+      gd.a_off = dy_off;
+      set_splits(net, gd, (gd.Kchunks + 3) / 4, count1);
+      TRY(launch_igemm(ws1, wts1, gd, ep, op.dgrad_bt, count1, stream));
+    }
+    for (const Group& G : groups) {
+      const size_t row0 = (size_t)G.first_row_block * net->mu;
+      IGemm gd = op.gd;
+      gd.a_off = net->g_dy_off + row0 * op.cs.K;
+      Epilogue eg = ep;
+      eg.mask_off = op.gx_off + row0 * op.cs.C;      // the layer's stacked input, kept from the forward pass
+      TRY(stacked_product(G, gd, eg, op.dgrad_bt, dy_off, net->g_dy_off, op.cs.K, dx_off, net->g_dx_off, op.cs.C, 2));
+    }
+    return hipSuccess;
+  };
   for (int k = (int)net->ops.size() - 1; k >= 0; k--) {
     const Op& op = net->ops[(size_t)k];
     const Tensor& tin = T[(size_t)op.in_t];
@@ -476,13 +603,7 @@ hipError_t net_calc_gradient(Net* net, const int* learners, const LearnerBind* b
           }
         } else if (op.mfma && op.factored) {
           TRY(launch_fc_save_factors(ws, grads, tin.off, dy, op.fx_off, op.fdy_off, op.b_off, op.cs.N, op.cs.C, op.cs.K, op.NP, count, stream));
-          if (need_dx) {
-            IGemm gd = op.gd;
-            gd.a_off = dy;
-            set_splits(net, gd, (gd.Kchunks + 3) / 4, count);
-            Epilogue ep{dx, tin.off, 0, 0, 0, tin.relu ? 1 : 0, 0};
-            TRY(launch_igemm(ws, wts, gd, ep, op.dgrad_bt, count, stream));
-          }
+          if (need_dx) TRY(fc_dgrad(op, tin, dy, dx));
         } else if (op.mfma) {
           IGemm gw = op.gf;
           {
@@ -496,7 +617,9 @@ hipError_t net_calc_gradient(Net* net, const int* learners, const LearnerBind* b
             gw.splits = choose_splits(tiles, count, (gw.M + 31) / 32, (size_t)gw.Ncols * (gw.Kchunks * 8 + 8) * 4, net->scratch_bytes, target);
           }
           TRY(launch_igemm_wgrad(ws, grads, gw, op.vc, dy, op.w_off, op.b_off, count, stream));
-          if (need_dx) {
+          if (need_dx && op.is_fc) {
+            TRY(fc_dgrad(op, tin, dy, dx));
+          } else if (need_dx) {
             IGemm gd = op.gd;
             gd.a_off = dy;
             set_splits(net, gd, (gd.Kchunks + 3) / 4, count);
