@@ -166,6 +166,35 @@ def cpu_baseline_net(cfg, budget_s=10.0):
                       "is not included" % (n, mu)}
 
 
+def activation_bytes_per_image(net, elem):
+    """Bytes of activations a layer-by-layer (unfused) forward + backward pass has to move per image: forward every layer
+    reads its input and writes its output; backward it reads its output gradient and its input (weight gradient, masks
+    and pooling winners) and writes its input gradient.  elem = bytes per stored activation; the input image is fp32."""
+    c, h, w = net["input"]
+    total = c * h * w * 4
+    for L in net["layers"]:
+        i_el = c * h * w
+        if L[0] == "conv":
+            _, co, k, st, pd = L
+            h = (h + 2 * pd - k) // st + 1
+            w = (w + 2 * pd - k) // st + 1
+            c = co
+        elif L[0] in ("maxpool", "avgpool"):
+            _, k, st = L
+            ho = -(-(h - k) // st) + 1
+            wo = -(-(w - k) // st) + 1
+            h = ho - 1 if (ho - 1) * st >= h else ho
+            w = wo - 1 if (wo - 1) * st >= w else wo
+        elif L[0] == "fc":
+            c, h, w = L[1], 1, 1
+        elif L[0] == "relu":
+            continue                      # fused into the layer in front of it
+        o_el = c * h * w
+        total += (i_el + o_el) * elem     # forward
+        total += (2 * o_el + 2 * i_el) * elem   # backward
+    return total
+
+
 def bench_net(args, cfg_id, prewarm=0, cold=False):
     """Whole hot path on BASELINE config 3 (CIFAR-shaped, bf16, 1-softsync) or 4 (AlexNet-shaped, bf16, 18-softsync):
     one step = one server update = c calcGradients (batched launches) + sumGradients + applyUpdate.
@@ -212,15 +241,33 @@ def bench_net(args, cfg_id, prewarm=0, cold=False):
         driver.run_softsync_batched(tmp, sched, batch_of, lam)
         torch.cuda.synchronize()
         tmp.destroy()
+    if args.calibrate_copy:
+        # plain device-to-device copies of known size (240 MB read + 240 MB written): the reference the rocprofv3
+        # FETCH_SIZE / WRITE_SIZE counters of the update kernels are scaled by
+        src = torch.zeros(60_000_000, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     ctx = make_ctx()
     # learners whose weights already exist are computed in one batched call (same versions, same staleness)
     driver.run_softsync_batched(ctx, sched[:warm], batch_of, lam)
     torch.cuda.synchronize()
-    ctx.setProfiling(True)
+    # the timed steps, as a caller runs them ...
     t0 = time.perf_counter()
-    _, calls = driver.run_softsync_batched(ctx, sched[warm:], batch_of, lam, first_update=warm)
+    _, calls = driver.run_softsync_batched(ctx, sched[warm:warm + steps], batch_of, lam, first_update=warm)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
+    # ... and the same steps again on a second context brought to the same point, with the phase timer on (HIP events
+    # around each phase on the library's stream) for the roofline figures
+    ctx.destroy()
+    ctx = make_ctx()
+    driver.run_softsync_batched(ctx, sched[:warm], batch_of, lam)
+    torch.cuda.synchronize()
+    ctx.setProfiling(True)
+    driver.run_softsync_batched(ctx, sched[warm:], batch_of, lam, first_update=warm)
+    torch.cuda.synchronize()
     ms_g, n_g = ctx.phaseTime(0)
     ms_u, n_u = ctx.phaseTime(1)
     _, n_pass = ctx.phaseTime(2)   # passes over the vector: consecutive updates are applied in one pass (fused steps)
@@ -266,6 +313,14 @@ def bench_net(args, cfg_id, prewarm=0, cold=False):
                          "lone_update_equivalent_GBs": round(upd_bytes / (upd_us * 1e-6) / 1e9, 1), "factored_fc_weights": Wf},
         "phase_ms_per_step": {"calcGradient": round(ms_g / steps, 4), "applyUpdate": round(ms_u / steps, 4)},
     }
+    if cfg_id == 3:
+        # the small-channel CIFAR-shaped layers are bound by moving activations, not by the matrix cores: report the
+        # calcGradient phase against the HBM peak as well (bytes of a layer-by-layer pass, see activation_bytes_per_image)
+        act = activation_bytes_per_image(net, 2) * images
+        out["roofline_activations"] = {"bound": "hbm", "kernel": "calcGradient phase, activation traffic of a layer-by-layer pass",
+                                       "achieved": round(act / t_grad / 1e9, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                                       "frac": round(act / t_grad / 1e9 / HBM_PEAK_GBS, 4), "traffic": None,
+                                       "bytes_per_image": activation_bytes_per_image(net, 2)}
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline_net(cfg)
     return out
