@@ -412,7 +412,7 @@ def bench_all(args):
     sub.steps, sub.warmup = 5, 2
     out["calc_only"] = nested(bench_calc(sub, 4))
     gc.collect(); torch.cuda.empty_cache()
-    sub.steps, sub.warmup, sub.calibrate_copy = 5, 2, False
+    sub.steps, sub.warmup, sub.calibrate_copy = 10, 3, False
     out["server_config1"] = nested(bench_server(sub))
     return out
 
