@@ -36,6 +36,11 @@ HBM_PEAK_GBS = 8000.0
 TRAFFIC_C1 = 1.2000e9
 TRAFFIC_C54 = 14.402e9      # the two-pass form writes and re-reads its sums: + 2 x 240 MB
 TRAFFIC_SOURCE = "rocprofv3 --pmc FETCH_SIZE/WRITE_SIZE, profiles/apply_update_config1.txt (not measured by this run)"
+# Counted / algorithmic HBM bytes of an update pass of BASELINE config 4 (fused steps, factored fully connected layers),
+# from the same two counters over `--workload alex` (summary: profiles/apply_update_config4_fused.txt).
+TRAFFIC_RATIO_CFG4 = 1.011
+TRAFFIC_SOURCE_CFG4 = ("bytes_per_launch x 1.011 = counted / algorithmic bytes of rocprofv3 --pmc FETCH_SIZE/WRITE_SIZE runs, "
+                       "profiles/apply_update_config4_fused.txt (not measured by this run)")
 PREWARM_CFG4 = 36           # updates that fill the ring of BASELINE config 4 before anything is timed
 
 
@@ -307,7 +312,9 @@ def bench_net(args, cfg_id, prewarm=0, cold=False):
                                                    "are ready together (%.2f per pass on average); bytes = theta, v read and v%s written once per "
                                                    "pass + per update its weight version and its gradients" % (k_pass, "" if fp32 else ", theta"),
                          "achieved": round(pass_bytes / (pass_us * 1e-6) / 1e9, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                         "frac": round(pass_bytes / (pass_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4), "traffic": None,
+                         "frac": round(pass_bytes / (pass_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
+                         "traffic": int(pass_bytes * TRAFFIC_RATIO_CFG4) if cfg_id == 4 else None,
+                         "traffic_source": TRAFFIC_SOURCE_CFG4 if cfg_id == 4 else None,
                          "avg_launch_us": round(pass_us, 2), "bytes_per_launch": int(pass_bytes), "updates_per_pass": round(k_pass, 3),
                          "per_update_us": round(upd_us, 2), "lone_update_bytes": upd_bytes,
                          "lone_update_equivalent_GBs": round(upd_bytes / (upd_us * 1e-6) / 1e9, 1), "factored_fc_weights": Wf},
