@@ -169,6 +169,25 @@ hipError_t launch_softmax_ce(bool is_bf16, bool z_f32, const PtrTab& ws, const C
                              size_t loss_byte_off, int N, int K, float* loss_out, int count, hipStream_t s);
 hipError_t launch_label_rank(bool is_bf16, bool z_f32, const PtrTab& ws, const CPtrTab& labels, size_t z_off, int N, int K,
                              int32_t* rank_out, int count, hipStream_t s);
+// ---- fully connected layers grouped by weight version (fc_group.hip)
+// Group k = members first[k] .. first[k] + members[k] - 1 of the pointer tables handed to the launch (learners that read
+// one weight version, listed next to each other); at most kMaxGroupMembers members and 128 image rows per group.
+constexpr int kMaxGroupMembers = 8;
+struct GroupTab {
+  uint8_t first[kMaxLearners];
+  uint8_t members[kMaxLearners];
+};
+// A layer of `in` inputs and `out` units on mini-batches of mu images that the grouped kernels take.
+bool fc_group_layer_ok(int mu, int in, int out);
+// y = x W^T + b (optional ReLU, optional fp32 output) for every group; g = the layer's forward GEMM of ONE learner
+// (M = mu).  scratch_off / scratch_bytes: the split-partial area of a workspace (the first member's is used).
+hipError_t launch_fc_group_fwd(const PtrTab& ws, const CPtrTab& wts, const GroupTab& gt, int groups, const IGemm& g, const Epilogue& ep,
+                               size_t scratch_off, size_t scratch_bytes, hipStream_t s);
+// dx = dy W (optionally zeroed where the forward tensor at ep.mask_off is <= 0); g = the layer's input-gradient GEMM of
+// one learner with a_off = offset of dy.
+hipError_t launch_fc_group_dgrad(const PtrTab& ws, const CPtrTab& wts, const GroupTab& gt, int groups, const IGemm& g, const Epilogue& ep,
+                                 size_t scratch_off, size_t scratch_bytes, hipStream_t s);
+
 // Copies [bytes_per_member] between every member's workspace (at member_off_bytes) and consecutive pieces of `stage`.
 hipError_t launch_stack_rows(const PtrTab& members, int count, size_t member_off_bytes, void* stage, int64_t bytes_per_member,
                              bool to_stage, hipStream_t s);

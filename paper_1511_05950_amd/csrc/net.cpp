@@ -41,6 +41,9 @@ struct Op {
   // element offset of the stacked layer input in the group staging area
   bool stacked = false;
   size_t gx_off = 0;
+  // fully connected layer on the grouped kernels (small mini-batches): learners of one weight version share every read
+  // of its weights without any copy; takes precedence over `stacked`
+  bool grouped = false;
 };
 
 struct Tensor {
@@ -237,6 +240,7 @@ int net_create(const sasgd_config& cfg, Net** out, int64_t* out_P, size_t* out_p
         op.vc = VConv{in, 1, L.units, 1, in, 1};
         op.gf = IGemm{0, op.w_off, N, L.units, 1, 1, in, 1, 1, 1, 0, in / chunk, in / chunk, in};
         op.gd = IGemm{0, op.w_off, N, in, 1, 1, L.units, 1, 1, 1, 0, L.units / chunk, L.units / chunk, in};
+        op.grouped = net->bf16 && fc_group_layer_ok(N, in, L.units);
         // rank-N weight gradient kept as factors: worth it while the N FMAs per weight and pending gradient stay far
         // below what the update's streaming rate leaves room for
         const int c_upd = cfg.lambda / cfg.n;
@@ -351,7 +355,7 @@ int net_create(const sasgd_config& cfg, Net** out, int64_t* out_P, size_t* out_p
     size_t g = 256, max_in = 0, max_out = 0;
     net->g_zero_off = 0;
     for (Op& op : net->ops) {
-      if (!(op.is_fc && op.mfma)) continue;
+      if (!(op.is_fc && op.mfma) || op.grouped) continue;
       const size_t in = (size_t)op.cs.C, outn = (size_t)op.cs.K;
       if ((N * in * 2) % 16 || (N * outn * (op.out_f32 ? 4 : 2)) % 16 || R * std::max(in, outn) * 4 >= ((size_t)1 << 31)) continue;
       op.stacked = true;
@@ -472,6 +476,39 @@ hipError_t net_calc_gradient(Net* net, const int* learners, const LearnerBind* b
       else single.push_back(a);
     }
   }
+  // The grouped fully connected kernels take every learner of the call, those of one weight version next to each
+  // other: `wsG` / `wtsG` list the learners in that order, `gtab` cuts the list into groups of at most 128 image rows.
+  PtrTab wsG;
+  CPtrTab wtsG;
+  GroupTab gtab;
+  int ngroups = 0;
+  bool any_grouped = false;
+  for (const Op& op : net->ops) any_grouped = any_grouped || op.grouped;
+  if (any_grouped) {
+    memset(&wsG, 0, sizeof(wsG)); memset(&wtsG, 0, sizeof(wtsG)); memset(&gtab, 0, sizeof(gtab));
+    const int cap = std::max(1, std::min(kMaxGroupMembers, 128 / net->mu));
+    std::vector<char> taken((size_t)count, 0);
+    int pos = 0;
+    for (int a = 0; a < count; a++) {
+      if (taken[(size_t)a]) continue;
+      int in_group = 0;
+      for (int b2 = a; b2 < count; b2++) {
+        if (taken[(size_t)b2] || wts.p[b2] != wts.p[a]) continue;
+        taken[(size_t)b2] = 1;
+        if (in_group == 0 || in_group == cap) {
+          gtab.first[ngroups] = (uint8_t)pos;
+          gtab.members[ngroups] = 0;
+          ngroups++;
+          in_group = 0;
+        }
+        wsG.p[pos] = ws.p[b2];
+        wtsG.p[pos] = wts.p[b2];
+        gtab.members[ngroups - 1]++;
+        in_group++;
+        pos++;
+      }
+    }
+  }
   PtrTab ws1, grads1;
   CPtrTab wts1;
   memset(&ws1, 0, sizeof(ws1)); memset(&grads1, 0, sizeof(grads1)); memset(&wts1, 0, sizeof(wts1));
@@ -516,6 +553,9 @@ hipError_t net_calc_gradient(Net* net, const int* learners, const LearnerBind* b
           IGemm gf = op.gf;
           set_splits_f32(net, gf, count);
           TRY(launch_igemm_f32(ws, wts, gf, op.vc, ep, op.w_off, false, count, stream));
+        } else if (op.mfma && op.grouped) {
+          Epilogue ep{yo, 0, op.b_off, 1, op.relu ? 1 : 0, 0, op.out_f32 ? 1 : 0};
+          TRY(launch_fc_group_fwd(wsG, wtsG, gtab, ngroups, op.gf, ep, net->scratch_off, net->scratch_bytes, stream));
         } else if (op.mfma && op.stacked && !groups.empty()) {
           Epilogue ep{yo, 0, op.b_off, 1, op.relu ? 1 : 0, 0, op.out_f32 ? 1 : 0};
           if (count1 > 0) {
@@ -558,6 +598,11 @@ hipError_t net_calc_gradient(Net* net, const int* learners, const LearnerBind* b
   // input gradient of a fully connected layer on the MFMA path: per learner, or stacked per group of one weight version
   auto fc_dgrad = [&](const Op& op, const Tensor& tin, size_t dy_off, size_t dx_off) -> hipError_t {
     Epilogue ep{dx_off, tin.off, 0, 0, 0, tin.relu ? 1 : 0, 0};
+    if (op.grouped) {
+      IGemm gd = op.gd;
+      gd.a_off = dy_off;
+      return launch_fc_group_dgrad(wsG, wtsG, gtab, ngroups, gd, ep, net->scratch_off, net->scratch_bytes, stream);
+    }
     if (!(op.stacked && !groups.empty())) {
       IGemm gd = op.gd;
       gd.a_off = dy_off;

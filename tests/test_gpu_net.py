@@ -369,16 +369,19 @@ def alex8_tolerances():
     return vs_reduced, vs_exact
 
 
-def alex_learners(net, netarg, w0, X, Y, versions=1, lam=1, push_seed=0):
-    """calcGradient of `lam` learners in ONE call at mu = len(X) / lam, learner L on weight version L * versions // lam.
-    Versions 1, 2, ... are made from w0 by server updates with seeded random gradients.  Returns the gradients, the
-    losses and, per learner, the weights it read (as the library holds them)."""
+def learners_on_versions(net, netarg, w0, X, Y, ver_of, push_seed=0, mu=None):
+    """calcGradient of len(ver_of) learners in ONE call, learner k on weight version ver_of[k].  Versions 1, 2, ... are
+    made from w0 by server updates with seeded random gradients.  Returns the gradients, the losses and, per learner,
+    the weights it read (as the library holds them)."""
     from paper_1511_05950_amd import binding
-    mu = X.shape[0] // lam
+    lam = len(ver_of)
+    mu = X.shape[0] // lam if mu is None else mu
+    versions = max(ver_of) + 1
     ctx = binding.Sasgd(max(lam, 2), mu, max(lam, 2), versions, net=netarg, compute="bf16", alpha0=0.5, init_weights=w0)
     rng = np.random.default_rng(push_seed)
+    scale = 0.2 * float(np.sqrt(np.mean(np.asarray(w0, dtype=np.float64) ** 2)))
     for _ in range(versions - 1):
-        push = torch.from_numpy((rng.standard_normal(ctx.P) * 0.004).astype(np.float32)).cuda()
+        push = torch.from_numpy((rng.standard_normal(ctx.P) * scale).astype(np.float32)).cuda()
         ctx.pushGradientExternal(push, ctx.timestamp())
         ctx.sumGradients()
         ctx.applyUpdate()
@@ -387,17 +390,19 @@ def alex_learners(net, netarg, w0, X, Y, versions=1, lam=1, push_seed=0):
     Xd, Yd = torch.from_numpy(X).cuda(), torch.from_numpy(Y).cuda()
     loss = torch.zeros(lam, device="cuda")
     ids = list(range(lam)) if lam > 1 else [1]
-    ver = []
     for k, L in enumerate(ids):
         ctx.getMinibatch(L, Xd[k * mu:(k + 1) * mu], Yd[k * mu:(k + 1) * mu])
-        j = k * versions // lam
-        assert ctx.pullWeights(L, ctx.timestamp() - j) == j
-        ver.append(j)
+        assert ctx.pullWeights(L, ctx.timestamp() - ver_of[k]) == ver_of[k]
     ctx.calcGradient(ids, loss)
     grads = [ctx.copyGradient(L) for L in ids]
-    weights = {j: ctx.copyWeights(j) for j in sorted(set(ver))}
+    weights = {j: ctx.copyWeights(j) for j in sorted(set(ver_of))}
     ctx.destroy()
-    return grads, [float(v) for v in loss.cpu()], [weights[j] for j in ver]
+    return grads, [float(v) for v in loss.cpu()], [weights[j] for j in ver_of]
+
+
+def alex_learners(net, netarg, w0, X, Y, versions=1, lam=1, push_seed=0):
+    """`lam` learners in one call at mu = len(X) / lam, learner L on weight version L * versions // lam."""
+    return learners_on_versions(net, netarg, w0, X, Y, [k * versions // lam for k in range(lam)], push_seed)
 
 
 def test_alex8_shapes_smooth_variant_full_size():
@@ -751,6 +756,40 @@ def test_learners_on_different_weight_versions_in_one_call():
         worst, errs = layer_errors(net, g, rg)
         assert worst < TOL["bf16"], (L, errs)
     ctx.destroy()
+
+
+GROUP_NETS = {
+    # fully connected layers the grouped kernels take (inputs a multiple of 256): 1 024 -> 256 -> 24 (a ragged block of
+    # units, a contraction of three chunks in the input gradient) and 1 024 -> 512 -> 8
+    "fc_256_24": wl.tiny_net(3, 9, 9, 24, conv=((64, 3, 1, 1),), pool="maxpool", fc_hidden=256),
+    "fc_512_8": wl.tiny_net(3, 9, 9, 8, conv=((64, 3, 1, 1),), pool="avgpool", fc_hidden=512),
+}
+
+
+@pytest.mark.parametrize("mu,ver_of", [
+    (16, [0, 1, 2, 2]),                          # a pair shares 32 rows: one row block
+    (16, [1, 0, 1, 2, 1]),                       # three learners of one version, not next to each other: two row blocks
+    (16, [0] * 9 + [1] * 3 + [2]),               # nine on one version: a full group of eight (four row blocks) and a rest
+    (4, [0] * 11 + [1, 1]),                      # mu = 4: eight members make 32 rows
+    (32, [0, 0, 0, 0, 0, 1]),                    # mu = 32: four members fill 128 rows, the fifth is a group of its own
+    (5, [0, 1, 0, 0]),                           # rows per member not a multiple of four
+])
+@pytest.mark.parametrize("name", sorted(GROUP_NETS))
+def test_fully_connected_layers_grouped_by_weight_version(name, mu, ver_of):
+    """Learners of one batched call that read the same weight version share the reads of the fully connected weights
+    (one launch per layer and direction, rows addressed through each member's workspace).  Every learner's gradient
+    and loss against the oracle on the weights that learner read."""
+    net = GROUP_NETS[name]
+    lam = len(ver_of)
+    rng = np.random.default_rng(770 + lam)
+    w0 = (rng.standard_normal(wl.num_params(net)) * 0.05).astype(np.float32)
+    X, Y = wl.images(net, lam * mu, 771), wl.labels(net, lam * mu, 772)
+    grads, losses, weights = learners_on_versions(net, net, w0, X, Y, ver_of, push_seed=773, mu=mu)
+    if max(ver_of) > 0:
+        assert rel(weights[ver_of.index(1)], weights[ver_of.index(0)]) > 1e-2
+    for L in range(lam):
+        rl, rg = cnn.loss_and_gradient(net, weights[L], X[L * mu:(L + 1) * mu], Y[L * mu:(L + 1) * mu], round_bf16=True)
+        check_gradient(net, "bf16", grads[L], rg, losses[L], rl, "learner %d of %s" % (L, ver_of))
 
 
 def test_patch_kernel_tiles_spanning_many_small_images():
