@@ -181,32 +181,33 @@ hipError_t enqueue_updates(sasgd_ctx* ctx, int n) {
     }
     return launch_apply_updates_fused(r, sr, final_theta ? final_theta + begin : nullptr, ctx->stream);
   };
+  // every stretch of the flat vector between the factored layers, then all factored layers in one launch
   int64_t cursor = 0;
   for (int k = 0; k < nfl && e == hipSuccess; k++) {
-    const FactoredLayer& F = fl[k];
-    e = flat_range(cursor, F.w_off);
-    if (e != hipSuccess) break;
+    e = flat_range(cursor, fl[k].w_off);
+    cursor = fl[k].w_off + (int64_t)fl[k].out * fl[k].in + fl[k].out;
+  }
+  if (nfl > 0 && e == hipSuccess) {
     FcUpdateLaunch fu;
-    fu.theta_in = u.theta_in + F.w_off;
-    fu.theta_out = u.theta_out + F.w_off;
-    fu.v = u.v + F.w_off;
-    fu.shadow_out = u.shadow_out ? u.shadow_out + F.w_off : nullptr;
-    fu.in = F.in; fu.out = F.out; fu.N = F.N; fu.NP = F.NP;
+    fu.theta_in = u.theta_in;
+    fu.theta_out = u.theta_out;
+    fu.v = u.v;
+    fu.shadow_out = u.shadow_out;
+    fu.N = fl[0].N; fu.NP = fl[0].NP;
+    fu.layers = nfl;
+    for (int k = 0; k < nfl; k++) {
+      fu.in[k] = fl[k].in; fu.out[k] = fl[k].out; fu.w_off[k] = fl[k].w_off;
+      fu.fx_off[k] = fl[k].fx_off; fu.fdy_off[k] = fl[k].fdy_off;
+    }
     fu.c = total;
     for (int l = 0; l < total; l++) {
-      const Pending& pd = *src[l];
-      fu.grads[l] = pd.grad + F.w_off;
+      fu.grads[l] = src[l]->grad;
       fu.coef[l] = u.coef[l];
-      fu.fx[l] = pd.factors_ws ? (const bf16_t*)pd.factors_ws + F.fx_off : nullptr;
-      fu.fdyT[l] = pd.factors_ws ? (const bf16_t*)pd.factors_ws + F.fdy_off : nullptr;
+      fu.factors[l] = (const bf16_t*)src[l]->factors_ws;
     }
     fu.momentum = u.momentum;
     fu.decay = u.decay;
-    StepTable sr = st;
-    for (int t = 0; t < n; t++)
-      if (sr.shadow_out[t]) sr.shadow_out[t] += F.w_off;
-    e = launch_apply_update_fc(fu, ctx->stream, &sr);
-    cursor = F.w_off + (int64_t)F.out * F.in + F.out;
+    e = launch_apply_update_fc(fu, ctx->stream, &st);
   }
   if (e == hipSuccess) e = flat_range(cursor, ctx->P);
   prof_end(ctx);

@@ -871,7 +871,7 @@ __global__ __launch_bounds__(64 * (BM / WM) * (BN / WN), (WM * WN > 64 * 64 ? 2 
   bf16x8 a0[TM];
   auto step = [&](bf16x8 (&bcur)[2][TN], bf16x8 (&bld)[2][TN], bool ld, bool has_next) {
     if (ld) load_b(bld, n_boff + b_tap);
-    bf16x8 a1[TM], a0n[TM];
+    bf16x8 a1[TM];
 #pragma unroll
     for (int i = 0; i < TM; i++) a1[i] = lds_a(i, c_aoff, 1);
     __builtin_amdgcn_sched_barrier(0);
@@ -881,9 +881,10 @@ __global__ __launch_bounds__(64 * (BM / WM) * (BN / WN), (WM * WN > 64 * 64 ? 2 
 #pragma unroll
       for (int j = 0; j < TN; j++) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0[i], bcur[0][j], acc[i][j], 0, 0, 0);
     __builtin_amdgcn_s_setprio(0);
-    if (has_next) {
+    __builtin_amdgcn_sched_barrier(0);
+    if (has_next) {                              // straight into a0: its last readers have been issued
 #pragma unroll
-      for (int i = 0; i < TM; i++) a0n[i] = lds_a(i, n_aoff, 0);
+      for (int i = 0; i < TM; i++) a0[i] = lds_a(i, n_aoff, 0);
     }
     __builtin_amdgcn_s_setprio(1);
 #pragma unroll
@@ -891,10 +892,6 @@ __global__ __launch_bounds__(64 * (BM / WM) * (BN / WN), (WM * WN > 64 * 64 ? 2 
 #pragma unroll
       for (int j = 0; j < TN; j++) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1[i], bcur[1][j], acc[i][j], 0, 0, 0);
     __builtin_amdgcn_s_setprio(0);
-    if (has_next) {
-#pragma unroll
-      for (int i = 0; i < TM; i++) a0[i] = a0n[i];
-    }
     advance();
   };
 

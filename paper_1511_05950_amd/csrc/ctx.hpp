@@ -52,24 +52,29 @@ hipError_t launch_apply_updates_fused(const UpdateLaunch& u, const StepTable& st
 // Device address, on the current device, of the library's statically allocated buffer of kSumStretch floats (looked up
 // once per device; no allocation).  Every caller on a device shares it: launches that use it must not overlap.
 hipError_t static_sum_buffer(float** out);
-// Update of one fully connected layer (weights [out][in] followed by the bias [out]) whose gradients are kept as
-// factors.  All pointers address the first weight of the layer.
+// Update of the fully connected layers (each: weights [out][in] followed by the bias [out]) whose gradients are kept as
+// factors, all layers in ONE launch.  theta_in / theta_out / v / shadow_out / grads address element 0 of the flat vector.
+constexpr int kMaxFactoredLayers = 16;   // further fully connected layers write their gradient out
 struct FcUpdateLaunch {
   const float* theta_in;
   float* theta_out;
   float* v;
   bf16_t* shadow_out;      // optional
-  int in, out, N, NP;      // N images per mini-batch, dyT rows padded to NP
+  int N, NP;               // N images per mini-batch, factor rows padded to NP
+  int layers;
+  int in[kMaxFactoredLayers], out[kMaxFactoredLayers];
+  int64_t w_off[kMaxFactoredLayers];                     // first weight of the layer in the flat vector
+  size_t fx_off[kMaxFactoredLayers], fdy_off[kMaxFactoredLayers];   // the layer's factors, bf16 elements from factors[l]
   int32_t c;
   const float* grads[kMaxLearners];     // written-out gradient of every pending gradient (bias part always used)
-  const bf16_t* fx[kMaxLearners];       // factor x transposed [in][NP], or nullptr: use the written-out weights gradient
-  const bf16_t* fdyT[kMaxLearners];     // factor dy transposed [out][NP]
+  const bf16_t* factors[kMaxLearners];  // base of the pending gradient's factors (x transposed [in][NP] at fx_off, dy
+                                        // transposed [out][NP] at fdy_off), or nullptr: use the written-out weights gradient
   float coef[kMaxLearners];
   float momentum;
   float decay;
 };
 // st == nullptr: one step (u.shadow_out, u.decay).  Otherwise fused steps: st's first / decay / shadow_out are used (its
-// theta_out is ignored: the layer's weights are written once, to u.theta_out).
+// theta_out is ignored: the weights are written once, to u.theta_out).
 hipError_t launch_apply_update_fc(const FcUpdateLaunch& u, hipStream_t stream, const StepTable* st = nullptr);
 hipError_t launch_fp32_to_bf16(const float* src, bf16_t* dst, int64_t n, hipStream_t stream);
 hipError_t launch_bf16_to_fp32(const bf16_t* src, float* dst, int64_t n, hipStream_t stream);
@@ -103,7 +108,6 @@ hipError_t net_calc_gradient(Net* net, const int* learners, const LearnerBind* b
                              float* out_loss_dev, int32_t* out_rank_dev, hipStream_t stream);
 // Fully connected layers whose weight gradient calcGradient leaves as factors in the learner's workspace
 // (bf16 element offsets from the workspace base): weights at w_off [out][in], bias right behind them.
-constexpr int kMaxFactoredLayers = 16;   // further fully connected layers write their gradient out
 struct FactoredLayer {
   int64_t w_off;
   int in, out, N, NP;

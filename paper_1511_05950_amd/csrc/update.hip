@@ -423,8 +423,16 @@ hipError_t launch_apply_updates_fused(const UpdateLaunch& u, const StepTable& st
 // arrival order, then the update of apply_update_kernel.  The layer's bias follows its weights in the flat vector and is
 // updated by one extra row of workgroups from the written-out bias gradients.
 struct FcFactors {
-  const bf16_t* xT[kMaxLearners];    // [in][NP] or nullptr: gradient l is a written-out vector
-  const bf16_t* dyT[kMaxLearners];   // [out][NP]
+  const bf16_t* base[kMaxLearners];  // the pending gradient's factors, or nullptr: gradient l is a written-out vector
+};
+// The layers of one launch: workgroups tile0[k] .. tile0[k + 1] - 1 belong to layer k, cols[k] of them per block of 32
+// output units (plus one such row for the bias).
+struct FcLayerTab {
+  int count;
+  int in[kMaxFactoredLayers], out[kMaxFactoredLayers], cols[kMaxFactoredLayers];
+  int tile0[kMaxFactoredLayers + 1];
+  int64_t w_off[kMaxFactoredLayers];
+  int64_t fx_off[kMaxFactoredLayers], fdy_off[kMaxFactoredLayers];
 };
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
@@ -438,19 +446,26 @@ constexpr int kFcNQ = kFcTileRows / kFcRPI;           // 16-byte pieces per lane
 constexpr int kFcLds = kFcTileCols + 4;               // LDS row stride in floats
 
 template <bool SHADOW>
-__global__ __launch_bounds__(256) void apply_update_fc_kernel(const float* theta_in, float* theta_out, float* v, int in, int out, int N,
-                                                              int NP, GradTable t, FcFactors f, StepTable st, float m) {
+__global__ __launch_bounds__(256) void apply_update_fc_kernel(const float* theta_in, float* theta_out, float* v, int NP, GradTable t,
+                                                              FcFactors f, FcLayerTab lt, StepTable st, float m) {
   __shared__ __attribute__((aligned(16))) float lds[4 * kFcTileRows * kFcLds];
+  int layer = 0;
+  for (int k = 1; k < lt.count; k++) layer = (int)blockIdx.x >= lt.tile0[k] ? k : layer;
+  const int local = (int)blockIdx.x - lt.tile0[layer];
+  const int bx = local % lt.cols[layer], by = local / lt.cols[layer];
+  const int in = lt.in[layer], out = lt.out[layer];
+  const int64_t woff = lt.w_off[layer];
+  theta_in += woff; theta_out += woff; v += woff;
   const int nrb = (out + kFcTileRows - 1) / kFcTileRows;
-  if ((int)blockIdx.y == nrb) {       // bias: elements out * in + col .. col + 3
-    const int col = (blockIdx.x * 256 + threadIdx.x) * 4;
+  if (by == nrb) {       // bias: elements out * in + col .. col + 3
+    const int col = (bx * 256 + threadIdx.x) * 4;
     if (col >= out) return;
     const int64_t e = (int64_t)out * in + col;
     float4 a = *reinterpret_cast<const float4*>(theta_in + e), b = *reinterpret_cast<const float4*>(v + e);
     for (int step = 0; step < st.steps; step++) {
       float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
       for (int l = st.first[step]; l < st.first[step + 1]; l++) {
-        const float4 g = *reinterpret_cast<const float4*>(t.g[l] + e);
+        const float4 g = *reinterpret_cast<const float4*>(t.g[l] + woff + e);
         s.x = fmaf(t.coef[l], g.x, s.x); s.y = fmaf(t.coef[l], g.y, s.y);
         s.z = fmaf(t.coef[l], g.z, s.z); s.w = fmaf(t.coef[l], g.w, s.w);
       }
@@ -462,7 +477,7 @@ __global__ __launch_bounds__(256) void apply_update_fc_kernel(const float* theta
         uint2 o;
         o.x = (uint32_t)f2bf(a.x) | ((uint32_t)f2bf(a.y) << 16);
         o.y = (uint32_t)f2bf(a.z) | ((uint32_t)f2bf(a.w) << 16);
-        *reinterpret_cast<uint2*>(st.shadow_out[step] + e) = o;
+        *reinterpret_cast<uint2*>(st.shadow_out[step] + woff + e) = o;
       }
     }
     *reinterpret_cast<float4*>(v + e) = b;
@@ -470,8 +485,8 @@ __global__ __launch_bounds__(256) void apply_update_fc_kernel(const float* theta
     return;
   }
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int o0 = blockIdx.y * kFcTileRows;
-  const int w0 = (blockIdx.x * 4 + wave) * kFcTileCols;
+  const int o0 = by * kFcTileRows;
+  const int w0 = (bx * 4 + wave) * kFcTileCols;
   if (w0 >= in) return;               // whole wavefronts leave: no workgroup barrier below
   float* tile = lds + wave * (kFcTileRows * kFcLds);
   // row-major registers: piece q is row kFcRPI q + lane / kFcLPR, columns 4 (lane % kFcLPR) .. + 3 of the tile
@@ -496,7 +511,9 @@ __global__ __launch_bounds__(256) void apply_update_fc_kernel(const float* theta
     for (int q = 0; q < kFcNQ; q++) s[q] = make_float4(0.f, 0.f, 0.f, 0.f);
     for (int l = st.first[step]; l < st.first[step + 1]; l++) {
       const float cf = t.coef[l];
-      if (f.xT[l]) {
+      if (f.base[l]) {
+        const bf16_t* xT = f.base[l] + lt.fx_off[layer];
+        const bf16_t* dyT = f.base[l] + lt.fdy_off[layer];
         floatx16_t p[kFcCB];
 #pragma unroll
         for (int b = 0; b < kFcCB; b++)
@@ -506,11 +523,11 @@ __global__ __launch_bounds__(256) void apply_update_fc_kernel(const float* theta
           const int n0 = 16 * kb + 8 * h;
           union { uint4 u; bf16x8_t x; } fa, fb[kFcCB];
           fa.u = make_uint4(0u, 0u, 0u, 0u);
-          if (n0 < NP && o0 + j < out) fa.u = *reinterpret_cast<const uint4*>(f.dyT[l] + (int64_t)(o0 + j) * NP + n0);
+          if (n0 < NP && o0 + j < out) fa.u = *reinterpret_cast<const uint4*>(dyT + (int64_t)(o0 + j) * NP + n0);
 #pragma unroll
           for (int b = 0; b < kFcCB; b++) {
             fb[b].u = make_uint4(0u, 0u, 0u, 0u);
-            if (n0 < NP && w0 + 32 * b + j < in) fb[b].u = *reinterpret_cast<const uint4*>(f.xT[l] + (int64_t)(w0 + 32 * b + j) * NP + n0);
+            if (n0 < NP && w0 + 32 * b + j < in) fb[b].u = *reinterpret_cast<const uint4*>(xT + (int64_t)(w0 + 32 * b + j) * NP + n0);
           }
 #pragma unroll
           for (int b = 0; b < kFcCB; b++) p[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa.x, fb[b].x, p[b], 0, 0, 0);
@@ -535,7 +552,7 @@ __global__ __launch_bounds__(256) void apply_update_fc_kernel(const float* theta
         for (int q = 0; q < kFcNQ; q++) {
           const int o = o0 + kFcRPI * q + rr;
           if (o < out && col_ok) {
-            const float4 g = ldg_nt(reinterpret_cast<const float4*>(t.g[l] + (int64_t)o * in + w0 + cc));
+            const float4 g = ldg_nt(reinterpret_cast<const float4*>(t.g[l] + woff + (int64_t)o * in + w0 + cc));
             s[q].x = fmaf(cf, g.x, s[q].x); s[q].y = fmaf(cf, g.y, s[q].y);
             s[q].z = fmaf(cf, g.z, s[q].z); s[q].w = fmaf(cf, g.w, s[q].w);
           }
@@ -557,7 +574,7 @@ __global__ __launch_bounds__(256) void apply_update_fc_kernel(const float* theta
         uint2 w2;
         w2.x = (uint32_t)f2bf(a.x) | ((uint32_t)f2bf(a.y) << 16);
         w2.y = (uint32_t)f2bf(a.z) | ((uint32_t)f2bf(a.w) << 16);
-        *reinterpret_cast<uint2*>(st.shadow_out[step] + (int64_t)o * in + w0 + cc) = w2;
+        *reinterpret_cast<uint2*>(st.shadow_out[step] + woff + (int64_t)o * in + w0 + cc) = w2;
       }
     }
   }
@@ -572,15 +589,33 @@ __global__ __launch_bounds__(256) void apply_update_fc_kernel(const float* theta
 }
 
 hipError_t launch_apply_update_fc(const FcUpdateLaunch& u, hipStream_t stream, const StepTable* steps) {
-  if (u.in < 4 || u.out < 4 || (u.in & 3) || (u.out & 3) || u.c < 1 || u.c > kMaxLearners) return hipErrorInvalidValue;
+  if (u.layers < 1 || u.layers > kMaxFactoredLayers || u.c < 1 || u.c > kMaxLearners) return hipErrorInvalidValue;
+  if (u.NP < 8 || u.NP > 32 || (u.NP & 7)) return hipErrorInvalidValue;
   GradTable t;
   FcFactors f;
   for (int l = 0; l < kMaxLearners; l++) {
     t.g[l] = l < u.c ? u.grads[l] : nullptr;
     t.coef[l] = l < u.c ? u.coef[l] : 0.f;
-    f.xT[l] = l < u.c ? u.fx[l] : nullptr;
-    f.dyT[l] = l < u.c ? u.fdyT[l] : nullptr;
+    f.base[l] = l < u.c ? u.factors[l] : nullptr;
   }
+  FcLayerTab lt;
+  memset(&lt, 0, sizeof(lt));
+  lt.count = u.layers;
+  int64_t tiles = 0;
+  for (int k = 0; k < u.layers; k++) {
+    if (u.in[k] < 4 || u.out[k] < 4 || (u.in[k] & 3) || (u.out[k] & 3)) return hipErrorInvalidValue;
+    lt.in[k] = u.in[k];
+    lt.out[k] = u.out[k];
+    lt.w_off[k] = u.w_off[k];
+    lt.fx_off[k] = (int64_t)u.fx_off[k];
+    lt.fdy_off[k] = (int64_t)u.fdy_off[k];
+    // 4 kFcTileCols input units per workgroup (four wavefronts side by side), or 1024 bias elements in the extra row
+    lt.cols[k] = std::max((u.in[k] + 4 * kFcTileCols - 1) / (4 * kFcTileCols), (u.out[k] + 1023) / 1024);
+    lt.tile0[k] = (int)tiles;
+    tiles += (int64_t)lt.cols[k] * ((u.out[k] + kFcTileRows - 1) / kFcTileRows + 1);
+    if (tiles > 0x7fffffff) return hipErrorInvalidValue;
+  }
+  lt.tile0[u.layers] = (int)tiles;
   StepTable st;
   if (steps) {
     st = *steps;
@@ -595,16 +630,11 @@ hipError_t launch_apply_update_fc(const FcUpdateLaunch& u, hipStream_t stream, c
   bool shadow = st.shadow_out[0] != nullptr;
   for (int k = 0; k < st.steps; k++)
     if ((st.shadow_out[k] != nullptr) != shadow) return hipErrorInvalidValue;
-  if (u.NP < 8 || u.NP > 32 || (u.NP & 7)) return hipErrorInvalidValue;
-  // x: 4 kFcTileCols input units per workgroup (four wavefronts side by side), or 1024 bias elements in the extra row
-  const int cols = std::max((u.in + 4 * kFcTileCols - 1) / (4 * kFcTileCols), (u.out + 1023) / 1024);
-  dim3 grid((unsigned)cols, (unsigned)((u.out + kFcTileRows - 1) / kFcTileRows + 1));
+  const dim3 grid((unsigned)tiles);
   if (shadow)
-    hipLaunchKernelGGL((apply_update_fc_kernel<true>), grid, dim3(256), 0, stream, u.theta_in, u.theta_out, u.v, u.in, u.out, u.N, u.NP, t, f,
-                       st, u.momentum);
+    hipLaunchKernelGGL((apply_update_fc_kernel<true>), grid, dim3(256), 0, stream, u.theta_in, u.theta_out, u.v, u.NP, t, f, lt, st, u.momentum);
   else
-    hipLaunchKernelGGL((apply_update_fc_kernel<false>), grid, dim3(256), 0, stream, u.theta_in, u.theta_out, u.v, u.in, u.out, u.N, u.NP, t, f,
-                       st, u.momentum);
+    hipLaunchKernelGGL((apply_update_fc_kernel<false>), grid, dim3(256), 0, stream, u.theta_in, u.theta_out, u.v, u.NP, t, f, lt, st, u.momentum);
   return hipGetLastError();
 }
 
