@@ -3,8 +3,9 @@
 // Under n-softsync several learners of one batched call often read the same weight version (Section 2.2: a learner
 // pulls whatever version is current when it starts).  With mu <= 32 images per learner a fully connected layer uses
 // every weight once per image row block, so the layer runs at the rate its weights stream in from HBM; reading them
-// once per VERSION instead of once per learner is what grouping buys.  A group = up to 8 learners (at most 128 image
-// rows) on one version; a learner alone is a group of one.  All groups of a call run in one launch (blockIdx.z =
+// once per VERSION instead of once per learner is what grouping buys.  A group = learners of a call on one version, at
+// most 128 image rows (more learners on a version are cut into several equal groups, whose reads of the same weights at
+// the same time meet in the last-level cache); a learner alone is a group of one.  All groups of a call run in one launch (blockIdx.z =
 // group x split): nothing is copied together, a row's address is looked up through its member's workspace pointer.
 //
 //   forward   y[m][n]  = sum_k x[m][k] W[n][k] + b[n]        W rows are contraction-major: streamed as they lie
@@ -390,7 +391,7 @@ static bool group_table_ok(const GroupTab& gt, int groups, int mu, int* max_rows
   int mr = 0;
   for (int k = 0; k < groups; k++) {
     const int nm = gt.members[k];
-    if (nm < 1 || nm > kMaxGroupMembers || nm * mu > 128 || gt.first[k] + nm > kMaxLearners) return false;
+    if (nm < 1 || nm * mu > kMaxGroupRows || gt.first[k] + nm > kMaxLearners) return false;
     mr = std::max(mr, nm * mu);
   }
   *max_rows = mr;

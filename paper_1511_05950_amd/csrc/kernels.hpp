@@ -171,8 +171,8 @@ hipError_t launch_label_rank(bool is_bf16, bool z_f32, const PtrTab& ws, const C
                              int32_t* rank_out, int count, hipStream_t s);
 // ---- fully connected layers grouped by weight version (fc_group.hip)
 // Group k = members first[k] .. first[k] + members[k] - 1 of the pointer tables handed to the launch (learners that read
-// one weight version, listed next to each other); at most kMaxGroupMembers members and 128 image rows per group.
-constexpr int kMaxGroupMembers = 8;
+// one weight version, listed next to each other); at most kMaxGroupRows image rows per group.
+constexpr int kMaxGroupRows = 128;
 struct GroupTab {
   uint8_t first[kMaxLearners];
   uint8_t members[kMaxLearners];

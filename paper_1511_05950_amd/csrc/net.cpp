@@ -477,7 +477,11 @@ hipError_t net_calc_gradient(Net* net, const int* learners, const LearnerBind* b
     }
   }
   // The grouped fully connected kernels take every learner of the call, those of one weight version next to each
-  // other: `wsG` / `wtsG` list the learners in that order, `gtab` cuts the list into groups of at most 128 image rows.
+  // other: `wsG` / `wtsG` list the learners in that order, `gtab` cuts the list into groups of at most 128 image rows;
+  // the learners of a version that has more are dealt out evenly (18 learners of 16 images: three groups of six).
+  // (Measured against that: kernels that take up to 512 rows in one group, the row blocks dealt out to the wavefronts --
+  // every 32-unit workgroup then walks an input tensor larger than an L2, and the fully connected launches of 18 learners
+  // on one version took 438 us against 369 us.)
   PtrTab wsG;
   CPtrTab wtsG;
   GroupTab gtab;
@@ -486,26 +490,24 @@ hipError_t net_calc_gradient(Net* net, const int* learners, const LearnerBind* b
   for (const Op& op : net->ops) any_grouped = any_grouped || op.grouped;
   if (any_grouped) {
     memset(&wsG, 0, sizeof(wsG)); memset(&wtsG, 0, sizeof(wtsG)); memset(&gtab, 0, sizeof(gtab));
-    const int cap = std::max(1, std::min(kMaxGroupMembers, 128 / net->mu));
+    const int cap = std::max(1, kMaxGroupRows / net->mu);
     std::vector<char> taken((size_t)count, 0);
     int pos = 0;
     for (int a = 0; a < count; a++) {
       if (taken[(size_t)a]) continue;
-      int in_group = 0;
-      for (int b2 = a; b2 < count; b2++) {
-        if (taken[(size_t)b2] || wts.p[b2] != wts.p[a]) continue;
-        taken[(size_t)b2] = 1;
-        if (in_group == 0 || in_group == cap) {
-          gtab.first[ngroups] = (uint8_t)pos;
-          gtab.members[ngroups] = 0;
-          ngroups++;
-          in_group = 0;
+      std::vector<int> same;
+      for (int b2 = a; b2 < count; b2++)
+        if (!taken[(size_t)b2] && wts.p[b2] == wts.p[a]) { same.push_back(b2); taken[(size_t)b2] = 1; }
+      const int n = (int)same.size(), chunks = (n + cap - 1) / cap;
+      for (int ch = 0, at = 0; ch < chunks; ch++) {
+        const int len = (n - at + (chunks - ch) - 1) / (chunks - ch);     // the remaining learners, evenly
+        gtab.first[ngroups] = (uint8_t)pos;
+        gtab.members[ngroups] = (uint8_t)len;
+        ngroups++;
+        for (int k = 0; k < len; k++, at++, pos++) {
+          wsG.p[pos] = ws.p[same[(size_t)at]];
+          wtsG.p[pos] = wts.p[same[(size_t)at]];
         }
-        wsG.p[pos] = ws.p[b2];
-        wtsG.p[pos] = wts.p[b2];
-        gtab.members[ngroups - 1]++;
-        in_group++;
-        pos++;
       }
     }
   }

@@ -760,18 +760,25 @@ def test_learners_on_different_weight_versions_in_one_call():
 
 GROUP_NETS = {
     # fully connected layers the grouped kernels take (inputs a multiple of 256): 1 024 -> 256 -> 24 (a ragged block of
-    # units, a contraction of three chunks in the input gradient) and 1 024 -> 512 -> 8
+    # units, a contraction of three chunks in the input gradient) behind a ReLU and a max pool
     "fc_256_24": wl.tiny_net(3, 9, 9, 24, conv=((64, 3, 1, 1),), pool="maxpool", fc_hidden=256),
-    "fc_512_8": wl.tiny_net(3, 9, 9, 8, conv=((64, 3, 1, 1),), pool="avgpool", fc_hidden=512),
+    # the same shape family without a ReLU or a max pool (decision-free): checked element by element as well
+    "fc_512_8_smooth": {"name": "tiny", "input": (3, 9, 9), "classes": 8,
+                        "layers": [("conv", 64, 3, 1, 1), ("avgpool", 3, 2), ("fc", 512), ("fc", 8)]},
 }
 
 
 @pytest.mark.parametrize("mu,ver_of", [
     (16, [0, 1, 2, 2]),                          # a pair shares 32 rows: one row block
     (16, [1, 0, 1, 2, 1]),                       # three learners of one version, not next to each other: two row blocks
-    (16, [0] * 9 + [1] * 3 + [2]),               # nine on one version: a full group of eight (four row blocks) and a rest
-    (4, [0] * 11 + [1, 1]),                      # mu = 4: eight members make 32 rows
-    (32, [0, 0, 0, 0, 0, 1]),                    # mu = 32: four members fill 128 rows, the fifth is a group of its own
+    (16, [0] * 8 + [1] * 3 + [2]),               # eight on one version: 128 rows, four row blocks per wavefront
+    (16, [0] * 9 + [1] * 3 + [2]),               # nine on one version: groups of five and four
+    (16, [0] * 18),                              # hardsync-like: three groups of six
+    (16, [0] * 20 + [1, 1, 2]),                  # groups of seven, seven and six beside small ones
+    (16, [1] * 32 + [0] * 2),                    # four full groups of eight
+    (8, [0] * 64),                               # 64 learners on one version: four groups of sixteen 8-image members
+    (4, [0] * 11 + [1, 1]),                      # mu = 4: eleven members make 44 rows
+    (32, [0, 0, 0, 0, 0, 1]),                    # mu = 32: five members as groups of three and two
     (5, [0, 1, 0, 0]),                           # rows per member not a multiple of four
 ])
 @pytest.mark.parametrize("name", sorted(GROUP_NETS))
@@ -780,6 +787,7 @@ def test_fully_connected_layers_grouped_by_weight_version(name, mu, ver_of):
     (one launch per layer and direction, rows addressed through each member's workspace).  Every learner's gradient
     and loss against the oracle on the weights that learner read."""
     net = GROUP_NETS[name]
+    smooth = not any(L[0] in ("relu", "maxpool") for L in net["layers"])
     lam = len(ver_of)
     rng = np.random.default_rng(770 + lam)
     w0 = (rng.standard_normal(wl.num_params(net)) * 0.05).astype(np.float32)
@@ -788,8 +796,21 @@ def test_fully_connected_layers_grouped_by_weight_version(name, mu, ver_of):
     if max(ver_of) > 0:
         assert rel(weights[ver_of.index(1)], weights[ver_of.index(0)]) > 1e-2
     for L in range(lam):
-        rl, rg = cnn.loss_and_gradient(net, weights[L], X[L * mu:(L + 1) * mu], Y[L * mu:(L + 1) * mu], round_bf16=True)
-        check_gradient(net, "bf16", grads[L], rg, losses[L], rl, "learner %d of %s" % (L, ver_of))
+        xs, ys = X[L * mu:(L + 1) * mu], Y[L * mu:(L + 1) * mu]
+        rl, rg = cnn.loss_and_gradient(net, weights[L], xs, ys, round_bf16=True)
+        # per tensor 2e-2, or 1.5 x the distance between the oracle's own two evaluations of this learner's gradient
+        # (reduced-precision and exact) where that is larger: a mini-batch whose ReLU signs sit on bf16 rounding
+        # boundaries moves every tensor by a few per cent whichever way the sums are ordered
+        _, eg = cnn.loss_and_gradient(net, weights[L], xs, ys)
+        _, spread = layer_errors(net, rg, eg)
+        _, errs = layer_errors(net, grads[L], rg)
+        assert all(e < max(TOL["bf16"], SPREAD_FACTOR * sp) for e, sp in zip(errs, spread)), (L, ver_of, errs, spread)
+        if smooth:
+            # (with ReLUs a one-ulp difference in a bf16 activation flips hidden units whose input lies within 1e-5 of
+            # its terms' magnitude -- every mini-batch here has some -- and a flipped unit moves its whole row of dW)
+            ew, at = elem_error(net, grads[L], rg)
+            assert ew < ELEM_TOL["bf16"], (L, ver_of, "element", at, ew)
+        assert abs(losses[L] - rl) < 2e-2 * max(1.0, abs(rl))
 
 
 def test_patch_kernel_tiles_spanning_many_small_images():
