@@ -1220,130 +1220,6 @@ __global__ __launch_bounds__(256) void igemm_finish_kernel(PtrTab ws, CPtrTab wt
   }
 }
 
-// ------------------------------------------------------------------ fully connected forward for one small mini-batch
-// y[m][n] = sum_k x[m][k] W[n][k] with at most 32 rows m: every weight is used once, so the layer runs at the rate the
-// weights stream in, and that rate grows with the length of the contiguous pieces requested.  A workgroup owns 32
-// output units and walks the contraction in steps of 256: 32 lanes fetch 512 contiguous bytes of one weight row
-// (the generic tile kernel fetches 64).  The tile goes through LDS; each of the four wavefronts multiplies one
-// quarter of the step (64 k) into its own 32 x 32 accumulator, and the four are added at the end.
-constexpr int FCK = 256;                 // contraction elements per step
-constexpr int FCLD = FCK + 8;            // LDS row stride (elements): 528 bytes, conflict-free 16-byte reads
-__global__ __launch_bounds__(256) void fc_rows_kernel(PtrTab ws, CPtrTab wts, IGemm g, Epilogue ep) {
-  __shared__ __attribute__((aligned(16))) bf16_t lds[2 * 32 * FCLD];
-  const int z = blockIdx.z / g.splits, sp = blockIdx.z % g.splits;
-  const bf16_t* x = (const bf16_t*)ws.p[z] + g.a_off;
-  const bf16_t* W = (const bf16_t*)wts.p[z] + g.b_off;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int n0 = blockIdx.x * 32;
-  const __amdgpu_buffer_rsrc_t rsrc_w = __builtin_amdgcn_make_buffer_rsrc((void*)W, 0, (int)((int64_t)g.Ncols * g.ldb * 2), 0x00020000);
-  const __amdgpu_buffer_rsrc_t rsrc_x = __builtin_amdgcn_make_buffer_rsrc((void*)x, 0, (int)((int64_t)g.M * g.C * 2), 0x00020000);
-  // loader: pass i fetches rows 8 i + tid / 32, 16 bytes at element 8 (tid % 32) of the step
-  const int lrow = tid >> 5, lpiece = tid & 31;
-  uint32_t woff[4];
-#pragma unroll
-  for (int i = 0; i < 4; i++) {
-    const int n = n0 + 8 * i + lrow;
-    woff[i] = n < g.Ncols ? (uint32_t)(((int64_t)n * g.ldb + 8 * lpiece) * 2) : kOutOfRange;
-  }
-  // x fragments of this wavefront's quarter: lane (m, h) holds x[m][step + 64 wave + 16 j + 8 h ...]
-  const int m = lane & 31, h = lane >> 5;
-  const uint32_t xoff = m < g.M ? (uint32_t)(((int64_t)m * g.C + 64 * wave + 8 * h) * 2) : kOutOfRange;
-
-  const int steps_all = g.C / FCK;
-  const int per = (steps_all + g.splits - 1) / g.splits;
-  const int s_begin = __builtin_amdgcn_readfirstlane(sp * per);
-  const int s_end = __builtin_amdgcn_readfirstlane(min(steps_all, s_begin + per));
-
-  v4i_t rw[4], rx[4];
-  auto fetch = [&](int st) {
-#pragma unroll
-    for (int i = 0; i < 4; i++) rw[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_w, (int)woff[i], st * (FCK * 2), 0);
-#pragma unroll
-    for (int j = 0; j < 4; j++) rx[j] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_x, (int)(xoff + 32 * j), st * (FCK * 2), 0);
-  };
-  auto stash = [&](int buf) {
-#pragma unroll
-    for (int i = 0; i < 4; i++) *reinterpret_cast<v4i_t*>(lds + buf * (32 * FCLD) + (8 * i + lrow) * FCLD + 8 * lpiece) = rw[i];
-  };
-  floatx16 acc;
-#pragma unroll
-  for (int e = 0; e < 16; e++) acc[e] = 0.f;
-
-  bf16x8 xb[4];
-  auto keep_x = [&]() {
-#pragma unroll
-    for (int j = 0; j < 4; j++) { union { v4i_t u; bf16x8 v; } c; c.u = rx[j]; xb[j] = c.v; }
-  };
-  int st = s_begin;
-  if (st < s_end) {
-    fetch(st);
-    stash(0);
-    keep_x();
-    if (st + 1 < s_end) fetch(st + 1);
-  }
-  __syncthreads();
-  for (int buf = 0; st < s_end; st++, buf ^= 1) {
-    const bool has1 = st + 1 < s_end;
-    if (has1) stash(buf ^ 1);                   // the tile fetched during the previous step
-    bf16x8 xn[4];
-    if (has1) {
-#pragma unroll
-      for (int j = 0; j < 4; j++) { union { v4i_t u; bf16x8 v; } c; c.u = rx[j]; xn[j] = c.v; }
-    }
-    if (st + 2 < s_end) fetch(st + 2);
-    const bf16_t* A = lds + buf * (32 * FCLD) + m * FCLD + 64 * wave + 8 * h;
-#pragma unroll
-    for (int j = 0; j < 4; j++) {
-      const bf16x8 a = *reinterpret_cast<const bf16x8*>(A + 16 * j);
-      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, xb[j], acc, 0, 0, 0);
-    }
-    if (has1) {
-#pragma unroll
-      for (int j = 0; j < 4; j++) xb[j] = xn[j];
-    }
-    __syncthreads();
-  }
-
-  // add the four wavefronts' accumulators: D[i][j], i = unit (MFMA row), j = image (lane & 31)
-  float* red = reinterpret_cast<float*>(lds);                   // [wave][16][64]: 16 KiB, the tiles are no longer needed
-#pragma unroll
-  for (int e = 0; e < 16; e++) red[(wave * 16 + e) * 64 + lane] = acc[e];
-  __syncthreads();
-  // thread (q = tid / 64, lane): the four consecutive units 8 q + 4 h .. + 3 of image m
-  const int q = wave;
-  float f[4];
-#pragma unroll
-  for (int e = 0; e < 4; e++) {
-    float v = 0.f;
-#pragma unroll
-    for (int w = 0; w < 4; w++) v += red[(w * 16 + 4 * q + e) * 64 + lane];
-    f[e] = v;
-  }
-  const int n = n0 + 8 * q + 4 * h;
-  if (m >= g.M || n >= g.Ncols) return;
-  if (g.splits > 1) {
-    float* part = reinterpret_cast<float*>((char*)ws.p[z] + g.scratch_off) + (int64_t)sp * g.M * g.Ncols + (int64_t)m * g.Ncols + n;
-    *reinterpret_cast<float4*>(part) = make_float4(f[0], f[1], f[2], f[3]);
-    return;
-  }
-  bf16_t* out = (bf16_t*)ws.p[z] + ep.out_off;
-  const bf16_t* bias = (const bf16_t*)wts.p[z] + ep.bias_off;
-#pragma unroll
-  for (int e = 0; e < 4; e++) {
-    if (ep.has_bias) f[e] += bf2f(bias[n + e]);
-    if (ep.relu) f[e] = fmaxf(f[e], 0.f);
-  }
-  const int64_t o = (int64_t)m * g.Ncols + n;
-  if (ep.out_f32) {
-    *reinterpret_cast<float4*>(reinterpret_cast<float*>(out) + o) = make_float4(f[0], f[1], f[2], f[3]);
-  } else {
-    uint2 w2;
-    w2.x = (uint32_t)f2bf(f[0]) | ((uint32_t)f2bf(f[1]) << 16);
-    w2.y = (uint32_t)f2bf(f[2]) | ((uint32_t)f2bf(f[3]) << 16);
-    *reinterpret_cast<uint2*>(out + o) = w2;
-  }
-}
-
 int choose_splits(int64_t tiles, int count, int steps, size_t bytes_per_split, size_t scratch_bytes, int64_t target) {
   // target = workgroups wanted per launch; 600 by default (256..1024 measured, flat between 400 and 768 at 6 and 18 learners)
   int64_t sp = (target + tiles * count - 1) / (tiles * count);
@@ -1526,22 +1402,6 @@ hipError_t launch_igemm(const PtrTab& ws, const CPtrTab& wts, const IGemm& g_in,
                         hipStream_t s) {
   const IGemm& g = g_in;
   if (g.C % 8 || g.ldb % 8 || (b_transposed && g.Ncols % 8) || g.splits < 1) return hipErrorInvalidValue;
-  if (!b_transposed && g.M <= 32 && g.ks == 1 && g.H == 1 && g.W == 1 && g.C % FCK == 0 && g.ldb == g.C && g.Ncols % 8 == 0 &&
-      (int64_t)g.Ncols * g.ldb * 2 < ((int64_t)1 << 31) && (int64_t)g.M * g.C * 2 < ((int64_t)1 << 31) && !ep.use_mask) {
-    // a fully connected layer on one learner's small mini-batch: the weight-streaming kernel (fc6 of the AlexNet shape,
-    // 18 learners with a weight version each: 257 us = 5.3 TB/s against 290 us with the generic tile kernel)
-    // the split was chosen for 128-unit tiles; with 32 units per workgroup fewer copies (often none) fill the chip
-    IGemm g = g_in;
-    const int64_t blocks = (int64_t)((g.Ncols + 31) / 32) * count;
-    g.splits = (int)std::max<int64_t>(1, std::min<int64_t>(g.splits, (1024 + blocks - 1) / blocks));
-    hipLaunchKernelGGL(fc_rows_kernel, dim3((unsigned)((g.Ncols + 31) / 32), 1, (unsigned)(count * g.splits)), dim3(256), 0, s, ws, wts, g, ep);
-    if (g.splits > 1) {
-      int64_t total = ((int64_t)g.M * g.Ncols) >> 2;
-      unsigned blocks = (unsigned)((total + 255) / 256 < 2048 ? (total + 255) / 256 : 2048);
-      hipLaunchKernelGGL(igemm_finish_kernel, dim3(blocks, 1, (unsigned)count), dim3(256), 0, s, ws, wts, g, ep);
-    }
-    return hipGetLastError();
-  }
   if (g.M <= 32) {
     // input gradient of a wide fully connected layer: 512-byte pieces of the weight rows (236 us against 252 us)
     if (b_transposed && g.Ncols >= 1024) launch_igemm_t<32, 256, 32, 64, true>(ws, wts, g, ep, count, s);
