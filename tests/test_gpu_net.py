@@ -780,6 +780,7 @@ GROUP_NETS = {
     (4, [0] * 11 + [1, 1]),                      # mu = 4: eleven members make 44 rows
     (32, [0, 0, 0, 0, 0, 1]),                    # mu = 32: five members as groups of three and two
     (5, [0, 1, 0, 0]),                           # rows per member not a multiple of four
+    (1, [0, 1, 0]),                              # single-image mini-batches: a group of two rows
 ])
 @pytest.mark.parametrize("name", sorted(GROUP_NETS))
 def test_fully_connected_layers_grouped_by_weight_version(name, mu, ver_of):
