@@ -1244,10 +1244,10 @@ template <int BM, int BN, int WM, int WN>
 static void launch_frag_t(const PtrTab& ws, const CPtrTab& wts, const IGemm& g_in, const Epilogue& ep, int count, hipStream_t s) {
   IGemm g = g_in;
   {
-    // a two-way split that the tiles nearly fill the chip without is not worth its second pass
+    // a split of up to six ways is not worth its second pass once the tiles alone take a fifth of the resident places
     const int64_t tiles = (int64_t)((g.M + BM - 1) / BM) * ((g.Ncols + BN - 1) / BN) * count;
     const int64_t places = 256 * (WM * WN > 64 * 64 ? 2 : 3);
-    if (g.splits == 2 && tiles * 10 >= places * 6) g.splits = 1;
+    if (g.splits <= 6 && tiles * 5 >= places) g.splits = 1;
   }
   dim3 grid((unsigned)((g.M + BM - 1) / BM), (unsigned)((g.Ncols + BN - 1) / BN), (unsigned)(count * g.splits));
   constexpr int NT = 64 * (BM / WM) * (BN / WN);
@@ -1270,11 +1270,14 @@ static bool launch_halo_t(const PtrTab& ws, const CPtrTab& wts, const IGemm& g_i
   IGemm g = g_in;
   g.splits = std::min(g.splits, g.C / 32);
   {
-    // a two-way split that the tiles nearly fill the chip without is not worth its second pass (conv5 forward of the
-    // AlexNet shape at 18 learners, 396 tiles on 512 places: 92 us unsplit against 104 + 25 us)
+    // A split of up to six ways is not worth its partials and second pass once the tiles alone take a fifth of the
+    // resident places (conv5 forward of the AlexNet shape at 18 learners, 396 tiles on 512 places: 92 us unsplit against
+    // 104 + 25 us; conv3 forward at 8 learners, 264 tiles: two-way split 60 + 18 us for the second pass; over a run of
+    // config 4 the calcGradient phase takes 0.230 ms per update with this rule against 0.237 ms when only two-way
+    // splits of tiles filling 60 % of the places were dropped, and 0.233 ms when nothing is split)
     const int64_t tiles = (int64_t)((g.M + BM - 1) / BM) * ((g.Ncols + BN - 1) / BN) * count;
     const int64_t places = 256 * (WM * WN > 64 * 64 ? 2 : 3);
-    if (g.splits == 2 && tiles * 10 >= places * 6) g.splits = 1;
+    if (g.splits <= 6 && tiles * 5 >= places) g.splits = 1;
   }
   HaloArgs h;
   h.PW = g.OW + g.ks - 1;
@@ -1316,7 +1319,7 @@ static bool launch_halo_seq_t(const PtrTab& ws, const CPtrTab& wts, const IGemm&
   {
     const int64_t tiles = (int64_t)((g.M + BM - 1) / BM) * ((g.Ncols + BN - 1) / BN) * count;
     const int64_t places = 256 * (WM * WN > 64 * 64 ? 2 : 3);
-    if (g.splits == 2 && tiles * 10 >= places * 6) g.splits = 1;
+    if (g.splits <= 6 && tiles * 5 >= places) g.splits = 1;
   }
   HaloSeqArgs h;
   h.PW = g.OW + g.ks - 1;
